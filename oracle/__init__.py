@@ -1,0 +1,25 @@
+"""CPU oracle for latent-KV attention (FDC, arXiv 2408.04107).
+
+TEST INFRASTRUCTURE ONLY. This package is a plain, slow, float64 / integer
+reference of what the GPU library computes. It exists so that tests, the smoke
+check and the benchmark's CPU-baseline leg can compare the HIP path against
+something written independently from the paper. The product path never imports
+it, and it imports nothing from the product package.
+
+Modules
+  factors    truncated-SVD factors W ~= A.B              (Section 2, low-rank KV paragraph)
+  attention  latent projection, query absorption, decode / causal-prefill
+             attention on latent K/V, output absorption  (Section 2; Section 5 overview, steps 4-7)
+  layout     ragged per-head cache offsets
+  planner    decode LPT list scheduling, prefill row-block rescaling and
+             last-round redistribution                   (Section 5.3)
+  rank_select  per-head compression rate from the singular-value removal rate (Eq. 1)
+
+Pin status: every function is pinned by the CPU tests (full-rank equals
+standard attention, exact-rank equals uncompressed attention, closed forms,
+brute force, scheduling invariants and the paper's worked scheduling example),
+except that the KV-chunk splitting of the decode planner and the causal-cost
+mode of the prefill planner extend the paper: those parts are pinned only by
+invariants (coverage, load sums, list-scheduling bounds), i.e. "parity
+unpinned" by the paper itself.
+"""

@@ -1,0 +1,262 @@
+"""Pins for the integer oracle: layout bijection, scheduling invariants, list-scheduling
+bounds against an exhaustive optimum, the paper's worked decode example, hand-worked
+prefill numbers, and Eq. (1) against closed-form geometric tails.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import layout as ol
+from oracle import planner as op
+from oracle import rank_select as ors
+from workloads import generators as gen
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ------------------------------------------------------------------ layout
+def test_layout_is_a_bijection_and_chunks_are_contiguous():
+    ranks = np.array([[16, 48, 32], [64, 16, 16]])
+    B, S = 2, 5
+    tb = ol.layout_tables(ranks, B, S)
+    for l in range(2):
+        seen = set()
+        for b in range(B):
+            for h in range(3):
+                prev = None
+                for t in range(S):
+                    for i in range(ranks[l, h]):
+                        e = ol.element_index(tb, ranks, S, l, b, h, t, i)
+                        assert e not in seen
+                        seen.add(e)
+                        if prev is not None:
+                            assert e == prev + 1      # a unit is one dense run: any [t0,t1) is a span
+                        prev = e
+        assert seen == set(range(int(tb["elems"][l])))
+        assert np.all(np.diff(tb["off"][l]) > 0)
+        assert tb["off_r"][l, -1] == ranks[l].sum()
+        assert tb["off"][l, -1] + S * ranks[l, -1] == S * ranks[l].sum()
+
+
+# ------------------------------------------------------------------ decode planner
+def _check_decode_invariants(plan, seq_len, rk, rv, W, split=True, G=64):
+    B, H = len(seq_len), len(rk)
+    n = len(plan["tile_b"])
+    d_sum = [int(rk[h] + rv[h] + 1) for h in range(H)]
+    # every token of every unit exactly once, tiles of a unit consecutive and ordered
+    utp = plan["unit_tile_ptr"]
+    assert utp[0] == 0 and utp[-1] == n
+    for b in range(B):
+        for h in range(H):
+            u = b * H + h
+            t = 0
+            for j in range(utp[u], utp[u + 1]):
+                assert (plan["tile_b"][j], plan["tile_h"][j]) == (b, h)
+                assert plan["tile_t0"][j] == t and plan["tile_t1"][j] > t
+                assert plan["tile_cost"][j] == (plan["tile_t1"][j] - t) * d_sum[h]
+                t = plan["tile_t1"][j]
+            assert t == seq_len[b]
+    # every tile on exactly one worker; loads add up
+    assert sorted(plan["worker_tiles"].tolist()) == list(range(n))
+    total = sum(int(seq_len[b]) * d_sum[h] for b in range(B) for h in range(H))
+    assert int(plan["worker_load"].sum()) == total
+    for w in range(W):
+        ids = plan["worker_tiles"][plan["worker_ptr"][w]:plan["worker_ptr"][w + 1]]
+        assert int(plan["tile_cost"][ids].sum()) == int(plan["worker_load"][w])
+        if not split:   # the paper's rule hands a worker its tasks in non-increasing cost order
+            assert np.all(np.diff(plan["tile_cost"][ids]) <= 0)
+    if n:
+        mx = int(plan["worker_load"].max())
+        big = int(plan["tile_cost"].max())
+        assert mx >= max(math.ceil(total / W), big)
+        assert mx <= total / W + big                     # list-scheduling bound
+        if split:                                        # capacity: mean load plus one granule
+            assert mx <= math.ceil(total / W) + G * max(d_sum)
+            assert mx <= total / W + big
+            # cuts fall on granule multiples; at most one extra tile per worker
+            assert np.all(plan["tile_t0"] % G == 0)
+
+
+def test_decode_paper_example_from_golden_file():
+    spec = {}
+    sets = {}
+    for line in open(os.path.join(GOLDEN, "decode_schedule_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        if k == "set":
+            sets[v[0]] = sorted(int(s[1:]) - 1 for s in v[1:])
+        else:
+            spec[k] = [int(x) for x in v]
+    costs = spec["costs_not_from_paper"]
+    W = spec["workers"][0]
+    assert len(costs) == spec["tasks"][0] and costs == sorted(costs, reverse=True)
+    lists, loads = op.lpt_assign(costs, W)
+    assert [sorted(x) for x in lists] == [sets["SM1"], sets["SM2"], sets["SM3"]]
+    # the same through the planner proper: one sequence of length 1 per task is not expressible
+    # (cost = s_kv * d_sum), so use seven sequences whose lengths are the costs and a single head
+    # whose d_sum is 33, with splitting switched off.
+    plan = op.plan_decode(costs, [16], [16], W, granule=64, min_split=1, split=False)
+    got = [sorted(plan["worker_tiles"][plan["worker_ptr"][w]:plan["worker_ptr"][w + 1]].tolist())
+           for w in range(W)]
+    assert got == [sets["SM1"], sets["SM2"], sets["SM3"]]
+    assert plan["worker_load"].tolist() == [13 * 33, 13 * 33, 12 * 33]
+
+
+def test_decode_no_split_is_one_task_per_head_sorted_descending():
+    seq = [700, 64, 1300]
+    rk, rv = [16, 128, 48], [32, 128, 16]
+    plan = op.plan_decode(seq, rk, rv, 4, split=False)
+    assert len(plan["tile_b"]) == 9 and np.all(np.diff(plan["unit_tile_ptr"]) == 1)
+    assert np.array_equal(plan["tile_cost"].reshape(3, 3),
+                          np.outer(seq, [49, 257, 65]))
+    _check_decode_invariants(plan, seq, rk, rv, 4, split=False)
+    # hand-worked: costs sorted 334100 179900 84500 63700 45500 34300 16448 4160 3136
+    # first four open workers 0..3; 45500 -> w3 (63700); 34300 -> w2 (84500); 16448 -> w3 (109200);
+    # 4160 -> w2 (118800); 3136 -> w2 (122960 < 125648)
+    assert plan["worker_load"].tolist() == [334100, 179900, 84500 + 34300 + 4160 + 3136, 63700 + 45500 + 16448]
+
+
+def test_lpt_tie_breaks():
+    lists, loads = op.lpt_assign([5, 5, 5, 5], 3)
+    assert lists == [[0, 3], [1], [2]] and loads == [10, 5, 5]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_lpt_against_exhaustive_optimum(seed):
+    g = gen.make_rng(100 + seed)
+    n, W = int(g.integers(4, 9)), int(g.integers(2, 4))
+    costs = [int(c) for c in g.integers(1, 40, size=n)]
+    _, loads = op.lpt_assign(costs, W)
+    best = min(max(sum(c for c, a in zip(costs, assign) if a == w) for w in range(W))
+               for assign in itertools.product(range(W), repeat=n))
+    assert best <= max(loads) <= (4 / 3 - 1 / (3 * W)) * best + 1e-9      # Graham's bound
+
+
+@pytest.mark.parametrize("name", ["c2_uniform_decode", "c3_adaptive_decode", "c4_long_decode"])
+def test_decode_plan_invariants_on_benchmark_shapes(name):
+    wl = gen.CONFIGS[name]
+    ranks = wl.ranks()[0]
+    seq = [wl.context] * wl.batch
+    W = 4096
+    plan = op.plan_decode(seq, ranks, ranks, W, granule=64, min_split=wl.min_split)
+    _check_decode_invariants(plan, seq, ranks, ranks, W)
+    per_unit = np.diff(plan["unit_tile_ptr"])
+    assert per_unit.min() >= wl.min_split
+    n_chunks = wl.batch * wl.n_heads * wl.min_split
+    assert len(plan["tile_b"]) <= n_chunks + W          # every cut fills one worker
+    # balance: the busiest worker is within 10 % of the mean on these shapes (one granule of 64
+    # tokens of the widest head is 8 % of a 193 KB share)
+    assert plan["worker_load"].max() <= 1.10 * plan["worker_load"].mean()
+
+
+def test_decode_plan_ragged_and_empty_sequences():
+    seq = [0, 1, 63, 64, 65, 1000, 0, 4097]
+    rk, rv = [16, 112, 64, 32], [48, 16, 64, 128]
+    for W, ms, split in [(7, 1, True), (64, 1, True), (5, 3, True), (5, 3, False), (3, 1, False)]:
+        plan = op.plan_decode(seq, rk, rv, W, granule=64, min_split=ms, split=split)
+        _check_decode_invariants(plan, seq, rk, rv, W, split=split)
+    empty = op.plan_decode([0, 0], rk, rv, 4)
+    assert len(empty["tile_b"]) == 0 and empty["worker_ptr"].tolist() == [0] * 5
+
+
+# ------------------------------------------------------------------ prefill planner
+def test_prefill_row_blocks_equalise_task_cost():
+    # B_r_i = B_r * d_sum_max / d_sum_i (Section 5.3), rounded up to 16 (Section 6.1)
+    rk = [16, 32, 64, 128, 48]
+    br = op.prefill_row_blocks(rk, rk, br_base=64, br_cap=1 << 20)
+    d_sum = [2 * r + 1 for r in rk]
+    assert br[3] == 64                                            # the widest head keeps B_r
+    assert br[0] == 512 and br[1] == 256 and br[2] == 128         # ceil(64*257/33)=499 -> 512, ...
+    for b, ds in zip(br, d_sum):
+        assert b % 16 == 0
+        assert 64 * 257 <= b * ds < 64 * 257 + 16 * ds            # equal cost up to one 16-row step
+    assert op.prefill_row_blocks(rk, rk, 64, 256)[0] == 256       # register cap
+
+
+def _check_prefill_cover(plan, q_len, H):
+    cover = {}
+    for b, h, q0, q1 in zip(plan["task_b"], plan["task_h"], plan["task_q0"], plan["task_q1"]):
+        assert q1 > q0
+        cover.setdefault((int(b), int(h)), []).append((int(q0), int(q1)))
+    for b in range(len(q_len)):
+        for h in range(H):
+            if q_len[b] == 0:
+                assert (b, h) not in cover
+                continue
+            t = 0
+            for q0, q1 in sorted(cover[(b, h)]):
+                assert q0 == t
+                t = q1
+            assert t == q_len[b]
+    n = len(plan["task_b"])
+    assert sorted(plan["worker_tasks"].tolist()) == list(range(n))
+    assert int(plan["worker_load"].sum()) == int(plan["task_cost"].sum())
+
+
+def test_prefill_last_round_hand_worked():
+    # Two heads, d_sum = 33 and 97; B_r = [192, 64]  (ceil(64*97/33) = 189 -> 192).
+    # One sequence of 256 tokens: head 0 -> rows [0,192), [192,256); head 1 -> four blocks of 64.
+    # Six tasks on W = 4 workers: one full round (tasks 0..3), last round = tasks 4, 5
+    # (head 1 rows [128,192) and [192,256)).  wl = ceil((64*97 + 64*97) / 4) = 3104;
+    # new row block = floor16(3104 / 97 = 32) = 32 -> four tasks of 32 rows, one per worker.
+    plan = op.plan_prefill([256], [256], [16, 48], [16, 48], 4, br_base=64, br_cap=256, cost_mode="paper")
+    assert plan["br"].tolist() == [192, 64]
+    tasks = list(zip(plan["task_h"].tolist(), plan["task_q0"].tolist(), plan["task_q1"].tolist()))
+    assert tasks == [(0, 0, 192), (0, 192, 256), (1, 0, 64), (1, 64, 128),
+                     (1, 128, 160), (1, 160, 192), (1, 192, 224), (1, 224, 256)]
+    assert plan["task_cost"].tolist() == [192 * 256 * 33, 64 * 256 * 33, 64 * 256 * 97, 64 * 256 * 97] + \
+        [32 * 256 * 97] * 4
+    lists = [plan["worker_tasks"][plan["worker_ptr"][w]:plan["worker_ptr"][w + 1]].tolist() for w in range(4)]
+    assert lists == [[0, 4], [1, 5], [2, 6], [3, 7]]
+    _check_prefill_cover(plan, [256], 2)
+
+
+@pytest.mark.parametrize("mode", ["paper", "causal"])
+def test_prefill_plan_cover_and_balance(mode):
+    wl = gen.CONFIGS["c5_prefill"]
+    ranks = wl.ranks()[0]
+    q = [wl.context] * wl.batch
+    plan = op.plan_prefill(q, q, ranks, ranks, 256, cost_mode=mode)
+    _check_prefill_cover(plan, q, wl.n_heads)
+    assert np.all(plan["task_q0"] % 16 == 0)
+    if mode == "causal":
+        # cost = d_sum * sum_{i in block} (i + 1); descending hand-out balances to within 2 %
+        j = 17
+        h, q0, q1 = plan["task_h"][j], plan["task_q0"][j], plan["task_q1"][j]
+        assert plan["task_cost"][j] == (2 * ranks[h] + 1) * (q1 * (q1 + 1) // 2 - q0 * (q0 + 1) // 2)
+        assert plan["worker_load"].max() <= 1.02 * plan["worker_load"].mean()
+
+
+def test_prefill_plan_ragged_lengths():
+    plan = op.plan_prefill([0, 5, 130, 17], [0, 9, 130, 4000], [16, 64, 32], [32, 64, 16], 6, cost_mode="paper")
+    _check_prefill_cover(plan, [0, 5, 130, 17], 3)
+    plan = op.plan_prefill([0, 5, 130, 17], [0, 9, 130, 4000], [16, 64, 32], [32, 64, 16], 6, cost_mode="causal")
+    _check_prefill_cover(plan, [0, 5, 130, 17], 3)
+
+
+# ------------------------------------------------------------------ Eq. (1)
+def test_rank_selection_geometric_closed_form():
+    # theta_i = e^{-i/c}: tail(j) = (e^{-j/c} - e^{-n/c}) / (1 - e^{-n/c}); invert by hand for each r
+    n, c = 128, 32.0
+    theta = np.exp(-np.arange(n) / c)
+    for r in (0.001, 0.01, 0.05, 0.2, 0.5, 0.9):
+        # largest j with tail(j) > r  <=>  e^{-j/c} > r (1 - e^{-n/c}) + e^{-n/c}
+        rhs = r * (1 - math.exp(-n / c)) + math.exp(-n / c)
+        j_closed = math.ceil(-c * math.log(rhs)) - 1
+        j = ors.last_kept_index(theta, r)
+        assert j == j_closed
+        tail = lambda k: theta[k:].sum() / theta.sum()
+        assert tail(j + 1) <= r < tail(j)                   # Eq. (1) itself
+        lo, hi = ors.compression_rate_interval(j, n)
+        for p in (hi, (lo + hi) / 2):
+            assert math.floor((1 - p) * (n - 1) + 1e-12) == j
+        assert ors.kept_rank(theta, r) == -(-(j + 1) // 16) * 16
+    assert ors.last_kept_index(theta, 0.0) == n - 1         # nothing may be removed
+    assert ors.last_kept_index(theta, 1.0) == 0             # keep one dimension at least
+    # flat spectrum: removing m of n dimensions removes m/n of the mass
+    flat = np.ones(10)
+    assert ors.last_kept_index(flat, 0.35) == 6             # dims 7,8,9 removed (0.3 <= 0.35 < 0.4)
