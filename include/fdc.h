@@ -1,0 +1,218 @@
+/*
+ * libfdc - attention computed directly on a low-rank ("latent") KV cache with a
+ * different kept rank per (layer, head), for AMD MI355X (gfx950).
+ *
+ * Method: FDC, "Fast KV Dimensionality Compression for Efficient LLM Inference"
+ * (arXiv 2408.04107). Per head the key/value projection weight is factorised
+ * W ~= A.B (Section 2); the cache stores the latent rows x.A, the query is
+ * moved into latent space (q.B_k^T), attention runs on the latent tensors
+ * without decompression (Section 5, steps 4-7) and the per-head work, which is
+ * uneven because the kept ranks differ, is balanced by a scheduler
+ * (Section 5.3).
+ *
+ * Conventions
+ *  - Every function returns fdc_status (0 = OK, negative = error) and never
+ *    throws or aborts. fdc_last_error() returns a thread-local description.
+ *  - "device" pointers are HIP device memory owned by the caller; "host"
+ *    pointers are ordinary host memory. The library never allocates or frees
+ *    device memory. Device work is enqueued on the caller's stream (a
+ *    hipStream_t passed as void*; NULL = the null stream) and the call returns
+ *    without synchronising.
+ *  - Kept ranks are multiples of 16 in [16, d_head] (Section 6.1,
+ *    implementation: widths rounded up to 16, zero padded); anything else is
+ *    FDC_UNSUPPORTED_RANK. Device pointers must be 16-byte aligned
+ *    (FDC_BAD_ALIGNMENT).
+ *  - dtype of a layout: FDC_BF16 = caches, activations and weights are bf16,
+ *    sums are fp32; FDC_F32 = everything fp32 (small validation shapes; the
+ *    prefill kernel does not support it).
+ *  - fdc_layout and fdc_plan are host objects, immutable after creation,
+ *    destroyed by the matching call.
+ */
+#ifndef FDC_H_
+#define FDC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FDC_OK = 0,
+  FDC_INVALID_ARG = -1,
+  FDC_BAD_SHAPE = -2,
+  FDC_BAD_ALIGNMENT = -3,
+  FDC_WORKSPACE_TOO_SMALL = -4,
+  FDC_UNSUPPORTED_RANK = -5,
+  FDC_HIP_ERROR = -6,
+  FDC_UNSUPPORTED_DTYPE = -7
+} fdc_status;
+
+typedef enum { FDC_BF16 = 0, FDC_F32 = 1 } fdc_dtype;
+
+typedef struct fdc_layout fdc_layout;
+typedef struct fdc_plan fdc_plan;
+
+/* Copies the calling thread's last error text into buf (NUL terminated, at most n bytes). */
+void fdc_last_error(char* buf, size_t n);
+
+/* ------------------------------------------------------------------------------------------
+ * Ragged latent-KV cache layout.
+ *
+ * The cache keeps, per layer and per head, the compressed K' (s x k) and V' instead of K and V
+ * (Section 2), with k chosen per head (Section 5.2). Per layer there are two device buffers, one
+ * for K' and one for V'. Unit (b, h) is a dense row-major block [max_seq, r[h]]; the blocks of
+ * a sequence are concatenated over heads and sequences over b:
+ *     elem(b, h, t, i) = b * max_seq * R + off[h] + t * r[h] + i
+ *     off[h] = max_seq * sum_{h' < h} r[h'],   R = sum_h r[h]
+ * so any token range of a unit is one contiguous span.
+ *
+ * rk, rv: host int32 [n_layers * n_heads], kept ranks of K' and V' (they may differ per head).
+ * ------------------------------------------------------------------------------------------ */
+fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
+                             const int32_t* rk, const int32_t* rv, int max_batch, int max_seq,
+                             fdc_dtype dtype, fdc_layout** out);
+
+/* Writes the offset tables to host arrays (any pointer may be NULL to skip it):
+ *   koff, voff  int64 [L*H]      element offset of unit (0, h) inside the layer's buffer
+ *   koff_r, voff_r int32 [L*(H+1)] prefix sums of the ranks (column offsets in [T, RK] tensors)
+ *   k_bytes, v_bytes int64 [L]   size of the layer's K' / V' buffer in bytes                  */
+fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff, int32_t* koff_r,
+                             int32_t* voff_r, int64_t* k_bytes, int64_t* v_bytes);
+
+void fdc_layout_destroy(fdc_layout* lay);
+
+/* ------------------------------------------------------------------------------------------
+ * Work partitioner (Section 5.3). Host side, integer arithmetic only, deterministic.
+ *
+ * decode:  task cost = s_kv * d_sum, d_sum = rk + rv + 1. Tasks are sorted by descending cost
+ *          (ties: lower id first) and handed one at a time to the worker with the smallest
+ *          accumulated cost (ties: lowest worker). Extension (split != 0): every unit is first cut
+ *          into min_split near-equal chunks on multiples of `granule` tokens; a worker is filled
+ *          only up to the mean load, a chunk that does not fit is cut at the nearest granule and
+ *          its remainder goes to the next least-loaded worker. The partial softmax states of a
+ *          split unit are merged exactly by fdc_latent_attn_decode.
+ * prefill: head i uses row block B_r_i = round_up_16(ceil(br_base * d_sum_max / d_sum_i)), capped
+ *          at br_cap. cost_mode 0 (paper): task cost rows * s_kv * d_sum; full rounds of
+ *          n_workers tasks are dealt round-robin in task order; the tasks of an incomplete last
+ *          round are re-split with row block max(16, floor_16(wl / d_sum_i)),
+ *          wl = ceil(sum_last rows_i * d_sum_i / n_workers), and handed in order to the
+ *          least-loaded worker. cost_mode 1 (causal): task cost counts only the keys a causal
+ *          query row sees; all tasks are handed out in descending cost order.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_workers; /* > 0. A worker is one wavefront (decode) or one workgroup (prefill). */
+  int32_t granule;   /* decode: token granularity of cuts (default 64) */
+  int32_t min_split; /* decode: minimum number of chunks per unit (default 1) */
+  int32_t split;     /* decode: 1 = divisible-work extension, 0 = the paper's one task per head */
+  int32_t br_base;   /* prefill: base row block (default 64) */
+  int32_t br_cap;    /* prefill: largest row block (default 256) */
+  int32_t cost_mode; /* prefill: 0 = paper, 1 = causal */
+} fdc_plan_params;
+
+/* Fills *p with the defaults above and n_workers = 0 (the caller must set it, e.g. from
+ * fdc_suggest_workers). */
+void fdc_plan_params_default(fdc_plan_params* p);
+
+/* Number of workers that are resident at once on the current HIP device for the decode
+ * (kind 0) or prefill (kind 1) kernel. Needs a GPU (FDC_HIP_ERROR otherwise). */
+fdc_status fdc_suggest_workers(int kind, int32_t* n_workers);
+
+/* seq_len: host int32 [batch], 0 <= seq_len[b] <= max_seq. */
+fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
+                           const fdc_plan_params* params, fdc_plan** out);
+
+/* q_len, kv_len: host int32 [batch]; the queries of sequence b are its last q_len[b] positions,
+ * q_len[b] <= kv_len[b] <= max_seq. Query rows of all sequences are stacked b-major: T = sum q_len. */
+fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
+                            const int32_t* kv_len, const fdc_plan_params* params, fdc_plan** out);
+
+/* Host view of a plan's tables (pointers stay valid until fdc_plan_destroy). An item is a decode
+ * tile (lo, hi = token range) or a prefill task (lo, hi = query-row range). */
+typedef struct {
+  int32_t kind; /* 0 decode, 1 prefill */
+  int32_t n_items;
+  int32_t n_workers;
+  int32_t n_units; /* batch * n_heads */
+  const int32_t* item_b;
+  const int32_t* item_h;
+  const int32_t* item_lo;
+  const int32_t* item_hi;
+  const int64_t* item_cost;
+  const int32_t* unit_item_ptr; /* decode: [n_units + 1], items of a unit are consecutive; prefill: NULL */
+  const int32_t* worker_ptr;    /* [n_workers + 1] */
+  const int32_t* worker_items;  /* [n_items], in hand-out order */
+  const int64_t* worker_load;   /* [n_workers] */
+  const int32_t* br;            /* prefill: [n_heads]; decode: NULL */
+} fdc_plan_tables;
+
+fdc_status fdc_plan_export(const fdc_plan* plan, fdc_plan_tables* out);
+
+/* Device workspace a plan needs: its tables plus, for decode, one partial softmax state per tile. */
+size_t fdc_plan_workspace_bytes(const fdc_plan* plan);
+
+/* Copies the plan's tables into the device workspace (asynchronously on `stream`; the plan must
+ * stay alive until the copy has completed). Must be called once before the attention call that
+ * uses (plan, workspace). */
+fdc_status fdc_plan_upload(const fdc_plan* plan, void* workspace, size_t workspace_bytes, void* stream);
+
+void fdc_plan_destroy(fdc_plan* plan);
+
+/* ------------------------------------------------------------------------------------------
+ * The five hot-path calls. All pointers below are device pointers unless marked host.
+ * ------------------------------------------------------------------------------------------ */
+
+/* K'_h = x . A_k^h and V'_h = x . A_v^h for all heads (Section 2: K' = E A), written into the
+ * ragged cache: row t goes to sequence tok_batch[t], position tok_pos[t].
+ *   x        [T, d_model]                       layout dtype
+ *   tok_batch, tok_pos  int32 [T]               0 <= tok_batch < max_batch, 0 <= tok_pos < max_seq
+ *   A_cat_t  [RK + RV, d_model] row-major       row n holds the d_model weights of latent column n
+ *                                               (the "out x in" order of a linear layer); rows: all K
+ *                                               heads (head-major), then all V heads
+ *   k_cache, v_cache    the layer's K' / V' buffers (sizes from fdc_layout_tables)
+ * T = 0 is a no-op. */
+fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x, int T,
+                                 const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
+                                 void* k_cache, void* v_cache, void* stream);
+
+/* q'_h = q_h . (B_k^h)^T per head (Section 2: Q K^T = E (W_Q B_K^T) K'^T).
+ *   q      [T, H, d_head]        layout dtype
+ *   Bk     [RK, d_head]          head h = rows koff_r[h] .. koff_r[h+1]
+ *   q_lat  [T, RK]               q_lat_dtype (F32 for decode, BF16 for prefill) */
+fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const void* Bk,
+                            void* q_lat, fdc_dtype q_lat_dtype, void* stream);
+
+/* Decode attention on the latent cache, one query per sequence (Section 5, step 7; Section 5.3
+ * decode scheduling): o'_h = softmax_t(scale * <q'_h, K'_h[t]>) . V'_h over t < seq_len[b].
+ *   q_lat [batch, RK] f32, o_lat [batch, RV] f32, scale normally 1/sqrt(d_head).
+ *   workspace: prepared by fdc_plan_upload for this plan. Sequences with seq_len 0 give zeros.
+ * Calls that share a workspace must not overlap in time. */
+fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
+                                  const void* k_cache, const void* v_cache, float scale, void* o_lat,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/* Prefill attention on the latent cache (Section 5, step 7; Section 5.3 prefill scheduling).
+ *   q_lat [T, RK] bf16 and o_lat [T, RV] bf16, rows stacked b-major as in fdc_plan_prefill;
+ *   causal != 0: query at position p sees keys t <= p. BF16 layouts only. */
+fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
+                                   const void* k_cache, const void* v_cache, float scale, int causal,
+                                   void* o_lat, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Output absorption: the latent head outputs go straight through M = B_v . W_o (the paper
+ * compresses V "following Palu"; the fold is (P V') B_v W_o = (P V') (B_v W_o)).
+ * Weights are stored "out x in" (contiguous along the summed index), so W_o comes as
+ * Wo_t [d_model, H*d_head] and the folded matrix is kept as Mt [d_model, RV] = M^T.
+ *   mode FDC_FOLD : M_h = B_v^h . W_o^h for every head; Bv [RV, d_head], Wo_t, Mt all layout dtype
+ *                   (Mt fp32 in an FDC_F32 layout). o_lat, y ignored.
+ *   mode FDC_APPLY: y [T, d_model] = o_lat [T, RV] . M;  o_lat_dtype / y_dtype say how they are
+ *                   stored. Bv, Wo_t ignored. */
+enum { FDC_FOLD = 0, FDC_APPLY = 1 };
+fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const void* Bv, const void* Wo_t,
+                             void* Mt, const void* o_lat, fdc_dtype o_lat_dtype, int T, void* y,
+                             fdc_dtype y_dtype, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDC_H_ */

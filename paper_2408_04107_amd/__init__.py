@@ -1,0 +1,12 @@
+"""MI355X-native latent-KV attention (FDC, arXiv 2408.04107).
+
+The product is libfdc.so (HIP kernels for gfx950 behind a C ABI, see
+include/fdc.h); this package is its thin ctypes binding. The entry points keep
+their C names.
+"""
+from .binding import (  # noqa: F401
+    FDC_APPLY, FDC_BF16, FDC_F32, FDC_FOLD, EXPORTED_SYMBOLS, FdcError, Layout, Plan, PlanParams,
+    fdc_absorb_output, fdc_absorb_query, fdc_latent_attn_decode, fdc_latent_attn_prefill,
+    fdc_plan_decode, fdc_plan_params_default, fdc_plan_prefill, fdc_plan_upload,
+    fdc_project_latent_kv, fdc_suggest_workers, lib,
+)

@@ -1,0 +1,399 @@
+// Decode attention on the latent KV cache (Section 5, step 7 of the paper: compressed Q', K', V'
+// go into attention without decompression; Section 5.3: per-head tasks of uneven cost are balanced
+// over the compute units).
+//
+// Design for gfx950. The work is one dot product and one axpy per cached element (1 flop per
+// byte), so the kernel is a pure HBM stream. A worker is one wavefront. It walks the tiles the
+// planner gave it; a tile is a token range of one (sequence, head) unit and therefore ONE
+// contiguous span of K' and one of V'. Each lane issues 16-byte loads that are contiguous across
+// the wave (1 KiB per load instruction). A row of rank r occupies L = r*sizeof(T)/16 lanes, padded
+// to a power of two, so a dot product is finished with log2(L) DPP adds. Scores of a block of
+// tokens go through a per-wave LDS strip, which (a) lets each score be exponentiated once instead
+// of once per lane of its row and (b) decouples the lane mapping of K' rows (rank rk) from that
+// of V' rows (rank rv). The softmax reference m is only raised when a block exceeds it by a
+// margin, so most blocks need no cross-lane maximum and no rescale. Split units leave
+// (m, l, acc) in a slot of their own (no atomics, deterministic) and a second small kernel merges
+// them.
+#include <hip/hip_runtime.h>
+
+#include "fdc_internal.h"
+
+namespace fdc {
+
+constexpr int kWavesPerBlock = 4;
+constexpr int kLdsFloatsPerWave = 256;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRaiseMargin = 6.0f;  // in log2 units: p never exceeds 2^6 between raises
+constexpr int kBufferFlags = 0x00020000;  // word 3 of a gfx9 raw buffer descriptor: 32-bit data format
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ---- small device helpers -------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over aligned groups of L lanes (L a power of two); every lane of the group gets the sum.
+template <int L>
+__device__ __forceinline__ float group_sum(float v) {
+  if constexpr (L >= 2) v += dpp<0xB1>(v);    // quad_perm [1,0,3,2]
+  if constexpr (L >= 4) v += dpp<0x4E>(v);    // quad_perm [2,3,0,1]
+  if constexpr (L >= 8) v += dpp<0x141>(v);   // row_half_mirror
+  if constexpr (L >= 16) v += dpp<0x140>(v);  // row_mirror
+  if constexpr (L >= 32) v += __shfl_xor(v, 16);
+  if constexpr (L >= 64) v += __shfl_xor(v, 32);
+  return v;
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  return v;
+}
+
+__device__ __forceinline__ void wave_lds_sync() {
+  // LDS operations of one wavefront execute in order; this only stops the compiler from moving
+  // LDS accesses of different lanes' data across the point.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<uint16_t> {  // bf16 bits
+  static constexpr int EL = 8;
+  __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
+    f[0] = __uint_as_float(r[0] << 16), f[1] = __uint_as_float(r[0] & 0xffff0000u);
+    f[2] = __uint_as_float(r[1] << 16), f[3] = __uint_as_float(r[1] & 0xffff0000u);
+    f[4] = __uint_as_float(r[2] << 16), f[5] = __uint_as_float(r[2] & 0xffff0000u);
+    f[6] = __uint_as_float(r[3] << 16), f[7] = __uint_as_float(r[3] & 0xffff0000u);
+  }
+};
+template <>
+struct Elem<float> {
+  static constexpr int EL = 4;
+  __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
+    f[0] = __uint_as_float(r[0]), f[1] = __uint_as_float(r[1]);
+    f[2] = __uint_as_float(r[2]), f[3] = __uint_as_float(r[3]);
+  }
+};
+
+// ---- one tile -----------------------------------------------------------------------------
+// LK / LV: lanes per K' / V' row (power of two >= rank * sizeof(T) / 16).
+template <typename T, int LK, int LV>
+__device__ __forceinline__ void decode_tile(const DecTile& td, const float* __restrict__ q_lat,
+                                            const T* __restrict__ kc, const T* __restrict__ vc, float scale_log2,
+                                            float* __restrict__ o_lat, float* __restrict__ partials, float* lds,
+                                            const int lane) {
+  constexpr int EL = Elem<T>::EL;
+  constexpr int TB = (512 / LK) < (512 / LV) ? (512 / LK) : (512 / LV);  // tokens per block
+  constexpr int RK_ROWS = 64 / LK, RV_ROWS = 64 / LV;                    // rows per wave-wide load
+  constexpr int NK = TB / RK_ROWS, NV = TB / RV_ROWS;                    // loads per lane per block
+  constexpr int NS = (TB + 63) / 64;                                     // scores per lane per block
+  static_assert(NK >= 1 && NV >= 1 && TB <= kLdsFloatsPerWave, "block shape");
+
+  const int rk = td.rk_rv & 0xffff, rv = td.rk_rv >> 16;
+  const int len = td.len;
+  const int ck = lane % LK, sk = lane / LK;
+  const int cv = lane % LV, sv = lane / LV;
+  const bool k_on = ck * EL < rk, v_on = cv * EL < rv;
+
+  // q' of the lane's column group, pre-multiplied by scale * log2(e); padded lanes hold zeros
+  float qf[EL];
+  {
+    const float* qp = q_lat + td.q_elem + (k_on ? ck * EL : 0);
+    const float qs = k_on ? scale_log2 : 0.f;
+#pragma unroll
+    for (int j = 0; j < EL; ++j) qf[j] = qp[j] * qs;
+  }
+
+  // The tile's K' and V' spans as raw buffers: loads past the span (rows >= len in the last
+  // block) and loads of padded lanes (offset forced out of range) return zeros in hardware, so
+  // the stream has no branches. The range check covers the VGPR offset only, so the whole
+  // row offset is kept there.
+  const int k_row_bytes = rk * (int)sizeof(T), v_row_bytes = rv * (int)sizeof(T);
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<T*>(kc + td.k_elem), 0, len * k_row_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<T*>(vc + td.v_elem), 0, len * v_row_bytes, kBufferFlags);
+  const uint32_t k_lane = k_on ? (uint32_t)(sk * k_row_bytes + ck * 16) : 0x80000000u;
+  const uint32_t v_lane = v_on ? (uint32_t)(sv * v_row_bytes + cv * 16) : 0x80000000u;
+
+  u32x4 kreg[NK], vreg[NV];
+  auto load_k = [&](int t0) {
+    const uint32_t base = k_lane + (uint32_t)(t0 * k_row_bytes);
+#pragma unroll
+    for (int i = 0; i < NK; ++i)
+      kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(base + (uint32_t)(i * RK_ROWS * k_row_bytes)), 0, 0);
+  };
+  auto load_v = [&](int t0) {
+    const uint32_t base = v_lane + (uint32_t)(t0 * v_row_bytes);
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(base + (uint32_t)(i * RV_ROWS * v_row_bytes)), 0, 0);
+  };
+
+  float acc[EL];
+#pragma unroll
+  for (int j = 0; j < EL; ++j) acc[j] = 0.f;
+  float m = -INFINITY, l = 0.f;
+
+  load_k(0);
+  __builtin_amdgcn_sched_barrier(0);  // keep issue order K' then V': the wait counters rely on it
+  load_v(0);
+  __builtin_amdgcn_sched_barrier(0);
+  for (int t0 = 0; t0 < len; t0 += TB) {
+    // scores of the block -> LDS strip
+#pragma unroll
+    for (int i = 0; i < NK; ++i) {
+      float f[EL];
+      Elem<T>::widen(kreg[i], f);
+      float d = 0.f;
+#pragma unroll
+      for (int j = 0; j < EL; ++j) d = fmaf(qf[j], f[j], d);
+      d = group_sum<LK>(d);
+      const int r = i * RK_ROWS + sk;
+      if (t0 + r >= len) d = -INFINITY;
+      lds[r] = d;  // every lane of the row's group holds the sum; same-address writes need no branch
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(t0 + TB);  // past the end of the tile the hardware range check returns zeros
+    __builtin_amdgcn_sched_barrier(0);
+    wave_lds_sync();
+
+    // one exponential per score; raise the reference only when a block beats it by the margin
+    float s[NS], loc = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+      const int idx = lane + 64 * j;
+      s[j] = idx < TB ? lds[idx] : -INFINITY;
+      loc = fmaxf(loc, s[j]);
+    }
+    if (__any(loc > m + kRaiseMargin)) {
+      const float nm = fmaxf(m, wave_max(loc));
+      const float alpha = __builtin_amdgcn_exp2f(m - nm);  // m = -inf on the first block: 0
+      l *= alpha;
+#pragma unroll
+      for (int j = 0; j < EL; ++j) acc[j] *= alpha;
+      m = nm;
+    }
+#pragma unroll
+    for (int j = 0; j < NS; ++j) {
+      const int idx = lane + 64 * j;
+      const float p = __builtin_amdgcn_exp2f(s[j] - m);
+      l += p;
+      if (idx < TB) lds[idx] = p;
+    }
+    wave_lds_sync();
+
+    // acc += p * V'
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const float p = lds[i * RV_ROWS + sv];
+      float f[EL];
+      Elem<T>::widen(vreg[i], f);
+#pragma unroll
+      for (int j = 0; j < EL; ++j) acc[j] = fmaf(p, f[j], acc[j]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(t0 + TB);
+    __builtin_amdgcn_sched_barrier(0);
+    wave_lds_sync();
+  }
+
+  // tile result: l over all lanes, acc over the lanes that share a column group
+  l = group_sum<64>(l);
+#pragma unroll
+  for (int o = LV; o < 64; o <<= 1) {
+#pragma unroll
+    for (int j = 0; j < EL; ++j) acc[j] += __shfl_xor(acc[j], o);
+  }
+  if (sv == 0 && v_on) {
+    if (td.slot < 0) {
+      const float inv = 1.f / l;
+      float* o = o_lat + td.o_elem + cv * EL;
+#pragma unroll
+      for (int j = 0; j < EL; ++j) o[j] = acc[j] * inv;
+    } else {
+      float* pp = partials + (int64_t)td.slot * kPartialStride;
+#pragma unroll
+      for (int j = 0; j < EL; ++j) pp[4 + cv * EL + j] = acc[j];
+      if (cv == 0) pp[0] = m, pp[1] = l;
+    }
+  }
+}
+
+// log2 of the padded lanes-per-row: rank r needs r * sizeof(T) / 16 lanes.
+template <typename T>
+__device__ __forceinline__ int lane_class(int r) {
+  const int lanes = r / Elem<T>::EL;  // 2..16 (bf16), 4..32 (f32)
+  return 32 - __builtin_clz(lanes - 1);  // ceil(log2(lanes)) for lanes >= 2
+}
+
+template <typename T>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
+    const DecTile* __restrict__ tiles, const int32_t* __restrict__ worker_ptr,
+    const int32_t* __restrict__ worker_items, const float* __restrict__ q_lat, const T* __restrict__ kc,
+    const T* __restrict__ vc, float scale_log2, float* __restrict__ o_lat, float* __restrict__ partials,
+    int n_workers) {
+  __shared__ float lds_all[kWavesPerBlock][kLdsFloatsPerWave];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+  const int lane = threadIdx.x % 64;
+  const int worker = blockIdx.x * kWavesPerBlock + wave;
+  if (worker >= n_workers) return;
+  float* lds = lds_all[wave];
+  const int i0 = worker_ptr[worker], i1 = worker_ptr[worker + 1];
+  constexpr int BASE = Elem<T>::EL == 8 ? 1 : 2;  // smallest lane class of this element type
+  for (int i = i0; i < i1; ++i) {
+    const int tid = __builtin_amdgcn_readfirstlane(worker_items[i]);
+    const DecTile td = tiles[tid];
+    const int ck = lane_class<T>(td.rk_rv & 0xffff) - BASE, cvv = lane_class<T>(td.rk_rv >> 16) - BASE;
+#define FDC_CASE(a, b)                                                                                      \
+  case (a)*4 + (b):                                                                                         \
+    decode_tile<T, (2 << (a)) * (BASE == 2 ? 2 : 1), (2 << (b)) * (BASE == 2 ? 2 : 1)>(td, q_lat, kc, vc,   \
+                                                                                      scale_log2, o_lat,   \
+                                                                                      partials, lds, lane); \
+    break;
+    switch (ck * 4 + cvv) {
+      FDC_CASE(0, 0) FDC_CASE(0, 1) FDC_CASE(0, 2) FDC_CASE(0, 3)
+      FDC_CASE(1, 0) FDC_CASE(1, 1) FDC_CASE(1, 2) FDC_CASE(1, 3)
+      FDC_CASE(2, 0) FDC_CASE(2, 1) FDC_CASE(2, 2) FDC_CASE(2, 3)
+      FDC_CASE(3, 0) FDC_CASE(3, 1) FDC_CASE(3, 2) FDC_CASE(3, 3)
+      default: break;
+    }
+#undef FDC_CASE
+  }
+}
+
+// ---- split-K merge --------------------------------------------------------------------------
+// One workgroup per unit. o' = sum_j acc_j 2^(m_j - M) / sum_j l_j 2^(m_j - M), M = max_j m_j.
+constexpr int kMergeThreads = 256;
+__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecUnit* __restrict__ units,
+                                                                     const float* __restrict__ partials,
+                                                                     float* __restrict__ o_lat) {
+  const DecUnit u = units[blockIdx.x];
+  const int n = u.tile_end - u.tile_begin;
+  const int tid = threadIdx.x;
+  if (n == 1) return;  // the tile kernel wrote the normalised output itself
+  if (n == 0) {
+    for (int c = tid; c < u.rv; c += kMergeThreads) o_lat[u.o_elem + c] = 0.f;
+    return;
+  }
+  __shared__ float red[kMergeThreads];
+  __shared__ float accs[8][132];
+  // M
+  float mx = -INFINITY;
+  for (int j = tid; j < n; j += kMergeThreads) mx = fmaxf(mx, partials[(int64_t)(u.tile_begin + j) * kPartialStride]);
+  red[tid] = mx;
+  __syncthreads();
+  for (int s = kMergeThreads / 2; s > 0; s >>= 1) {
+    if (tid < s) red[tid] = fmaxf(red[tid], red[tid + s]);
+    __syncthreads();
+  }
+  const float M = red[0];
+  __syncthreads();
+  // 32 column quads x 8 tile groups; column quad 32 (threads with q == 0 reuse) carries l
+  const int q = tid % 32, g = tid / 32;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lsum = 0.f;
+  const bool col_on = q * 4 < u.rv;
+  for (int j = g; j < n; j += 8) {
+    const float* pp = partials + (int64_t)(u.tile_begin + j) * kPartialStride;
+    const float w = __builtin_amdgcn_exp2f(pp[0] - M);
+    if (q == 0) lsum += pp[1] * w;
+    if (col_on) {
+      const float4 v = *reinterpret_cast<const float4*>(pp + 4 + q * 4);
+      a.x += v.x * w, a.y += v.y * w, a.z += v.z * w, a.w += v.w * w;
+    }
+  }
+  accs[g][q * 4 + 0] = a.x, accs[g][q * 4 + 1] = a.y, accs[g][q * 4 + 2] = a.z, accs[g][q * 4 + 3] = a.w;
+  if (q == 0) accs[g][128] = lsum;
+  __syncthreads();
+  if (tid < u.rv) {
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) num += accs[k][tid], den += accs[k][128];
+    o_lat[u.o_elem + tid] = num / den;
+  }
+}
+
+}  // namespace fdc
+
+using namespace fdc;
+
+extern "C" {
+
+fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
+  if (!n_workers) FDC_FAIL(FDC_INVALID_ARG, "fdc_suggest_workers: NULL argument");
+  int dev = 0;
+  FDC_HIP_CHECK(hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  FDC_HIP_CHECK(hipGetDeviceProperties(&prop, dev));
+  if (kind == 0) {
+    int nb = 0;
+    FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<uint16_t>,
+                                                               kWavesPerBlock * 64, 0));
+    *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
+  } else if (kind == 1) {
+    *n_workers = prop.multiProcessorCount;
+  } else {
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_suggest_workers: kind %d", kind);
+  }
+  return FDC_OK;
+}
+
+fdc_status fdc_plan_upload(const fdc_plan* plan, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!plan || !workspace) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_upload: NULL argument");
+  if (workspace_bytes < plan->workspace_bytes)
+    FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_plan_upload: workspace has %zu bytes, the plan needs %zu", workspace_bytes,
+             plan->workspace_bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_plan_upload: workspace must be 256-byte aligned");
+  FDC_HIP_CHECK(hipMemcpyAsync(workspace, plan->image.data(), plan->image.size(), hipMemcpyHostToDevice,
+                               static_cast<hipStream_t>(stream)));
+  return FDC_OK;
+}
+
+fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat, const void* k_cache,
+                                  const void* v_cache, float scale, void* o_lat, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: NULL argument");
+  if (plan->kind != 0 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: not a decode plan of this layout");
+  if (workspace_bytes < plan->workspace_bytes)
+    FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_latent_attn_decode: workspace has %zu bytes, the plan needs %zu",
+             workspace_bytes, plan->workspace_bytes);
+  if (!aligned16(q_lat) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o_lat) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_latent_attn_decode: pointers must be 16-byte aligned (workspace 256)");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  const DecTile* tiles = reinterpret_cast<const DecTile*>(ws + plan->off_items);
+  const DecUnit* units = reinterpret_cast<const DecUnit*>(ws + plan->off_units);
+  const int32_t* wptr = reinterpret_cast<const int32_t*>(ws + plan->off_worker_ptr);
+  const int32_t* witems = reinterpret_cast<const int32_t*>(ws + plan->off_worker_items);
+  float* partials = reinterpret_cast<float*>(ws + plan->off_partials);
+  const int W = plan->n_workers;
+  const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
+  const float scale_log2 = scale * kLog2e;
+  if (!plan->item_b.empty()) {
+    if (lay->dtype == FDC_BF16)
+      hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, tiles, wptr, witems,
+                         static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
+                         static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+    else
+      hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, tiles, wptr, witems,
+                         static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),
+                         static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+    FDC_HIP_CHECK(hipGetLastError());
+  }
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(plan->n_units), dim3(kMergeThreads), 0, st, units, partials,
+                     static_cast<float*>(o_lat));
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,345 @@
+// The three projection-type calls of the hot path (Section 2 of the paper):
+//   fdc_project_latent_kv   K' = x A_k, V' = x A_v, written into the ragged cache
+//   fdc_absorb_query        q'_h = q_h B_k^T                      (grouped over heads)
+//   fdc_absorb_output       M = B_v W_o (grouped, once) and y = o' M
+// All four products have the form C[m, n] = sum_k A[m, k] * B[n, k] with both operands contiguous
+// along k, so one bf16 MFMA kernel (fp32 accumulation) serves them and only the addressing of a
+// group and the epilogue differ. FDC_F32 layouts use a plain fp32 kernel (validation shapes).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "fdc_internal.h"
+
+namespace fdc {
+
+constexpr int kMaxHeads = 128;
+
+enum GemmMode { kPlain = 0, kProject = 1, kAbsorbQuery = 2, kFold = 3 };
+
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  void* C2;  // project: the V' cache
+  int64_t lda, ldb, ldc;
+  int M, N, K;
+  int mode;
+  int H, d_head, max_seq;
+  int RK, RV;
+  const int32_t* tok_batch;
+  const int32_t* tok_pos;
+  int32_t koff_r[kMaxHeads + 1];
+  int32_t voff_r[kMaxHeads + 1];
+};
+
+// Per-group view: which rows/columns this z-slice multiplies.
+struct Group {
+  int64_t a_off, b_off, c_off;
+  int N;
+};
+
+__device__ __forceinline__ Group group_of(const GemmArgs& g, int z) {
+  Group r{0, 0, 0, g.N};
+  if (g.mode == kAbsorbQuery) {  // A = q[:, z, :], B = Bk rows of head z, C = q_lat columns of head z
+    r.a_off = (int64_t)z * g.d_head;
+    r.b_off = (int64_t)g.koff_r[z] * g.d_head;
+    r.c_off = g.koff_r[z];
+    r.N = g.koff_r[z + 1] - g.koff_r[z];
+  } else if (g.mode == kFold) {  // A = Wo_t[:, z*d_h ..], B = Bv rows of head z, C = Mt columns of head z
+    r.a_off = (int64_t)z * g.d_head;
+    r.b_off = (int64_t)g.voff_r[z] * g.d_head;
+    r.c_off = g.voff_r[z];
+    r.N = g.voff_r[z + 1] - g.voff_r[z];
+  }
+  return r;
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest, ties to even
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+template <typename T>
+__device__ __forceinline__ void store_out(T* p, float v);
+template <>
+__device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
+template <>
+__device__ __forceinline__ void store_out<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// Cache element for output column n of the concatenated [K heads | V heads] projection.
+// Returns the buffer (0 = K', 1 = V') and the element offset for token (b, pos).
+__device__ __forceinline__ int64_t project_dst(const GemmArgs& g, int n, int b, int pos, int* side) {
+  const int s = n >= g.RK;
+  const int c = s ? n - g.RK : n;
+  const int32_t* off_r = s ? g.voff_r : g.koff_r;
+  int lo = 0, hi = g.H;  // largest h with off_r[h] <= c
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (off_r[mid] <= c) lo = mid; else hi = mid;
+  }
+  const int r = off_r[lo + 1] - off_r[lo];
+  const int R = s ? g.RV : g.RK;
+  *side = s;
+  return (int64_t)b * g.max_seq * R + (int64_t)g.max_seq * off_r[lo] + (int64_t)pos * r + (c - off_r[lo]);
+}
+
+// ---- fp32 reference-quality kernel for FDC_F32 layouts -----------------------------------------
+template <typename TC>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
+  const Group gr = group_of(g, blockIdx.z);
+  const int n = blockIdx.x * 16 + threadIdx.x % 16;
+  const int m = blockIdx.y * 16 + threadIdx.x / 16;
+  if (m >= g.M || n >= gr.N) return;
+  const float* a = static_cast<const float*>(g.A) + gr.a_off + (int64_t)m * g.lda;
+  const float* b = static_cast<const float*>(g.B) + gr.b_off + (int64_t)n * g.ldb;
+  float acc = 0.f;
+  for (int k = 0; k < g.K; ++k) acc = fmaf(a[k], b[k], acc);
+  if (g.mode == kProject) {
+    int side;
+    const int64_t e = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+    static_cast<float*>(side ? g.C2 : g.C)[e] = acc;
+  } else {
+    store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc);
+  }
+}
+
+// ---- bf16 MFMA kernel --------------------------------------------------------------------------
+// Workgroup tile 128 x 128, k step 32, four waves in a 2 x 2 grid, each wave 64 x 64 as 2 x 2
+// v_mfma_f32_32x32x16_bf16 tiles. Both operands are staged through LDS with rows padded by 16
+// bytes; fragments are read with one 16-byte LDS load per lane (8 consecutive k of one row).
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int kLdsRow = BK + 8;  // elements per padded LDS row (80 bytes)
+
+template <typename TA>
+__device__ __forceinline__ u32x4 load_chunk(const TA* p);  // 8 consecutive elements -> 8 bf16
+template <>
+__device__ __forceinline__ u32x4 load_chunk<uint16_t>(const uint16_t* p) {
+  return *reinterpret_cast<const u32x4*>(p);
+}
+template <>
+__device__ __forceinline__ u32x4 load_chunk<float>(const float* p) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  u32x4 r;
+  r[0] = f32_to_bf16(a.x) | ((uint32_t)f32_to_bf16(a.y) << 16);
+  r[1] = f32_to_bf16(a.z) | ((uint32_t)f32_to_bf16(a.w) << 16);
+  r[2] = f32_to_bf16(b.x) | ((uint32_t)f32_to_bf16(b.y) << 16);
+  r[3] = f32_to_bf16(b.z) | ((uint32_t)f32_to_bf16(b.w) << 16);
+  return r;
+}
+
+template <typename TA, typename TC>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
+  const Group gr = group_of(g, blockIdx.z);
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  if (n0 >= gr.N) return;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[BM * kLdsRow];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[BN * kLdsRow];
+
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int wm = (wave / 2) * 64, wn = (wave % 2) * 64;
+  const TA* A = static_cast<const TA*>(g.A) + gr.a_off;
+  const uint16_t* B = static_cast<const uint16_t*>(g.B) + gr.b_off;
+
+  // staging: 128 rows x 4 chunks of 8 elements per operand, two chunks per thread
+  const int s_row = tid / 4, s_kc = (tid % 4) * 8;  // rows s_row and s_row + 64
+  u32x4 ra[2], rb[2];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = s_row + 64 * i;
+      const bool k_ok = k0 + s_kc < g.K;
+      ra[i] = (k_ok && m0 + row < g.M) ? load_chunk<TA>(A + (int64_t)(m0 + row) * g.lda + k0 + s_kc)
+                                       : u32x4{0, 0, 0, 0};
+      rb[i] = (k_ok && n0 + row < gr.N) ? load_chunk<uint16_t>(B + (int64_t)(n0 + row) * g.ldb + k0 + s_kc)
+                                        : u32x4{0, 0, 0, 0};
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = s_row + 64 * i;
+      *reinterpret_cast<u32x4*>(&lds_a[row * kLdsRow + s_kc]) = ra[i];
+      *reinterpret_cast<u32x4*>(&lds_b[row * kLdsRow + s_kc]) = rb[i];
+    }
+  };
+
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+    __syncthreads();  // previous iteration's fragment reads are done
+    stage();
+    __syncthreads();
+    if (k0 + BK < g.K) fetch(k0 + BK);
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *reinterpret_cast<const bf16x8*>(&lds_a[(wm + i * 32 + lane % 32) * kLdsRow + ks + (lane / 32) * 8]);
+        fb[i] = *reinterpret_cast<const bf16x8*>(&lds_b[(wn + i * 32 + lane % 32) * kLdsRow + ks + (lane / 32) * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+  // epilogue. 32x32 accumulator: register e of lane l is row (e/4)*8 + (l/32)*4 + e%4, column l%32.
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = n0 + wn + j * 32 + lane % 32;
+    if (n >= gr.N) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm + i * 32 + (e / 4) * 8 + (lane / 32) * 4 + e % 4;
+        if (m >= g.M) continue;
+        if (g.mode == kProject) {
+          int side;
+          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(acc[i][j][e]);
+        } else {
+          store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc[i][j][e]);
+        }
+      }
+    }
+  }
+}
+
+static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
+  const int H = lay->H;
+  a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq;
+  a.RK = lay->RK(layer), a.RV = lay->RV(layer);
+  std::copy_n(&lay->koff_r[(size_t)layer * (H + 1)], H + 1, a.koff_r);
+  std::copy_n(&lay->voff_r[(size_t)layer * (H + 1)], H + 1, a.voff_r);
+}
+
+// Launches the kernel for the layout's dtype. a_f32 / c_f32 say how A and C are stored in a
+// bf16 layout (activations coming from / going to fp32 tensors).
+static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, int n_max, bool a_f32, bool c_f32,
+                         hipStream_t st) {
+  if (a.M == 0 || n_max == 0) return FDC_OK;
+  if (lay->dtype == FDC_F32) {
+    const dim3 grid((n_max + 15) / 16, (a.M + 15) / 16, groups);
+    hipLaunchKernelGGL(gemm_f32_kernel<float>, grid, dim3(256), 0, st, a);
+  } else {
+    const dim3 grid((n_max + BN - 1) / BN, (a.M + BM - 1) / BM, groups);
+    if (a_f32 && c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, float>), grid, dim3(256), 0, st, a);
+    else if (a_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, uint16_t>), grid, dim3(256), 0, st, a);
+    else if (c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, float>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st, a);
+  }
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
+}
+
+static fdc_status check_common(const char* fn, const fdc_layout* lay, int layer, int T) {
+  if (!lay) FDC_FAIL(FDC_INVALID_ARG, "%s: layout is NULL", fn);
+  if (layer < 0 || layer >= lay->L) FDC_FAIL(FDC_BAD_SHAPE, "%s: layer %d outside [0, %d)", fn, layer, lay->L);
+  if (T < 0) FDC_FAIL(FDC_BAD_SHAPE, "%s: T = %d is negative", fn, T);
+  if (lay->H > kMaxHeads) FDC_FAIL(FDC_BAD_SHAPE, "%s: more than %d heads", fn, kMaxHeads);
+  return FDC_OK;
+}
+
+}  // namespace fdc
+
+using namespace fdc;
+
+extern "C" {
+
+fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x, int T, const int32_t* tok_batch,
+                                 const int32_t* tok_pos, const void* A_cat_t, void* k_cache, void* v_cache,
+                                 void* stream) {
+  fdc_status s = check_common("fdc_project_latent_kv", lay, layer, T);
+  if (s != FDC_OK) return s;
+  if (T == 0) return FDC_OK;
+  if (!x || !tok_batch || !tok_pos || !A_cat_t || !k_cache || !v_cache)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_project_latent_kv: NULL argument");
+  if (!aligned16(x) || !aligned16(A_cat_t) || !aligned16(k_cache) || !aligned16(v_cache))
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_project_latent_kv: pointers must be 16-byte aligned");
+  GemmArgs a{};
+  fill_tables(a, lay, layer);
+  a.A = x, a.B = A_cat_t, a.C = k_cache, a.C2 = v_cache;
+  a.lda = lay->d_model, a.ldb = lay->d_model, a.ldc = 0;
+  a.M = T, a.N = a.RK + a.RV, a.K = lay->d_model;
+  a.mode = kProject;
+  a.tok_batch = tok_batch, a.tok_pos = tok_pos;
+  return launch(lay, a, 1, a.N, false, false, static_cast<hipStream_t>(stream));
+}
+
+fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const void* Bk, void* q_lat,
+                            fdc_dtype q_lat_dtype, void* stream) {
+  fdc_status s = check_common("fdc_absorb_query", lay, layer, T);
+  if (s != FDC_OK) return s;
+  if (T == 0) return FDC_OK;
+  if (!q || !Bk || !q_lat) FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_query: NULL argument");
+  if (!aligned16(q) || !aligned16(Bk) || !aligned16(q_lat))
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_absorb_query: pointers must be 16-byte aligned");
+  if (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_absorb_query: q_lat_dtype");
+  if (lay->dtype == FDC_F32 && q_lat_dtype != FDC_F32)
+    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_absorb_query: an fp32 layout writes fp32 q_lat");
+  GemmArgs a{};
+  fill_tables(a, lay, layer);
+  a.A = q, a.B = Bk, a.C = q_lat;
+  a.lda = (int64_t)lay->H * lay->d_head, a.ldb = lay->d_head, a.ldc = a.RK;
+  a.M = T, a.N = 0, a.K = lay->d_head;
+  a.mode = kAbsorbQuery;
+  int n_max = 0;
+  for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rk[(size_t)layer * lay->H + h]);
+  return launch(lay, a, lay->H, n_max, false, q_lat_dtype == FDC_F32, static_cast<hipStream_t>(stream));
+}
+
+fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const void* Bv, const void* Wo_t, void* Mt,
+                             const void* o_lat, fdc_dtype o_lat_dtype, int T, void* y, fdc_dtype y_dtype,
+                             void* stream) {
+  fdc_status s = check_common("fdc_absorb_output", lay, layer, T);
+  if (s != FDC_OK) return s;
+  if (!Mt || !aligned16(Mt)) FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output: Mt is NULL or not 16-byte aligned");
+  GemmArgs a{};
+  fill_tables(a, lay, layer);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (mode == FDC_FOLD) {
+    if (!Bv || !Wo_t) FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output(FOLD): NULL argument");
+    if (!aligned16(Bv) || !aligned16(Wo_t)) FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_absorb_output(FOLD): alignment");
+    a.A = Wo_t, a.B = Bv, a.C = Mt;
+    a.lda = (int64_t)lay->H * lay->d_head, a.ldb = lay->d_head, a.ldc = a.RV;
+    a.M = lay->d_model, a.N = 0, a.K = lay->d_head;
+    a.mode = kFold;
+    int n_max = 0;
+    for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rv[(size_t)layer * lay->H + h]);
+    return launch(lay, a, lay->H, n_max, false, lay->dtype == FDC_F32, st);
+  }
+  if (mode == FDC_APPLY) {
+    if (T == 0) return FDC_OK;
+    if (!o_lat || !y) FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output(APPLY): NULL argument");
+    if (!aligned16(o_lat) || !aligned16(y)) FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_absorb_output(APPLY): alignment");
+    for (fdc_dtype d : {o_lat_dtype, y_dtype})
+      if (d != FDC_BF16 && d != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_absorb_output(APPLY): dtype");
+    if (lay->dtype == FDC_F32 && (o_lat_dtype != FDC_F32 || y_dtype != FDC_F32))
+      FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_absorb_output(APPLY): an fp32 layout takes and writes fp32");
+    a.A = o_lat, a.B = Mt, a.C = y;
+    a.lda = a.RV, a.ldb = a.RV, a.ldc = lay->d_model;
+    a.M = T, a.N = lay->d_model, a.K = a.RV;
+    a.mode = kPlain;
+    return launch(lay, a, 1, a.N, o_lat_dtype == FDC_F32, y_dtype == FDC_F32, st);
+  }
+  FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output: mode %d", mode);
+}
+
+}  // extern "C"

@@ -1,0 +1,441 @@
+// Host side of libfdc: error text, the ragged cache layout and the work partitioner.
+// Integer arithmetic only; no GPU is needed for anything in this file.
+#include <algorithm>
+#include <cstring>
+#include <functional>
+#include <new>
+#include <numeric>
+#include <queue>
+#include <utility>
+
+#include "fdc_internal.h"
+
+namespace fdc {
+
+static thread_local std::string g_error;
+
+void set_error(const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof(buf), fmt, ap);
+  va_end(ap);
+  g_error = buf;
+}
+
+// Min-heap of (load, worker id): the top is the least-loaded worker, ties to the lowest id.
+using Load = std::pair<int64_t, int32_t>;
+using LoadHeap = std::priority_queue<Load, std::vector<Load>, std::greater<Load>>;
+
+static LoadHeap empty_workers(int W) {
+  std::vector<Load> v(W);
+  for (int w = 0; w < W; ++w) v[w] = Load(0, w);
+  return LoadHeap(std::greater<Load>(), std::move(v));
+}
+
+template <class T>
+static size_t append_aligned(std::vector<unsigned char>& img, const T* data, size_t count) {
+  size_t off = (img.size() + 255) / 256 * 256;
+  img.resize(off + std::max<size_t>(count * sizeof(T), 16));
+  if (count) std::memcpy(img.data() + off, data, count * sizeof(T));
+  return off;
+}
+
+static void worker_csr(const std::vector<std::vector<int32_t>>& lists, fdc_plan* p) {
+  p->worker_ptr.assign(1, 0);
+  p->worker_items.clear();
+  for (const auto& l : lists) {
+    p->worker_items.insert(p->worker_items.end(), l.begin(), l.end());
+    p->worker_ptr.push_back((int32_t)p->worker_items.size());
+  }
+}
+
+}  // namespace fdc
+
+using namespace fdc;
+
+extern "C" {
+
+void fdc_last_error(char* buf, size_t n) {
+  if (!buf || n == 0) return;
+  std::strncpy(buf, g_error.c_str(), n - 1);
+  buf[n - 1] = '\0';
+}
+
+// ------------------------------------------------------------------------------------ layout
+fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head, const int32_t* rk,
+                             const int32_t* rv, int max_batch, int max_seq, fdc_dtype dtype,
+                             fdc_layout** out) {
+  if (!out) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create: out is NULL");
+  *out = nullptr;
+  if (!rk || !rv) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create: rk/rv is NULL");
+  if (n_layers <= 0 || n_heads <= 0 || d_model <= 0 || max_batch <= 0 || max_seq <= 0)
+    FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: non-positive dimension");
+  if (d_head < 16 || d_head > 128 || d_head % 16 != 0)
+    FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_head %d must be a multiple of 16 in [16, 128]", d_head);
+  if (d_model % 8 != 0) FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_model %d must be a multiple of 8", d_model);
+  if (dtype != FDC_BF16 && dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_layout_create: dtype %d", (int)dtype);
+  const size_t n = (size_t)n_layers * n_heads;
+  for (size_t i = 0; i < n; ++i) {
+    for (int32_t r : {rk[i], rv[i]})
+      if (r < 16 || r > d_head || r % 16 != 0)
+        FDC_FAIL(FDC_UNSUPPORTED_RANK, "fdc_layout_create: rank %d at index %zu is not a multiple of 16 in [16, %d]",
+                 r, i, d_head);
+  }
+  fdc_layout* lay = new (std::nothrow) fdc_layout();
+  if (!lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create: out of host memory");
+  lay->L = n_layers, lay->H = n_heads, lay->d_model = d_model, lay->d_head = d_head;
+  lay->max_batch = max_batch, lay->max_seq = max_seq, lay->dtype = dtype;
+  lay->elem_size = dtype == FDC_BF16 ? 2 : 4;
+  lay->rk.assign(rk, rk + n);
+  lay->rv.assign(rv, rv + n);
+  lay->koff.resize(n), lay->voff.resize(n);
+  lay->koff_r.resize((size_t)n_layers * (n_heads + 1));
+  lay->voff_r.resize((size_t)n_layers * (n_heads + 1));
+  lay->k_elems.resize(n_layers), lay->v_elems.resize(n_layers);
+  for (int l = 0; l < n_layers; ++l) {
+    int32_t runk = 0, runv = 0;
+    for (int h = 0; h < n_heads; ++h) {
+      const size_t i = (size_t)l * n_heads + h, j = (size_t)l * (n_heads + 1) + h;
+      lay->koff_r[j] = runk, lay->voff_r[j] = runv;
+      lay->koff[i] = (int64_t)max_seq * runk, lay->voff[i] = (int64_t)max_seq * runv;
+      runk += rk[i], runv += rv[i];
+    }
+    lay->koff_r[(size_t)l * (n_heads + 1) + n_heads] = runk;
+    lay->voff_r[(size_t)l * (n_heads + 1) + n_heads] = runv;
+    lay->k_elems[l] = (int64_t)max_batch * max_seq * runk;
+    lay->v_elems[l] = (int64_t)max_batch * max_seq * runv;
+  }
+  *out = lay;
+  return FDC_OK;
+}
+
+fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff, int32_t* koff_r,
+                             int32_t* voff_r, int64_t* k_bytes, int64_t* v_bytes) {
+  if (!lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_tables: layout is NULL");
+  if (koff) std::copy(lay->koff.begin(), lay->koff.end(), koff);
+  if (voff) std::copy(lay->voff.begin(), lay->voff.end(), voff);
+  if (koff_r) std::copy(lay->koff_r.begin(), lay->koff_r.end(), koff_r);
+  if (voff_r) std::copy(lay->voff_r.begin(), lay->voff_r.end(), voff_r);
+  for (int l = 0; l < lay->L; ++l) {
+    if (k_bytes) k_bytes[l] = lay->k_elems[l] * lay->elem_size;
+    if (v_bytes) v_bytes[l] = lay->v_elems[l] * lay->elem_size;
+  }
+  return FDC_OK;
+}
+
+void fdc_layout_destroy(fdc_layout* lay) { delete lay; }
+
+// ------------------------------------------------------------------------------------ planner
+void fdc_plan_params_default(fdc_plan_params* p) {
+  if (!p) return;
+  p->n_workers = 0;
+  p->granule = 64;
+  p->min_split = 1;
+  p->split = 1;
+  p->br_base = 64;
+  p->br_cap = 256;
+  p->cost_mode = 0;
+}
+
+static fdc_status check_plan_args(const char* fn, const fdc_layout* lay, int layer, int batch,
+                                  const void* lens, const fdc_plan_params* pr, fdc_plan** out) {
+  if (!out) FDC_FAIL(FDC_INVALID_ARG, "%s: out is NULL", fn);
+  *out = nullptr;
+  if (!lay || !lens || !pr) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
+  if (layer < 0 || layer >= lay->L) FDC_FAIL(FDC_BAD_SHAPE, "%s: layer %d outside [0, %d)", fn, layer, lay->L);
+  if (batch <= 0 || batch > lay->max_batch)
+    FDC_FAIL(FDC_BAD_SHAPE, "%s: batch %d outside [1, %d]", fn, batch, lay->max_batch);
+  if (pr->n_workers <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: n_workers must be positive", fn);
+  return FDC_OK;
+}
+
+fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
+                           const fdc_plan_params* pr, fdc_plan** out) {
+  fdc_status st = check_plan_args("fdc_plan_decode", lay, layer, batch, seq_len, pr, out);
+  if (st != FDC_OK) return st;
+  if (pr->granule <= 0 || pr->min_split <= 0)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: granule and min_split must be positive");
+  for (int b = 0; b < batch; ++b)
+    if (seq_len[b] < 0 || seq_len[b] > lay->max_seq)
+      FDC_FAIL(FDC_BAD_SHAPE, "fdc_plan_decode: seq_len[%d] = %d outside [0, %d]", b, seq_len[b], lay->max_seq);
+
+  const int H = lay->H, W = pr->n_workers;
+  const int64_t G = pr->granule;
+  const int32_t* rk = &lay->rk[(size_t)layer * H];
+  const int32_t* rv = &lay->rv[(size_t)layer * H];
+  std::vector<int64_t> d_sum(H);
+  int64_t d_max = 0;
+  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + 1, d_max = std::max(d_max, d_sum[h]);
+  int64_t total = 0;
+  for (int b = 0; b < batch; ++b)
+    for (int h = 0; h < H; ++h) total += seq_len[b] * d_sum[h];
+
+  // chunks: every non-empty unit cut into min_split near-equal, granule-aligned parts
+  struct Chunk { int32_t b, h, t0, t1; int64_t cost; };
+  std::vector<Chunk> chunks;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t S = seq_len[b];
+    if (S == 0) continue;
+    for (int h = 0; h < H; ++h) {
+      int64_t n = std::max<int64_t>(1, std::min<int64_t>(pr->min_split, ceil_div(S, G)));
+      const int64_t size = round_up(ceil_div(S, n), G);
+      n = ceil_div(S, size);
+      for (int64_t j = 0; j < n; ++j) {
+        const int64_t t0 = j * size, t1 = std::min(S, (j + 1) * size);
+        chunks.push_back({b, h, (int32_t)t0, (int32_t)t1, (t1 - t0) * d_sum[h]});
+      }
+    }
+  }
+  std::vector<int32_t> order(chunks.size());
+  std::iota(order.begin(), order.end(), 0);
+  std::sort(order.begin(), order.end(), [&](int32_t a, int32_t c) {
+    return chunks[a].cost != chunks[c].cost ? chunks[a].cost > chunks[c].cost : a < c;
+  });
+
+  // list scheduling with the per-worker mean-load fill
+  struct Piece { int32_t b, h, t0, t1, w; };
+  std::vector<Piece> pieces;
+  const int64_t mean = ceil_div(total, W);
+  LoadHeap heap = empty_workers(W);
+  for (int32_t ci : order) {
+    const Chunk& c = chunks[ci];
+    int64_t t0 = c.t0;
+    while (t0 < c.t1) {
+      Load top = heap.top();
+      heap.pop();
+      int64_t take = c.t1 - t0;
+      if (pr->split) {
+        const int64_t room = mean - top.first, step = G * d_sum[c.h];
+        const int64_t fit = std::max<int64_t>(1, (2 * room + step) / (2 * step)) * G;
+        take = std::min(take, fit);
+      }
+      pieces.push_back({c.b, c.h, (int32_t)t0, (int32_t)(t0 + take), top.second});
+      top.first += take * d_sum[c.h];
+      heap.push(top);
+      t0 += take;
+    }
+  }
+
+  // tiles = pieces numbered by (unit, t0)
+  const size_t n = pieces.size();
+  std::vector<int32_t> by_unit(n);
+  std::iota(by_unit.begin(), by_unit.end(), 0);
+  std::sort(by_unit.begin(), by_unit.end(), [&](int32_t a, int32_t c) {
+    const Piece &x = pieces[a], &y = pieces[c];
+    if (x.b != y.b) return x.b < y.b;
+    if (x.h != y.h) return x.h < y.h;
+    return x.t0 < y.t0;
+  });
+  std::vector<int32_t> tile_of_piece(n);
+  for (size_t tid = 0; tid < n; ++tid) tile_of_piece[by_unit[tid]] = (int32_t)tid;
+
+  fdc_plan* p = new (std::nothrow) fdc_plan();
+  if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: out of host memory");
+  p->kind = 0, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
+  p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer), p->total_q_rows = batch;
+  p->item_b.resize(n), p->item_h.resize(n), p->item_lo.resize(n), p->item_hi.resize(n), p->item_cost.resize(n);
+  p->unit_item_ptr.assign((size_t)p->n_units + 1, 0);
+  for (size_t tid = 0; tid < n; ++tid) {
+    const Piece& pc = pieces[by_unit[tid]];
+    p->item_b[tid] = pc.b, p->item_h[tid] = pc.h, p->item_lo[tid] = pc.t0, p->item_hi[tid] = pc.t1;
+    p->item_cost[tid] = (int64_t)(pc.t1 - pc.t0) * d_sum[pc.h];
+    p->unit_item_ptr[(size_t)pc.b * H + pc.h + 1] += 1;
+  }
+  for (int u = 0; u < p->n_units; ++u) p->unit_item_ptr[u + 1] += p->unit_item_ptr[u];
+  std::vector<std::vector<int32_t>> lists(W);
+  p->worker_load.assign(W, 0);
+  for (size_t k = 0; k < n; ++k) {  // pieces are in hand-out order
+    lists[pieces[k].w].push_back(tile_of_piece[k]);
+    p->worker_load[pieces[k].w] += (int64_t)(pieces[k].t1 - pieces[k].t0) * d_sum[pieces[k].h];
+  }
+  worker_csr(lists, p);
+
+  // device image
+  const int64_t* koff = &lay->koff[(size_t)layer * H];
+  const int64_t* voff = &lay->voff[(size_t)layer * H];
+  const int32_t* koff_r = &lay->koff_r[(size_t)layer * (H + 1)];
+  const int32_t* voff_r = &lay->voff_r[(size_t)layer * (H + 1)];
+  std::vector<DecTile> tiles(n);
+  for (size_t tid = 0; tid < n; ++tid) {
+    const int b = p->item_b[tid], h = p->item_h[tid];
+    const int u = b * H + h;
+    DecTile& t = tiles[tid];
+    std::memset(&t, 0, sizeof(t));
+    t.k_elem = (int64_t)b * lay->max_seq * p->RK + koff[h] + (int64_t)p->item_lo[tid] * rk[h];
+    t.v_elem = (int64_t)b * lay->max_seq * p->RV + voff[h] + (int64_t)p->item_lo[tid] * rv[h];
+    t.len = p->item_hi[tid] - p->item_lo[tid];
+    t.q_elem = b * p->RK + koff_r[h];
+    t.o_elem = b * p->RV + voff_r[h];
+    t.rk_rv = rk[h] | (rv[h] << 16);
+    t.slot = (p->unit_item_ptr[u + 1] - p->unit_item_ptr[u] == 1) ? -1 : (int32_t)tid;
+  }
+  std::vector<DecUnit> units(p->n_units);
+  for (int u = 0; u < p->n_units; ++u) {
+    const int b = u / H, h = u % H;
+    units[u] = {p->unit_item_ptr[u], p->unit_item_ptr[u + 1], b * p->RV + voff_r[h], rv[h]};
+  }
+  p->off_items = append_aligned(p->image, tiles.data(), tiles.size());
+  p->off_units = append_aligned(p->image, units.data(), units.size());
+  p->off_worker_ptr = append_aligned(p->image, p->worker_ptr.data(), p->worker_ptr.size());
+  p->off_worker_items = append_aligned(p->image, p->worker_items.data(), p->worker_items.size());
+  p->off_partials = (p->image.size() + 255) / 256 * 256;
+  p->partial_bytes = std::max<size_t>(n, 1) * kPartialStride * sizeof(float);
+  p->workspace_bytes = p->off_partials + p->partial_bytes;
+  *out = p;
+  return FDC_OK;
+}
+
+fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
+                            const int32_t* kv_len, const fdc_plan_params* pr, fdc_plan** out) {
+  fdc_status st = check_plan_args("fdc_plan_prefill", lay, layer, batch, q_len, pr, out);
+  if (st != FDC_OK) return st;
+  if (!kv_len) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: kv_len is NULL");
+  if (pr->br_base <= 0 || pr->br_cap < 16 || pr->br_cap % 16 != 0)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: br_base must be positive and br_cap a positive multiple of 16");
+  if (pr->cost_mode != 0 && pr->cost_mode != 1) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: cost_mode %d", pr->cost_mode);
+  for (int b = 0; b < batch; ++b)
+    if (q_len[b] < 0 || kv_len[b] < q_len[b] || kv_len[b] > lay->max_seq)
+      FDC_FAIL(FDC_BAD_SHAPE, "fdc_plan_prefill: need 0 <= q_len[%d]=%d <= kv_len=%d <= %d", b, q_len[b], kv_len[b],
+               lay->max_seq);
+
+  const int H = lay->H, W = pr->n_workers;
+  const int32_t* rk = &lay->rk[(size_t)layer * H];
+  const int32_t* rv = &lay->rv[(size_t)layer * H];
+  std::vector<int64_t> d_sum(H);
+  int64_t d_max = 0;
+  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + 1, d_max = std::max(d_max, d_sum[h]);
+
+  fdc_plan* p = new (std::nothrow) fdc_plan();
+  if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: out of host memory");
+  p->kind = 1, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
+  p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
+  p->br.resize(H);
+  for (int h = 0; h < H; ++h)
+    p->br[h] = (int32_t)std::min<int64_t>(pr->br_cap, round_up(ceil_div((int64_t)pr->br_base * d_max, d_sum[h]), 16));
+
+  struct Task { int32_t b, h, q0, q1; };
+  std::vector<Task> tasks;
+  for (int b = 0; b < batch; ++b)
+    for (int h = 0; h < H; ++h)
+      for (int32_t q0 = 0; q0 < q_len[b]; q0 += p->br[h]) tasks.push_back({b, h, q0, std::min(q_len[b], q0 + p->br[h])});
+
+  auto cost_of = [&](const Task& t) -> int64_t {
+    const int64_t rows = t.q1 - t.q0;
+    if (pr->cost_mode == 0) return rows * kv_len[t.b] * d_sum[t.h];
+    // sum over rows i in [q0, q1) of (kv_len - q_len + i + 1)
+    const int64_t first = (int64_t)kv_len[t.b] - q_len[t.b] + t.q0 + 1, last = (int64_t)kv_len[t.b] - q_len[t.b] + t.q1;
+    return (first + last) * rows / 2 * d_sum[t.h];
+  };
+
+  std::vector<std::vector<int32_t>> lists(W);
+  p->worker_load.assign(W, 0);
+  if (pr->cost_mode == 1) {
+    std::vector<int64_t> cost(tasks.size());
+    for (size_t i = 0; i < tasks.size(); ++i) cost[i] = cost_of(tasks[i]);
+    std::vector<int32_t> order(tasks.size());
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(),
+              [&](int32_t a, int32_t c) { return cost[a] != cost[c] ? cost[a] > cost[c] : a < c; });
+    LoadHeap heap = empty_workers(W);
+    for (int32_t i : order) {
+      Load top = heap.top();
+      heap.pop();
+      lists[top.second].push_back(i);
+      top.first += cost[i];
+      p->worker_load[top.second] += cost[i];
+      heap.push(top);
+    }
+  } else {
+    const size_t n_tasks = tasks.size(), n_last = n_tasks % W, full = n_tasks - n_last;
+    for (size_t i = 0; i < full; ++i) {
+      lists[i % W].push_back((int32_t)i);
+      p->worker_load[i % W] += cost_of(tasks[i]);
+    }
+    if (n_last > 0) {
+      int64_t sum = 0;
+      for (size_t i = full; i < n_tasks; ++i) sum += (int64_t)(tasks[i].q1 - tasks[i].q0) * d_sum[tasks[i].h];
+      const int64_t wl = ceil_div(sum, W);
+      std::vector<Task> resplit;
+      for (size_t i = full; i < n_tasks; ++i) {
+        const Task& t = tasks[i];
+        const int32_t nb = (int32_t)std::max<int64_t>(16, wl / d_sum[t.h] / 16 * 16);
+        for (int32_t s = t.q0; s < t.q1; s += nb) resplit.push_back({t.b, t.h, s, std::min(t.q1, s + nb)});
+      }
+      tasks.resize(full);
+      tasks.insert(tasks.end(), resplit.begin(), resplit.end());
+      LoadHeap heap = empty_workers(W);
+      for (size_t j = 0; j < resplit.size(); ++j) {
+        Load top = heap.top();
+        heap.pop();
+        const int64_t c = cost_of(resplit[j]);
+        lists[top.second].push_back((int32_t)(full + j));
+        top.first += c;
+        p->worker_load[top.second] += c;
+        heap.push(top);
+      }
+    }
+  }
+  const size_t n = tasks.size();
+  p->item_b.resize(n), p->item_h.resize(n), p->item_lo.resize(n), p->item_hi.resize(n), p->item_cost.resize(n);
+  for (size_t i = 0; i < n; ++i) {
+    p->item_b[i] = tasks[i].b, p->item_h[i] = tasks[i].h, p->item_lo[i] = tasks[i].q0, p->item_hi[i] = tasks[i].q1;
+    p->item_cost[i] = cost_of(tasks[i]);
+  }
+  worker_csr(lists, p);
+
+  // device image
+  const int64_t* koff = &lay->koff[(size_t)layer * H];
+  const int64_t* voff = &lay->voff[(size_t)layer * H];
+  const int32_t* koff_r = &lay->koff_r[(size_t)layer * (H + 1)];
+  const int32_t* voff_r = &lay->voff_r[(size_t)layer * (H + 1)];
+  std::vector<int64_t> row0(batch + 1, 0);
+  for (int b = 0; b < batch; ++b) row0[b + 1] = row0[b] + q_len[b];
+  p->total_q_rows = row0[batch];
+  std::vector<PreTask> pt(n);
+  for (size_t i = 0; i < n; ++i) {
+    const Task& t = tasks[i];
+    PreTask& d = pt[i];
+    std::memset(&d, 0, sizeof(d));
+    d.k_elem = (int64_t)t.b * lay->max_seq * p->RK + koff[t.h];
+    d.v_elem = (int64_t)t.b * lay->max_seq * p->RV + voff[t.h];
+    d.q_elem = (row0[t.b] + t.q0) * p->RK + koff_r[t.h];
+    d.o_elem = (row0[t.b] + t.q0) * p->RV + voff_r[t.h];
+    d.rows = t.q1 - t.q0;
+    d.pos0 = kv_len[t.b] - q_len[t.b] + t.q0;
+    d.kv_len = kv_len[t.b];
+    d.rk_rv = rk[t.h] | (rv[t.h] << 16);
+    d.ldq = p->RK, d.ldo = p->RV;
+  }
+  p->off_items = append_aligned(p->image, pt.data(), pt.size());
+  p->off_units = p->off_items;
+  p->off_worker_ptr = append_aligned(p->image, p->worker_ptr.data(), p->worker_ptr.size());
+  p->off_worker_items = append_aligned(p->image, p->worker_items.data(), p->worker_items.size());
+  p->off_partials = (p->image.size() + 255) / 256 * 256;
+  p->partial_bytes = 0;
+  p->workspace_bytes = p->off_partials + 256;
+  *out = p;
+  return FDC_OK;
+}
+
+fdc_status fdc_plan_export(const fdc_plan* p, fdc_plan_tables* o) {
+  if (!p || !o) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_export: NULL argument");
+  o->kind = p->kind;
+  o->n_items = (int32_t)p->item_b.size();
+  o->n_workers = p->n_workers;
+  o->n_units = p->n_units;
+  o->item_b = p->item_b.data(), o->item_h = p->item_h.data();
+  o->item_lo = p->item_lo.data(), o->item_hi = p->item_hi.data();
+  o->item_cost = p->item_cost.data();
+  o->unit_item_ptr = p->kind == 0 ? p->unit_item_ptr.data() : nullptr;
+  o->worker_ptr = p->worker_ptr.data(), o->worker_items = p->worker_items.data();
+  o->worker_load = p->worker_load.data();
+  o->br = p->kind == 1 ? p->br.data() : nullptr;
+  return FDC_OK;
+}
+
+size_t fdc_plan_workspace_bytes(const fdc_plan* p) { return p ? p->workspace_bytes : 0; }
+
+void fdc_plan_destroy(fdc_plan* p) { delete p; }
+
+}  // extern "C"

@@ -1,0 +1,102 @@
+// Internal declarations shared by the host side and the kernels of libfdc.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "fdc.h"
+
+namespace fdc {
+
+// ---- error text ---------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+#define FDC_FAIL(code, ...)        \
+  do {                             \
+    ::fdc::set_error(__VA_ARGS__); \
+    return (code);                 \
+  } while (0)
+
+#define FDC_HIP_CHECK(expr)                                                        \
+  do {                                                                             \
+    hipError_t e_ = (expr);                                                        \
+    if (e_ != hipSuccess) FDC_FAIL(FDC_HIP_ERROR, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- device-side descriptors (plain structs copied into the workspace) ----------------------
+
+// One decode tile: a token range of one (sequence, head) unit. 48 bytes.
+struct DecTile {
+  int64_t k_elem;   // element offset of the tile's first K' row inside the layer's K' buffer
+  int64_t v_elem;   // same for V'
+  int32_t len;      // tokens in the tile (> 0)
+  int32_t q_elem;   // element offset of q'_h in q_lat  (b * RK + koff_r[h])
+  int32_t o_elem;   // element offset of o'_h in o_lat  (b * RV + voff_r[h])
+  int32_t rk_rv;    // rk | rv << 16
+  int32_t slot;     // partial-state slot, or -1: the unit has one tile, write the normalised output
+  int32_t pad[3];
+};
+static_assert(sizeof(DecTile) == 48, "DecTile layout");
+
+// One (sequence, head) unit for the split-K merge. 16 bytes.
+struct DecUnit {
+  int32_t tile_begin, tile_end;  // partial slots of the unit
+  int32_t o_elem;
+  int32_t rv;
+};
+
+// Partial state of a tile: m, l, 2 pad floats, acc[rv <= 128].
+constexpr int kPartialStride = 132;
+
+// One prefill task: query rows [q0, q1) of one (sequence, head) unit. 64 bytes.
+struct PreTask {
+  int64_t k_elem;    // element offset of the unit's first K' row
+  int64_t v_elem;
+  int64_t q_elem;    // element offset of (row q0, head column 0) in q_lat [T, RK]
+  int64_t o_elem;    // element offset of (row q0, head column 0) in o_lat [T, RV]
+  int32_t rows;      // q1 - q0
+  int32_t pos0;      // absolute position of row q0 in the sequence (kv_len - q_len + q0)
+  int32_t kv_len;    // keys of the sequence
+  int32_t rk_rv;     // rk | rv << 16
+  int32_t ldq;       // RK (row stride of q_lat)
+  int32_t ldo;       // RV
+  int32_t pad[2];
+};
+static_assert(sizeof(PreTask) == 64, "PreTask layout");
+
+}  // namespace fdc
+
+// ---- host objects ---------------------------------------------------------------------------
+struct fdc_layout {
+  int L, H, d_model, d_head, max_batch, max_seq;
+  fdc_dtype dtype;
+  int elem_size;
+  std::vector<int32_t> rk, rv;          // [L*H]
+  std::vector<int32_t> koff_r, voff_r;  // [L*(H+1)]
+  std::vector<int64_t> koff, voff;      // [L*H]
+  std::vector<int64_t> k_elems, v_elems;  // [L]
+  int RK(int l) const { return koff_r[(size_t)l * (H + 1) + H]; }
+  int RV(int l) const { return voff_r[(size_t)l * (H + 1) + H]; }
+};
+
+struct fdc_plan {
+  int kind;  // 0 decode, 1 prefill
+  int layer, batch, H, n_workers, n_units;
+  const fdc_layout* lay;  // identity check only (the plan copies what it needs)
+  int RK, RV;
+  int64_t total_q_rows;   // prefill: T
+  // exported tables
+  std::vector<int32_t> item_b, item_h, item_lo, item_hi, unit_item_ptr, worker_ptr, worker_items, br;
+  std::vector<int64_t> item_cost, worker_load;
+  // device image: packed tables, copied verbatim by fdc_plan_upload
+  std::vector<unsigned char> image;
+  size_t off_items, off_units, off_worker_ptr, off_worker_items;  // byte offsets inside image
+  size_t off_partials, partial_bytes;                             // decode only, after the image
+  size_t workspace_bytes;
+};

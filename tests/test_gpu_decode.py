@@ -1,0 +1,196 @@
+"""GPU parity of fdc_latent_attn_decode (tile kernel + split-K merge) against the float64 oracle,
+element by element, on identical stored inputs (the oracle reads back the cache's bf16 / fp32
+bits and the fp32 q').
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_04107_amd as fdc
+from oracle import attention as oa
+from tests.gpu_util import Cache, assert_close, workspace_for
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+
+# fp32 accumulation of identical inputs: far below the bf16-storage tolerance. The tests assert the
+# spec tolerance AND this tighter bound (rounding of an S-term fp32 sum, S <= 131072).
+TIGHT_REL_L2 = 5e-5
+
+
+def say(msg):
+    print(f"[decode-parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def run_decode(rk, rv, seq, W, dtype=fdc.FDC_BF16, min_split=1, split=1, granule=64, q_gain=1.0, seed=0,
+               d_head=128, decay=32.0, check_units=None, device_fill=False):
+    H, B = len(rk), len(seq)
+    S_max = max(max(seq), 1)
+    lay = fdc.Layout(1, H, 256, d_head, [rk], [rv], B, S_max, dtype)
+    cache = Cache(lay)
+    g = gen.make_rng(seed)
+    tg = torch.Generator(device="cuda:0").manual_seed(seed)
+    for b in range(B):
+        for h in range(H):
+            if seq[b] == 0:
+                continue
+            if device_fill:
+                for side, r in (("k", rk[h]), ("v", rv[h])):
+                    sig = torch.exp(-torch.arange(r, device="cuda:0", dtype=torch.float32) / decay)
+                    u = cache.unit(side, b, h)
+                    u[:seq[b]] = (torch.randn(seq[b], r, generator=tg, device="cuda:0") * sig).to(u.dtype)
+            else:
+                cache.fill_unit("k", b, h, gen.direct_latent(seq[b], rk[h], decay, g))
+                cache.fill_unit("v", b, h, gen.direct_latent(seq[b], rv[h], decay, g))
+    q_lat = torch.from_numpy((g.standard_normal((B, cache.RK)) * q_gain).astype(np.float32)).cuda()
+    o_lat = torch.full((B, cache.RV), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split, pp.split, pp.granule = W, min_split, split, granule
+    plan = fdc.fdc_plan_decode(lay, 0, seq, pp)
+    ws = workspace_for(plan)
+    scale = 1.0 / math.sqrt(d_head)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    out = o_lat.cpu().numpy().astype(np.float64)
+    qh = q_lat.cpu().numpy().astype(np.float64)
+    kr, vr = cache.t["koff_r"][0], cache.t["voff_r"][0]
+    units = check_units if check_units is not None else [(b, h) for b in range(B) for h in range(H)]
+    ref_all, got_all = [], []
+    for b, h in units:
+        K = cache.unit_f64("k", b, h, seq[b])
+        V = cache.unit_f64("v", b, h, seq[b])
+        ref = oa.latent_attn_decode(qh[b, kr[h]:kr[h + 1]], K, V, scale)
+        got = out[b, vr[h]:vr[h + 1]]
+        ref_all.append(ref), got_all.append(got)
+        assert_close(got, ref, f"unit b={b} h={h} rk={rk[h]} rv={rv[h]} S={seq[b]}", rel_l2_tol=TIGHT_REL_L2 * 4)
+    ma, rl = assert_close(np.concatenate(got_all), np.concatenate(ref_all), "all units", rel_l2_tol=TIGHT_REL_L2)
+    n_tiles = plan.export()["n_items"]
+    return ma, rl, n_tiles, (lay, plan, cache, q_lat, o_lat, ws, scale)
+
+
+MIX_K = [16, 32, 48, 64, 80, 96, 112, 128]
+MIX_V = [128, 16, 48, 64, 32, 112, 96, 80]
+
+
+@pytest.mark.parametrize("W,min_split,split", [(1, 1, 1), (7, 1, 1), (64, 1, 1), (1000, 1, 1), (5, 3, 0),
+                                               (64, 4, 1), (4096, 1, 1)])
+def test_decode_mixed_ranks_bf16(W, min_split, split):
+    say(f"mixed ranks bf16 W={W} min_split={min_split} split={split}")
+    ma, rl, n, _ = run_decode(MIX_K, MIX_V, [777, 64, 1300], W, min_split=min_split, split=split, seed=W)
+    say(f"  tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_ragged_and_empty_sequences():
+    say("ragged and empty sequences")
+    ma, rl, n, _ = run_decode(MIX_K, MIX_V, [0, 1, 63, 65, 300, 0, 31], 33, granule=16, seed=3)
+    say(f"  tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_all_sequences_empty_gives_zeros():
+    say("all sequences empty")
+    lay = fdc.Layout(1, 2, 256, 128, [[16, 64]], [[32, 16]], 2, 8, fdc.FDC_BF16)
+    cache = Cache(lay)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 8
+    plan = fdc.fdc_plan_decode(lay, 0, [0, 0], pp)
+    ws = workspace_for(plan)
+    q = torch.randn(2, cache.RK, device="cuda:0")
+    o = torch.full((2, cache.RV), float("nan"), device="cuda:0")
+    fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, 0.1, o, ws)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(o).item() == 0
+
+
+def test_decode_peaked_queries_make_max_abs_meaningful():
+    say("peaked queries (q x 8)")
+    ma, rl, n, st = run_decode(MIX_K, MIX_K, [2048, 500], 256, q_gain=8.0, seed=5)
+    o = st[4].abs().max().item()
+    say(f"  tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e} max|o|={o:.3f}")
+    assert o > 0.2          # outputs are O(1), so the absolute tolerance binds
+
+
+def test_decode_fp32_cache_config1_shape():
+    say("config 1 shape: fp32 cache, ranks 16..64, S=512")
+    wl = gen.CONFIGS["c1_tiny_decode_f32"]
+    r = wl.ranks()[0].tolist()
+    for W in (1, 16, 512):
+        ma, rl, n, _ = run_decode(r, r, [wl.context], W, dtype=fdc.FDC_F32, d_head=wl.d_head, decay=wl.decay, seed=0)
+        say(f"  W={W} tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e}")
+    # fp32 ranks up to 128 and rk != rv
+    run_decode(MIX_K, MIX_V, [300, 17], 40, dtype=fdc.FDC_F32, seed=2)
+
+
+def test_decode_is_deterministic():
+    say("determinism: two runs, bitwise equal")
+    _, _, _, (lay, plan, cache, q_lat, o_lat, ws, scale) = run_decode(MIX_K, MIX_V, [3000, 1500], 512, seed=9)
+    first = o_lat.clone()
+    o_lat.fill_(float("nan"))
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, o_lat)
+
+
+def _bench_workers():
+    return fdc.fdc_suggest_workers(0)
+
+
+def test_decode_config2_full_size_all_units():
+    wl = gen.CONFIGS["c2_uniform_decode"]
+    W = _bench_workers()
+    say(f"config 2 full size: B={wl.batch} S={wl.context} r=64, W={W}")
+    r = wl.ranks()[0].tolist()
+    ma, rl, n, _ = run_decode(r, r, [wl.context] * wl.batch, W, device_fill=True, seed=0)
+    say(f"  tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_config3_layer_sampled_units():
+    wl = gen.CONFIGS["c3_adaptive_decode"]
+    W = _bench_workers()
+    ranks = wl.ranks()
+    # the most skewed layer: largest max/mean rank
+    layer = int(np.argmax(ranks.max(axis=1) / ranks.mean(axis=1)))
+    r = ranks[layer].tolist()
+    say(f"config 3, layer {layer}: B={wl.batch} S={wl.context}, W={W}, ranks {sorted(set(r))}")
+    g = gen.make_rng(42)
+    units = {(int(b), int(h)) for b, h in zip(g.integers(0, wl.batch, 96), g.integers(0, wl.n_heads, 96))}
+    units |= {(0, int(np.argmax(r))), (wl.batch - 1, int(np.argmin(r)))}
+    ma, rl, n, _ = run_decode(r, r, [wl.context] * wl.batch, W, device_fill=True, seed=1,
+                              check_units=sorted(units))
+    say(f"  tiles={n} checked_units={len(units)} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_config4_long_context_split_256():
+    wl = gen.CONFIGS["c4_long_decode"]
+    W = _bench_workers()
+    r = wl.ranks()[0].tolist()
+    say(f"config 4: S={wl.context}, min_split={wl.min_split}, W={W}")
+    ma, rl, n, st = run_decode(r, r, [wl.context], W, min_split=wl.min_split, device_fill=True, seed=2)
+    per_unit = np.diff(st[1].export()["unit_item_ptr"])
+    assert per_unit.min() >= 256
+    say(f"  tiles={n} min chunks per head={per_unit.min()} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_argument_errors():
+    say("argument errors")
+    lay = fdc.Layout(1, 2, 256, 128, [[16, 64]], [[32, 16]], 2, 64, fdc.FDC_BF16)
+    cache = Cache(lay)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 8
+    plan = fdc.fdc_plan_decode(lay, 0, [64, 10], pp)
+    ws = workspace_for(plan)
+    q = torch.randn(2, cache.RK, device="cuda:0")
+    o = torch.empty(2, cache.RV, device="cuda:0")
+    with pytest.raises(fdc.FdcError) as e:
+        fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, 0.1, o, ws[:256])
+    assert e.value.status == -4                                       # FDC_WORKSPACE_TOO_SMALL
+    with pytest.raises(fdc.FdcError) as e:
+        fdc.fdc_latent_attn_decode(lay, plan, q.view(-1)[1:], cache.k, cache.v, 0.1, o, ws)
+    assert e.value.status == -3                                       # FDC_BAD_ALIGNMENT
+    other = fdc.Layout(1, 2, 256, 128, [[16, 64]], [[32, 16]], 2, 64, fdc.FDC_BF16)
+    with pytest.raises(fdc.FdcError) as e:
+        fdc.fdc_latent_attn_decode(other, plan, q, cache.k, cache.v, 0.1, o, ws)
+    assert e.value.status == -1

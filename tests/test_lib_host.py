@@ -1,0 +1,155 @@
+"""Host logic of libfdc against the oracle (no GPU): the library loads, exports every symbol the
+header declares, and its layout tables and planner tables are bit-exact with the integer oracle.
+No compute entry point is called here.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2408_04107_amd as fdc
+from oracle import layout as ol
+from oracle import planner as op
+from workloads import generators as gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fdc.h")).read()
+    declared = set(re.findall(r"\b(fdc_[a-z_0-9]+)\s*\(", header))
+    declared -= {"fdc_status"}
+    lib = fdc.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} is declared in include/fdc.h but not exported"
+    assert declared == set(fdc.EXPORTED_SYMBOLS)
+
+
+def _layout(ranks_k, ranks_v, B, S, d_head=128, d_model=256, dtype=None):
+    rk = np.atleast_2d(np.asarray(ranks_k, dtype=np.int32))
+    rv = np.atleast_2d(np.asarray(ranks_v, dtype=np.int32))
+    return fdc.Layout(rk.shape[0], rk.shape[1], d_model, d_head, rk, rv, B, S,
+                      fdc.FDC_BF16 if dtype is None else dtype)
+
+
+def test_layout_tables_bit_exact():
+    for seed in range(3):
+        ranks = gen.adaptive_ranks(4, 7, seed)
+        rv = gen.adaptive_ranks(4, 7, seed + 50)
+        lay = _layout(ranks, rv, 3, 1000)
+        t = lay.tables()
+        ok, ov = ol.layout_tables(ranks, 3, 1000), ol.layout_tables(rv, 3, 1000)
+        assert np.array_equal(t["koff"], ok["off"]) and np.array_equal(t["voff"], ov["off"])
+        assert np.array_equal(t["koff_r"], ok["off_r"]) and np.array_equal(t["voff_r"], ov["off_r"])
+        assert np.array_equal(t["k_bytes"], ok["elems"] * 2) and np.array_equal(t["v_bytes"], ov["elems"] * 2)
+    lay = _layout([[16, 64]], [[32, 16]], 2, 10, d_head=64, dtype=fdc.FDC_F32)
+    assert lay.tables()["k_bytes"].tolist() == [2 * 10 * 80 * 4]
+
+
+DEC_PAIRS = [("item_b", "tile_b"), ("item_h", "tile_h"), ("item_lo", "tile_t0"), ("item_hi", "tile_t1"),
+             ("item_cost", "tile_cost"), ("unit_item_ptr", "unit_tile_ptr"), ("worker_ptr", "worker_ptr"),
+             ("worker_items", "worker_tiles"), ("worker_load", "worker_load")]
+PRE_PAIRS = [("item_b", "task_b"), ("item_h", "task_h"), ("item_lo", "task_q0"), ("item_hi", "task_q1"),
+             ("item_cost", "task_cost"), ("worker_ptr", "worker_ptr"), ("worker_items", "worker_tasks"),
+             ("worker_load", "worker_load"), ("br", "br")]
+
+
+def _decode_case(rk, rv, seq, W, G, ms, split):
+    lay = _layout([rk], [rv], len(seq), max(max(seq), 1))
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.granule, pp.min_split, pp.split = W, G, ms, int(split)
+    got = fdc.fdc_plan_decode(lay, 0, seq, pp).export()
+    ref = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms, split=split)
+    for a, b in DEC_PAIRS:
+        assert got[a].dtype == ref[b].dtype and np.array_equal(got[a], ref[b]), (a, W, G, ms, split)
+
+
+def test_decode_plan_bit_exact_small_and_ragged():
+    rk, rv = [16, 112, 64, 32, 128], [48, 16, 64, 128, 128]
+    for seq in ([0, 1, 63, 64, 65, 1000, 0, 4097], [512], [0, 0], [7, 7, 7]):
+        for W, G, ms, split in [(7, 64, 1, True), (64, 64, 1, True), (5, 16, 3, True), (5, 64, 3, False),
+                                (3, 64, 1, False), (1, 64, 1, True), (300, 32, 2, True)]:
+            _decode_case(rk, rv, seq, W, G, ms, split)
+
+
+@pytest.mark.parametrize("name", ["c2_uniform_decode", "c3_adaptive_decode", "c4_long_decode"])
+@pytest.mark.parametrize("W", [1024, 4096])
+def test_decode_plan_bit_exact_benchmark_shapes(name, W):
+    wl = gen.CONFIGS[name]
+    r = wl.ranks()[min(3, wl.n_layers - 1)].tolist()
+    _decode_case(r, r, [wl.context] * wl.batch, W, 64, wl.min_split, True)
+
+
+def test_decode_plan_random_bit_exact():
+    g = gen.make_rng(77)
+    for _ in range(25):
+        H, B = int(g.integers(1, 9)), int(g.integers(1, 6))
+        rk = (16 * g.integers(1, 9, size=H)).tolist()
+        rv = (16 * g.integers(1, 9, size=H)).tolist()
+        seq = [int(x) for x in g.integers(0, 3000, size=B)]
+        _decode_case(rk, rv, seq, int(g.integers(1, 200)), int(g.choice([16, 32, 64, 128])),
+                     int(g.integers(1, 5)), bool(g.integers(0, 2)))
+
+
+def _prefill_case(rk, rv, q, kv, W, mode, base=64, cap=256):
+    lay = _layout([rk], [rv], len(q), max(max(kv), 1))
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = W, {"paper": 0, "causal": 1}[mode], base, cap
+    got = fdc.fdc_plan_prefill(lay, 0, q, kv, pp).export()
+    ref = op.plan_prefill(q, kv, rk, rv, W, br_base=base, br_cap=cap, cost_mode=mode)
+    for a, b in PRE_PAIRS:
+        assert got[a].dtype == ref[b].dtype and np.array_equal(got[a], ref[b]), (a, W, mode)
+
+
+@pytest.mark.parametrize("mode", ["paper", "causal"])
+def test_prefill_plan_bit_exact(mode):
+    _prefill_case([16, 48], [16, 48], [256], [256], 4, mode)
+    _prefill_case([16, 64, 32], [32, 64, 16], [0, 5, 130, 17], [0, 9, 130, 4000], 6, mode)
+    _prefill_case([128, 16, 96], [128, 16, 96], [1000, 333], [1000, 999], 256, mode, base=32, cap=128)
+    wl = gen.CONFIGS["c5_prefill"]
+    r = wl.ranks()[0].tolist()
+    _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 256, mode)
+    g = gen.make_rng(78)
+    for _ in range(10):
+        H, B = int(g.integers(1, 6)), int(g.integers(1, 4))
+        rk = (16 * g.integers(1, 9, size=H)).tolist()
+        rv = (16 * g.integers(1, 9, size=H)).tolist()
+        q = [int(x) for x in g.integers(0, 700, size=B)]
+        kv = [x + int(y) for x, y in zip(q, g.integers(0, 500, size=B))]
+        _prefill_case(rk, rv, q, kv, int(g.integers(1, 70)), mode)
+
+
+def test_error_codes_without_gpu():
+    with pytest.raises(fdc.FdcError) as e:
+        _layout([[16, 24]], [[16, 16]], 1, 8)
+    assert e.value.status == -5 and "multiple of 16" in str(e.value)      # FDC_UNSUPPORTED_RANK
+    with pytest.raises(fdc.FdcError) as e:
+        _layout([[16, 144]], [[16, 16]], 1, 8)
+    assert e.value.status == -5
+    with pytest.raises(fdc.FdcError) as e:
+        _layout([[16]], [[16]], 1, 8, d_head=100)
+    assert e.value.status == -2                                           # FDC_BAD_SHAPE
+    lay = _layout([[16, 32]], [[16, 32]], 2, 100)
+    pp = fdc.fdc_plan_params_default()
+    with pytest.raises(fdc.FdcError) as e:                                # n_workers not set
+        fdc.fdc_plan_decode(lay, 0, [10, 10], pp)
+    assert e.value.status == -1
+    pp.n_workers = 8
+    with pytest.raises(fdc.FdcError) as e:                                # longer than max_seq
+        fdc.fdc_plan_decode(lay, 0, [10, 101], pp)
+    assert e.value.status == -2
+    with pytest.raises(fdc.FdcError) as e:                                # more sequences than max_batch
+        fdc.fdc_plan_decode(lay, 0, [1, 1, 1], pp)
+    assert e.value.status == -2
+    with pytest.raises(fdc.FdcError) as e:
+        fdc.fdc_plan_decode(lay, 1, [1, 1], pp)
+    assert e.value.status == -2
+    with pytest.raises(fdc.FdcError) as e:                                # q_len > kv_len
+        fdc.fdc_plan_prefill(lay, 0, [5, 5], [5, 4], pp)
+    assert e.value.status == -2
+    plan = fdc.fdc_plan_decode(lay, 0, [100, 3], pp)
+    assert plan.workspace_bytes() % 4 == 0 and plan.workspace_bytes() > 0
+    d = fdc.fdc_plan_params_default()
+    assert (d.granule, d.min_split, d.split, d.br_base, d.br_cap, d.cost_mode) == (64, 1, 1, 64, 256, 0)
