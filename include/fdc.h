@@ -192,6 +192,12 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
                                   const void* k_cache, const void* v_cache, float scale, void* o_lat,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid: when both arguments are non-NULL hipEvent_t handles, the next
+ * fdc_latent_attn_decode call made by this thread records `start` immediately before and `stop`
+ * immediately after its tile kernel (the kernel that streams the cache; the split-K merge runs
+ * after `stop`), on that call's stream. The request is consumed by that call; NULLs cancel it. */
+fdc_status fdc_profile_decode_events(void* start_event, void* stop_event);
+
 /* Prefill attention on the latent cache (Section 5, step 7; Section 5.3 prefill scheduling).
  *   q_lat [T, RK] bf16 and o_lat [T, RV] bf16, rows stacked b-major as in fdc_plan_prefill;
  *   causal != 0: query at position p sees keys t <= p. BF16 layouts only. */

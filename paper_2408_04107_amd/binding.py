@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_prefill",
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
-    "fdc_latent_attn_prefill", "fdc_absorb_output",
+    "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events",
 ]
 
 
@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
         l.fdc_latent_attn_decode.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
+        l.fdc_profile_decode_events.argtypes = [vp, vp]
         _lib = l
     return _lib
 
@@ -258,3 +259,8 @@ def fdc_absorb_output(layout: Layout, layer: int, mode: int, Bv, Wo, M, o_lat, o
                       y_dtype: int, stream=None) -> None:
     _check(lib().fdc_absorb_output(layout.handle, layer, mode, _dev(Bv), _dev(Wo), _dev(M), _dev(o_lat),
                                    o_lat_dtype, int(T), _dev(y), y_dtype, _stream(stream)))
+
+
+def fdc_profile_decode_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    _check(lib().fdc_profile_decode_events(start_event, stop_event))

@@ -16,6 +16,8 @@
 // them.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "fdc_internal.h"
 
 namespace fdc {
@@ -324,7 +326,17 @@ __global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecUn
 
 using namespace fdc;
 
+static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
 extern "C" {
+
+fdc_status fdc_profile_decode_events(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr))
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_profile_decode_events: pass two events or two NULLs");
+  g_prof_start = static_cast<hipEvent_t>(start_event);
+  g_prof_stop = static_cast<hipEvent_t>(stop_event);
+  return FDC_OK;
+}
 
 fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
   if (!n_workers) FDC_FAIL(FDC_INVALID_ARG, "fdc_suggest_workers: NULL argument");
@@ -338,7 +350,10 @@ fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
                                                                kWavesPerBlock * 64, 0));
     *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
   } else if (kind == 1) {
-    *n_workers = prop.multiProcessorCount;
+    int nb = 0;
+    fdc_status st = prefill_blocks_per_cu(&nb);
+    if (st != FDC_OK) return st;
+    *n_workers = prop.multiProcessorCount * std::max(nb, 1);
   } else {
     FDC_FAIL(FDC_INVALID_ARG, "fdc_suggest_workers: kind %d", kind);
   }
@@ -379,7 +394,10 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
   const float scale_log2 = scale * kLog2e;
+  hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
   if (!plan->item_b.empty()) {
+    if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
     if (lay->dtype == FDC_BF16)
       hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, tiles, wptr, witems,
                          static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
@@ -389,6 +407,7 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
                          static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),
                          static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
     FDC_HIP_CHECK(hipGetLastError());
+    if (ev1) FDC_HIP_CHECK(hipEventRecord(ev1, st));
   }
   hipLaunchKernelGGL(decode_merge_kernel, dim3(plan->n_units), dim3(kMergeThreads), 0, st, units, partials,
                      static_cast<float*>(o_lat));

@@ -70,6 +70,9 @@ struct PreTask {
 };
 static_assert(sizeof(PreTask) == 64, "PreTask layout");
 
+// Resident workgroups per compute unit of the prefill kernel (occupancy query).
+fdc_status prefill_blocks_per_cu(int* nb);
+
 }  // namespace fdc
 
 // ---- host objects ---------------------------------------------------------------------------

@@ -1,11 +1,304 @@
-// Causal prefill attention on the latent cache: placeholder until the MFMA kernel lands.
+// Causal prefill attention on the latent cache (Section 5, step 7; Section 5.3 prefill: Q-block
+// tasks of equalised cost handed to workers).
+//
+// Design for gfx950. A worker is one workgroup of four waves; it walks the Q-block tasks the
+// planner gave it. A task is processed in passes of 128 query rows, 32 rows (two 16-row MFMA
+// tiles) per wave. K' and V' blocks of 64 tokens are staged through LDS once per workgroup: K'
+// row-major (rank padded to a multiple of 32 with zeros), V' transposed so that both MFMA
+// operands are read with vector LDS loads. All products are transposed ones,
+//     S^T = K' Q'^T          (A = K' rows,   B = Q' rows)      v_mfma_f32_16x16x32_bf16
+//     O^T = V'^T P^T         (A = V'^T rows, B = P^T)          v_mfma_f32_16x16x32_bf16
+// because then every quantity a lane holds belongs to ONE query row (column l%16 of the MFMA
+// output): the score tile comes out of the first product already in the operand layout of the
+// second (no LDS round trip for P), the running max / sum live in the lanes that use them, and
+// the rescale of O needs no cross-lane traffic. The k index of the second product (tokens) is
+// spread over lanes in the order the first product delivers it; both operands use the same order.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "fdc_internal.h"
 
+namespace fdc {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kPreThreads = 256;
+constexpr int BC = 64;                   // tokens per K'/V' block
+constexpr int kRowsPerWave = 32;         // two MFMA row tiles
+constexpr int kRowsPerPass = 128;        // four waves
+constexpr int kKPad = 8, kVPad = 8;      // LDS row padding in elements
+constexpr float kLog2eP = 1.4426950408889634f;
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
+  a += 0x7fffu + ((a >> 16) & 1u);
+  b += 0x7fffu + ((b >> 16) & 1u);
+  return (a >> 16) | (b & 0xffff0000u);
+}
+
+union Frag {
+  u32x4 u;
+  bf16x8 v;
+};
+
+// One instantiation serves every rank: the k-steps of the score product (ceil(rk / 32) <= 4) and
+// the column tiles of the output (rv / 16 <= 8) are fully unrolled loops with wave-uniform guards,
+// so register arrays keep compile-time indices and narrow heads skip the unused steps.
+constexpr int RK32 = 4, RV16 = 8;
+__device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* __restrict__ q_lat,
+                                             const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+                                             float scale_log2, int causal, uint16_t* __restrict__ o_lat,
+                                             uint16_t* lds_k, uint16_t* lds_vt) {
+  constexpr int KROW = 128 + kKPad;       // LDS row length of the K' tile
+  constexpr int VROW = BC + kVPad;        // LDS row length of the V'^T tile
+  const int rk = t.rk_rv & 0xffff, rv = t.rk_rv >> 16;
+  const int rk32 = (rk + 31) / 32, rv16 = rv / 16;
+  const int RKP = rk32 * 32;              // rank of the K' rows in LDS, padded with zeros
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const uint16_t* kbase = kc + t.k_elem;
+  const uint16_t* vbase = vc + t.v_elem;
+
+  // zero the rank padding of the K' tile once: staging never writes those columns
+  if (RKP != rk) {
+    for (int i = tid; i < BC * (RKP - rk); i += kPreThreads) {
+      const int r = i / (RKP - rk), c = rk + i % (RKP - rk);
+      lds_k[r * KROW + c] = 0;
+    }
+  }
+
+  const int k_chunks = BC * rk / 8, v_chunks = BC * rv / 8;  // 16-byte chunks per block
+  constexpr int kMaxChunks = (BC * 128 / 8 + kPreThreads - 1) / kPreThreads;  // 4
+
+  for (int r0 = 0; r0 < t.rows; r0 += kRowsPerPass) {
+    const int pass_rows = min(kRowsPerPass, t.rows - r0);
+    const int wrow0 = r0 + wave * kRowsPerWave;  // first row of this wave inside the task
+    // Q' fragments (B operand): lane (ln, lg) holds 8 consecutive k of query row 16 i + ln
+    Frag qf[2][RK32];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int row = wrow0 + 16 * i + ln;
+#pragma unroll
+      for (int ks = 0; ks < RK32; ++ks) {
+        const int col = 32 * ks + 8 * lg;
+        qf[i][ks].u = (ks < rk32 && row < t.rows && col < rk)
+                          ? *reinterpret_cast<const u32x4*>(q_lat + t.q_elem + (int64_t)row * t.ldq + col)
+                          : u32x4{0, 0, 0, 0};
+      }
+    }
+    f32x4 oacc[2][RV16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int c = 0; c < RV16; ++c) oacc[i][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    const int pos_base = t.pos0 + wrow0 + ln;  // absolute position of this lane's row in tile 0 (+16 for tile 1)
+
+    const int last_pos = t.pos0 + r0 + pass_rows - 1;
+    const int kv_end = causal ? min(t.kv_len, last_pos + 1) : t.kv_len;
+    const bool wave_on = wrow0 < t.rows;
+    const int wave_last_pos = t.pos0 + min(wrow0 + kRowsPerWave, t.rows) - 1;
+
+    // register staging of the next block
+    u32x4 kst[kMaxChunks], vst[kMaxChunks];
+    auto fetch = [&](int c0) {
+#pragma unroll
+      for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = tid + i * kPreThreads;
+        const int ktok = c0 + c / (rk / 8), vtok = c0 + c / (rv / 8);
+        kst[i] = (c < k_chunks && ktok < t.kv_len) ? *reinterpret_cast<const u32x4*>(kbase + (int64_t)c0 * rk + c * 8)
+                                                    : u32x4{0, 0, 0, 0};
+        vst[i] = (c < v_chunks && vtok < t.kv_len) ? *reinterpret_cast<const u32x4*>(vbase + (int64_t)c0 * rv + c * 8)
+                                                    : u32x4{0, 0, 0, 0};
+      }
+    };
+    auto stage = [&]() {
+#pragma unroll
+      for (int i = 0; i < kMaxChunks; ++i) {
+        const int c = tid + i * kPreThreads;
+        if (c < k_chunks) {
+          const int r = c / (rk / 8), col = (c % (rk / 8)) * 8;
+          *reinterpret_cast<u32x4*>(&lds_k[r * KROW + col]) = kst[i];
+        }
+        if (c < v_chunks) {
+          const int r = c / (rv / 8), col = (c % (rv / 8)) * 8;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            lds_vt[(col + 2 * e) * VROW + r] = (uint16_t)(vst[i][e] & 0xffffu);
+            lds_vt[(col + 2 * e + 1) * VROW + r] = (uint16_t)(vst[i][e] >> 16);
+          }
+        }
+      }
+    };
+
+    if (kv_end > 0) fetch(0);
+    for (int c0 = 0; c0 < kv_end; c0 += BC) {
+      __syncthreads();  // all waves are done reading the previous block
+      stage();
+      __syncthreads();
+      if (c0 + BC < kv_end) fetch(c0 + BC);
+      if (!wave_on || (causal && c0 > wave_last_pos)) continue;  // nothing visible for this wave (uniform)
+
+      // S^T tiles: st[j][i] = tokens 16 j .. of the block x query rows of tile i
+      f32x4 st[4][2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        st[j][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < RK32; ++ks) {
+          if (ks >= rk32) break;
+          Frag kf;
+          kf.u = *reinterpret_cast<const u32x4*>(&lds_k[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
+          st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][ks].v, st[j][0], 0, 0, 0);
+          st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][ks].v, st[j][1], 0, 0, 0);
+        }
+      }
+      // scale, mask, online softmax. Lane (ln, lg) holds tokens c0 + 16 j + 4 lg + e of row ln.
+      const bool need_mask = (causal && c0 + BC - 1 > t.pos0 + wrow0) || c0 + BC > t.kv_len;
+      Frag pf[2][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int pos = pos_base + 16 * i;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            float s = st[j][i][e] * scale_log2;
+            if (need_mask) {
+              const int tok = c0 + 16 * j + 4 * lg + e;
+              if ((causal && tok > pos) || tok >= t.kv_len) s = -INFINITY;
+            }
+            st[j][i][e] = s;
+            mx = fmaxf(mx, s);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run[i], mx);
+        // a row with nothing visible yet keeps m = -inf; use 0 as the reference to avoid inf - inf
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[i] - m_ref);
+        m_run[i] = m_new;
+        float psum = 0.f;
+        float p[4][4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            p[j][e] = __builtin_amdgcn_exp2f(st[j][i][e] - m_ref);
+            psum += p[j][e];
+          }
+        l_run[i] = l_run[i] * alpha + psum;
+#pragma unroll
+        for (int c = 0; c < RV16; ++c)
+          if (c < rv16) oacc[i][c] *= alpha;
+        // P^T operand of token pair-tiles (2 jp, 2 jp + 1): 8 bf16 per lane
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp) {
+          pf[i][jp].u[0] = pack_bf16(p[2 * jp][0], p[2 * jp][1]);
+          pf[i][jp].u[1] = pack_bf16(p[2 * jp][2], p[2 * jp][3]);
+          pf[i][jp].u[2] = pack_bf16(p[2 * jp + 1][0], p[2 * jp + 1][1]);
+          pf[i][jp].u[3] = pack_bf16(p[2 * jp + 1][2], p[2 * jp + 1][3]);
+        }
+      }
+      // O^T += V'^T P^T. A operand: lane (ln, lg) holds column 16 c + ln, tokens in the same order as P.
+#pragma unroll
+      for (int c = 0; c < RV16; ++c) {
+        if (c >= rv16) break;
+#pragma unroll
+        for (int jp = 0; jp < 2; ++jp) {
+          Frag vf;
+          const uint16_t* vrow = &lds_vt[(16 * c + ln) * VROW + 32 * jp + 4 * lg];
+          const u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
+          const u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 16);
+          vf.u = u32x4{lo[0], lo[1], hi[0], hi[1]};
+          oacc[0][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[0][jp].v, oacc[0][c], 0, 0, 0);
+          oacc[1][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[1][jp].v, oacc[1][c], 0, 0, 0);
+        }
+      }
+    }
+
+    // finish: l over the four lanes of a row, normalise, store. Lane (ln, lg) holds O[row ln][16 c + 4 lg + e].
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      float l = l_run[i];
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+      const float inv = l > 0.f ? 1.f / l : 0.f;
+      const int row = wrow0 + 16 * i + ln;
+      if (row < t.rows) {
+        uint16_t* orow = o_lat + t.o_elem + (int64_t)row * t.ldo;
+#pragma unroll
+        for (int c = 0; c < RV16; ++c) {
+          if (c >= rv16) break;
+          u32x2 w;
+          w[0] = pack_bf16(oacc[i][c][0] * inv, oacc[i][c][1] * inv);
+          w[1] = pack_bf16(oacc[i][c][2] * inv, oacc[i][c][3] * inv);
+          *reinterpret_cast<u32x2*>(orow + 16 * c + 4 * lg) = w;
+        }
+      }
+    }
+  }
+  __syncthreads();  // the next task may use another LDS tile geometry
+}
+
+__global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(const PreTask* __restrict__ tasks,
+                                                              const int32_t* __restrict__ worker_ptr,
+                                                              const int32_t* __restrict__ worker_items,
+                                                              const uint16_t* __restrict__ q_lat,
+                                                              const uint16_t* __restrict__ kc,
+                                                              const uint16_t* __restrict__ vc, float scale_log2,
+                                                              int causal, uint16_t* __restrict__ o_lat) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[BC * (128 + kKPad)];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_vt[128 * (BC + kVPad)];
+  const int w = blockIdx.x;
+  const int i0 = worker_ptr[w], i1 = worker_ptr[w + 1];
+  for (int it = i0; it < i1; ++it) {
+    const PreTask t = tasks[worker_items[it]];
+    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, lds_k, lds_vt);
+  }
+}
+
+fdc_status prefill_blocks_per_cu(int* nb) {
+  FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(nb, prefill_kernel, kPreThreads, 0));
+  return FDC_OK;
+}
+
+}  // namespace fdc
+
 using namespace fdc;
 
-extern "C" fdc_status fdc_latent_attn_prefill(const fdc_layout*, const fdc_plan*, const void*, const void*,
-                                              const void*, float, int, void*, void*, size_t, void*) {
-  FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: kernel not built in this library");
+extern "C" {
+
+fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat, const void* k_cache,
+                                   const void* v_cache, float scale, int causal, void* o_lat, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: NULL argument");
+  if (plan->kind != 1 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: not a prefill plan of this layout");
+  if (lay->dtype != FDC_BF16) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_prefill: bf16 layouts only");
+  if (workspace_bytes < plan->workspace_bytes)
+    FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_latent_attn_prefill: workspace has %zu bytes, the plan needs %zu",
+             workspace_bytes, plan->workspace_bytes);
+  if (!aligned16(q_lat) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(o_lat) ||
+      (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_latent_attn_prefill: pointers must be 16-byte aligned (workspace 256)");
+  if (plan->item_b.empty()) return FDC_OK;
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  hipLaunchKernelGGL(prefill_kernel, dim3(plan->n_workers), dim3(kPreThreads), 0, static_cast<hipStream_t>(stream),
+                     reinterpret_cast<const PreTask*>(ws + plan->off_items),
+                     reinterpret_cast<const int32_t*>(ws + plan->off_worker_ptr),
+                     reinterpret_cast<const int32_t*>(ws + plan->off_worker_items),
+                     static_cast<const uint16_t*>(q_lat), static_cast<const uint16_t*>(k_cache),
+                     static_cast<const uint16_t*>(v_cache), scale * kLog2eP, causal,
+                     static_cast<uint16_t*>(o_lat));
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
 }
+
+}  // extern "C"
