@@ -1,0 +1,361 @@
+#!/usr/bin/env python3
+"""Benchmark of the latent-KV attention hot path on one MI355X.
+
+Default workload: the adaptive-rank decode configuration (32 layers x 32 heads, d_head 128,
+per-(layer, head) rank drawn from {16..128} with P(r) ~ 1/r, batch 16, context 8192, bf16 cache).
+One step = one decode step through all layers: latent projection of the new token, query
+absorption, decode attention on the latent cache (tile kernel + split-K merge) and output
+absorption. Inputs are synthetic, seeded, and resident in HBM before the timed region.
+
+Prints ONE JSON line. `value` is the algorithmic HBM bytes of a whole step divided by the step
+time; `roofline` describes the dominant kernel (the decode tile kernel) from HIP events recorded
+around that kernel alone; `cpu_baseline` is the float64 oracle timed on the host on a bounded
+sample; `prefill` reports the MFMA calls of the prefill configuration in TFLOP/s.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+class HipEvents:
+    """hipEvent_t handles through the HIP runtime torch already loaded."""
+
+    def __init__(self, n: int):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.ev = []
+        for _ in range(n):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            if rc != 0:
+                raise RuntimeError(f"hipEventCreate failed: {rc}")
+            self.ev.append(e)
+
+    def ms(self, i: int, j: int) -> float:
+        out = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(out), self.ev[i], self.ev[j])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(out.value)
+
+    def destroy(self):
+        for e in self.ev:
+            self.hip.hipEventDestroy(e)
+        self.ev = []
+
+
+def fill_latent(buf, lay, tables_off_r, ranks, batch, S, decay, gen_t):
+    """Fills a layer buffer [b][h][t][i] with N(0, s_i^2), s_i = exp(-i / decay): the value
+    distribution of projected hidden states x ~ N(0, I) through a weight with that spectrum."""
+    import torch
+    R = int(tables_off_r[-1])
+    sig = torch.cat([torch.exp(-torch.arange(int(r), device=buf.device, dtype=torch.float32) / decay).repeat(S)
+                     for r in ranks])                       # one sequence: [S * R] in layout order
+    view = buf.view(batch, S * R)
+    for b in range(batch):
+        view[b] = (torch.randn(S * R, generator=gen_t, device=buf.device) * sig).to(buf.dtype)
+
+
+def decode_bytes(plan_tables, ranks_k, ranks_v, seq_len, RK, RV, batch):
+    """Algorithmic bytes of one decode launch: every cached element once (bf16), q' in, o' or the
+    partial state out."""
+    kv = sum(int(s) * (int(rk) + int(rv)) * 2 for s in seq_len for rk, rv in zip(ranks_k, ranks_v))
+    per_unit = np.diff(plan_tables["unit_item_ptr"])
+    H = len(ranks_k)
+    out = 0
+    for u, n in enumerate(per_unit):
+        rv = int(ranks_v[u % H])
+        out += rv * 4 if n <= 1 else int(n) * (rv + 2) * 4
+    return kv + batch * RK * 4 + out
+
+
+def run_decode_workload(fdc, gen, wl, steps, warmup, args):
+    import torch
+    dev = "cuda:0"
+    ranks = wl.ranks()
+    L, H, B, S, d, dh = wl.n_layers, wl.n_heads, wl.batch, wl.context, wl.d_model, wl.d_head
+    lay = fdc.Layout(L, H, d, dh, ranks, ranks, B, S, fdc.FDC_BF16)
+    t = lay.tables()
+    W = args.workers or fdc.fdc_suggest_workers(0)
+    gt = torch.Generator(device=dev).manual_seed(wl.seed)
+    bf = torch.bfloat16
+    kc, vc, A_cat_t, Bk, Mt, plans, wss = [], [], [], [], [], [], []
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split = W, wl.min_split
+    if args.granule:
+        pp.granule = args.granule
+    t_plan = 0.0
+    for l in range(L):
+        k = torch.empty(int(t["k_bytes"][l]) // 2, dtype=bf, device=dev)
+        v = torch.empty(int(t["v_bytes"][l]) // 2, dtype=bf, device=dev)
+        fill_latent(k, lay, t["koff_r"][l], ranks[l], B, S, wl.decay, gt)
+        fill_latent(v, lay, t["voff_r"][l], ranks[l], B, S, wl.decay, gt)
+        kc.append(k), vc.append(v)
+        RK, RV = int(t["koff_r"][l, -1]), int(t["voff_r"][l, -1])
+        A_cat_t.append((torch.randn(RK + RV, d, generator=gt, device=dev) / math.sqrt(d)).to(bf))
+        Bk.append((torch.randn(RK, dh, generator=gt, device=dev) / math.sqrt(dh)).to(bf))
+        Mt.append((torch.randn(d, RV, generator=gt, device=dev) / math.sqrt(RV)).to(bf))
+        t0 = time.perf_counter()
+        plan = fdc.fdc_plan_decode(lay, l, [S] * B, pp)
+        t_plan += time.perf_counter() - t0
+        ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + plan.workspace_bytes()]
+        fdc.fdc_plan_upload(plan, ws)
+        plans.append(plan), wss.append(ws)
+    x = torch.randn(B, d, generator=gt, device=dev).to(bf)
+    q = torch.randn(B, H, dh, generator=gt, device=dev).to(bf)
+    tb = torch.arange(B, dtype=torch.int32, device=dev)
+    tp = torch.full((B,), S - 1, dtype=torch.int32, device=dev)
+    RKmax = int(t["koff_r"][:, -1].max())
+    RVmax = int(t["voff_r"][:, -1].max())
+    q_lat = torch.empty(B * RKmax, dtype=torch.float32, device=dev)
+    o_lat = torch.empty(B * RVmax, dtype=torch.float32, device=dev)
+    y = torch.empty(B, d, dtype=bf, device=dev)
+    scale = 1.0 / math.sqrt(dh)
+
+    tabs = [p.export() for p in plans]
+    dec_bytes = [decode_bytes(tabs[l], ranks[l], ranks[l], [S] * B, int(t["koff_r"][l, -1]),
+                              int(t["voff_r"][l, -1]), B) for l in range(L)]
+    # algorithmic bytes of the other calls of a step: weights streamed once, activations in/out
+    other_bytes = []
+    for l in range(L):
+        RK, RV = int(t["koff_r"][l, -1]), int(t["voff_r"][l, -1])
+        proj = (RK + RV) * d * 2 + B * d * 2 + B * (RK + RV) * 2
+        absq = RK * dh * 2 + B * H * dh * 2 + B * RK * 4
+        apply_ = d * RV * 2 + B * RV * 4 + B * d * 2
+        merge = sum(int(n) * (int(ranks[l][u % H]) + 2) * 4 for u, n in enumerate(np.diff(tabs[l]["unit_item_ptr"])) if n > 1)
+        other_bytes.append(proj + absq + apply_ + merge)
+    step_bytes = sum(dec_bytes) + sum(other_bytes)
+
+    ev = HipEvents(2 * L * steps)
+
+    def step(si=None):
+        for l in range(L):
+            fdc.fdc_project_latent_kv(lay, l, x, tb, tp, A_cat_t[l], kc[l], vc[l])
+            fdc.fdc_absorb_query(lay, l, q, Bk[l], q_lat, fdc.FDC_F32)
+            if si is not None:
+                i = 2 * (si * L + l)
+                fdc.fdc_profile_decode_events(ev.ev[i], ev.ev[i + 1])
+            fdc.fdc_latent_attn_decode(lay, plans[l], q_lat, kc[l], vc[l], scale, o_lat, wss[l])
+            fdc.fdc_absorb_output(lay, l, fdc.FDC_APPLY, None, None, Mt[l], o_lat, fdc.FDC_F32, B, y, fdc.FDC_BF16)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for si in range(steps):
+        step(si)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    kern_ms = np.array([[ev.ms(2 * (si * L + l), 2 * (si * L + l) + 1) for l in range(L)] for si in range(steps)])
+    ev.destroy()
+    per_layer_ms = kern_ms.mean(axis=0)
+    avg_kernel_ms = float(kern_ms.mean())
+    avg_bytes = float(np.mean(dec_bytes))
+    achieved = avg_bytes / (avg_kernel_ms * 1e-3) / 1e9
+    layer_gbps = np.array(dec_bytes) / (per_layer_ms * 1e-3) / 1e9
+    imb = [float(tb_["worker_load"].max() / tb_["worker_load"].mean()) for tb_ in tabs]
+
+    # decode attention call alone (tile kernel + merge), all layers back to back
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    reps = max(2, steps // 2)
+    for _ in range(reps):
+        for l in range(L):
+            fdc.fdc_latent_attn_decode(lay, plans[l], q_lat, kc[l], vc[l], scale, o_lat, wss[l])
+    torch.cuda.synchronize()
+    attn_us_per_layer = (time.perf_counter() - t0) * 1e6 / (reps * L)
+
+    result = {
+        "ms_per_step": ms_per_step,
+        "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "decode_tiles_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "avg_launch_us": avg_kernel_ms * 1e3, "algorithmic_bytes_per_launch": avg_bytes,
+                     "launches_timed": int(kern_ms.size)},
+        "decode_attn": {"us_per_layer_call": attn_us_per_layer,
+                        "tile_kernel_us_per_layer": {"mean": float(per_layer_ms.mean() * 1e3),
+                                                     "min": float(per_layer_ms.min() * 1e3),
+                                                     "max": float(per_layer_ms.max() * 1e3)},
+                        "tile_kernel_GBps_per_layer": {"min": float(layer_gbps.min()), "max": float(layer_gbps.max())},
+                        "GBps_call": avg_bytes / (attn_us_per_layer * 1e-6) / 1e9,
+                        "planner_imbalance_max_over_mean": {"mean": float(np.mean(imb)), "max": float(np.max(imb))},
+                        "plan_host_ms_per_layer": t_plan * 1e3 / L, "n_workers": W,
+                        "tiles_per_layer": float(np.mean([tb_["n_items"] for tb_ in tabs]))},
+        "step_algorithmic_bytes": step_bytes,
+    }
+    state = dict(lay=lay, tables=t, kc=kc, vc=vc, ranks=ranks, q_lat=q_lat, scale=scale, B=B, S=S, H=H)
+    return result, state
+
+
+def cpu_baseline(state, budget_s=12.0):
+    """The float64 oracle (as it stands) on the host, over units of layer 0 of the same workload."""
+    import torch
+    from oracle import attention as oa
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    lay, t, ranks = state["lay"], state["tables"], state["ranks"]
+    B, S, H = state["B"], state["S"], state["H"]
+    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    q = state["q_lat"][:B * RK].view(B, RK).to(torch.float64).cpu().numpy()
+    g = np.random.Generator(np.random.PCG64(0))
+    units = [(int(b), int(h)) for b, h in zip(g.integers(0, B, 24), g.integers(0, H, 24))]
+    data = []
+    for b, h in units:
+        r = int(ranks[0][h])
+        ks = b * S * RK + int(t["koff"][0, h])
+        vs = b * S * RV + int(t["voff"][0, h])
+        K = state["kc"][0][ks:ks + S * r].view(S, r).to(torch.float64).cpu().numpy()
+        V = state["vc"][0][vs:vs + S * r].view(S, r).to(torch.float64).cpu().numpy()
+        data.append((q[b, int(t["koff_r"][0, h]):int(t["koff_r"][0, h + 1])], K, V, S * 2 * r * 2))
+    done_bytes, n_units = 0, 0
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < budget_s:
+        for qq, K, V, nbytes in data:
+            oa.latent_attn_decode(qq, K, V, state["scale"])
+            done_bytes += nbytes
+            n_units += 1
+    dt = time.perf_counter() - t0
+    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{n_units} (sequence, head) decode units of layer 0 (24 distinct, context {S}, "
+                      f"bf16 bytes counted as for the GPU), {dt:.1f} s of numpy float64",
+            "us_per_unit": dt * 1e6 / n_units}
+
+
+def run_prefill_workload(fdc, gen, iters=3):
+    """Config 5: projection of 16384 tokens, causal latent attention, output absorption (bf16 MFMA)."""
+    import torch
+    dev = "cuda:0"
+    wl = gen.CONFIGS["c5_prefill"]
+    r = wl.ranks()[0]
+    H, B, S, d, dh = wl.n_heads, wl.batch, wl.context, wl.d_model, wl.d_head
+    lay = fdc.Layout(1, H, d, dh, [r], [r], B, S, fdc.FDC_BF16)
+    t = lay.tables()
+    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    bf = torch.bfloat16
+    gt = torch.Generator(device=dev).manual_seed(wl.seed)
+    T = B * S
+    x = torch.randn(T, d, generator=gt, device=dev).to(bf)
+    A_cat_t = (torch.randn(RK + RV, d, generator=gt, device=dev) / math.sqrt(d)).to(bf)
+    Bk = (torch.randn(RK, dh, generator=gt, device=dev) / math.sqrt(dh)).to(bf)
+    Bv = (torch.randn(RV, dh, generator=gt, device=dev) / math.sqrt(dh)).to(bf)
+    Wo_t = (torch.randn(d, H * dh, generator=gt, device=dev) / math.sqrt(H * dh)).to(bf)
+    q = torch.randn(T, H, dh, generator=gt, device=dev).to(bf)
+    kc = torch.zeros(int(t["k_bytes"][0]) // 2, dtype=bf, device=dev)
+    vc = torch.zeros(int(t["v_bytes"][0]) // 2, dtype=bf, device=dev)
+    tb = torch.arange(B, dtype=torch.int32, device=dev).repeat_interleave(S)
+    tp = torch.arange(S, dtype=torch.int32, device=dev).repeat(B)
+    q_lat = torch.empty(T, RK, dtype=bf, device=dev)
+    o_lat = torch.empty(T, RV, dtype=bf, device=dev)
+    Mt = torch.empty(d, RV, dtype=bf, device=dev)
+    y = torch.empty(T, d, dtype=bf, device=dev)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = fdc.fdc_suggest_workers(1), 1, 128, 256
+    t0 = time.perf_counter()
+    plan = fdc.fdc_plan_prefill(lay, 0, [S] * B, [S] * B, pp)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan.workspace_bytes()]
+    fdc.fdc_plan_upload(plan, ws)
+    scale = 1.0 / math.sqrt(dh)
+    calls = {
+        "project_latent_kv": (lambda: fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A_cat_t, kc, vc), 2.0 * T * d * (RK + RV)),
+        "absorb_query": (lambda: fdc.fdc_absorb_query(lay, 0, q, Bk, q_lat, fdc.FDC_BF16), 2.0 * T * dh * RK),
+        "latent_attn_prefill": (lambda: fdc.fdc_latent_attn_prefill(lay, plan, q_lat, kc, vc, scale, True, o_lat, ws),
+                                float(B * sum(int(rr) * 2 for rr in r) * 2 * (S * (S + 1) // 2))),
+        "absorb_output_fold": (lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_FOLD, Bv, Wo_t, Mt, None, 0, 0, None, 0), 2.0 * RV * dh * d),
+        "absorb_output_apply": (lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt, o_lat, fdc.FDC_BF16, T, y, fdc.FDC_BF16), 2.0 * T * RV * d),
+    }
+    out = {"workload": "config 5: B=4, S=4096, d_model 4096, 32 heads, adaptive ranks", "plan_host_ms": plan_ms}
+    total_ms = 0.0
+    for name, (fn, flops) in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        ms = s.elapsed_time(e) / iters
+        total_ms += ms
+        out[name] = {"ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+    out["total_ms"] = total_ms
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3_adaptive_decode",
+                    choices=["c2_uniform_decode", "c3_adaptive_decode", "c4_long_decode"])
+    ap.add_argument("--workers", type=int, default=0, help="decode workers (0 = resident wavefronts of the device)")
+    ap.add_argument("--granule", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (own experiments)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
+              "(no collective is part of this path)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    import paper_2408_04107_amd as fdc
+    from workloads import generators as gen
+
+    wl = gen.CONFIGS[args.workload]
+    if args.layers:
+        import copy
+        wl = copy.copy(wl)
+        wl._ranks = wl.ranks()[:args.layers].copy()
+        wl.n_layers = args.layers
+    res, state = run_decode_workload(fdc, gen, wl, args.steps, args.warmup, args)
+    line = {
+        "metric": "latent-KV decode step: achieved HBM GB/s (algorithmic bytes of the whole step / step time)",
+        "value": res["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.n_layers, "heads": wl.n_heads, "d_head": wl.d_head,
+                   "batch": wl.batch, "context": wl.context, "ranks": "adaptive 16..128, P(r)~1/r"
+                   if wl.rank_seed is not None else "uniform 64", "kv_dtype": "bf16", "accumulate": "fp32"},
+        "pct_of_hbm_peak": 100.0 * res["value"] / HBM_PEAK_GBPS,
+        "roofline": res["roofline"], "decode_attn": res["decode_attn"],
+        "step_algorithmic_bytes": res["step_algorithmic_bytes"],
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(state)
+    del state
+    torch.cuda.empty_cache()
+    if not args.no_prefill:
+        line["prefill"] = run_prefill_workload(fdc, gen)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

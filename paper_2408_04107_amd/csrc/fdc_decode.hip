@@ -28,6 +28,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRaiseMargin = 6.0f;  // in log2 units: p never exceeds 2^6 between raises
 constexpr int kBufferFlags = 0x00020000;  // word 3 of a gfx9 raw buffer descriptor: 32-bit data format
 
+// Cache policy of the K'/V' stream: the "nt" (non-temporal) bit. Every cached byte is read exactly
+// once per step, so it should not displace anything in L2 / the last-level cache; measured on
+// MI355X a read-only stream reaches about 6.1 TB/s with default loads and about 7.0 TB/s with nt.
+constexpr int kStreamPolicy = 2;
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ---- small device helpers -------------------------------------------------------------------
@@ -129,13 +134,13 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
     const uint32_t base = k_lane + (uint32_t)(t0 * k_row_bytes);
 #pragma unroll
     for (int i = 0; i < NK; ++i)
-      kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(base + (uint32_t)(i * RK_ROWS * k_row_bytes)), 0, 0);
+      kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(base + (uint32_t)(i * RK_ROWS * k_row_bytes)), 0, kStreamPolicy);
   };
   auto load_v = [&](int t0) {
     const uint32_t base = v_lane + (uint32_t)(t0 * v_row_bytes);
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-      vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(base + (uint32_t)(i * RV_ROWS * v_row_bytes)), 0, 0);
+      vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(base + (uint32_t)(i * RV_ROWS * v_row_bytes)), 0, kStreamPolicy);
   };
 
   float acc[EL];
