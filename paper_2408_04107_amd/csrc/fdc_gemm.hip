@@ -222,6 +222,90 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
   }
 }
 
+// ---- bf16 MFMA kernel for few rows (decode: M = batch) ------------------------------------------
+// With M <= 64 the product is a weight stream: every B row (K contiguous bf16) is read once and
+// the kernel is bound by HBM, not by MFMA. A workgroup of eight waves owns 16 rows of B; the
+// waves split K into eight contiguous ranges, so a launch has ceil(N/16) * 8 waves in flight
+// (about 1500 to 2000 at the 7B shapes) instead of the few 128 x 128 tiles of the large kernel.
+// Each wave accumulates MT 16 x 16 tiles (v_mfma_f32_16x16x32_bf16), the eight partial tiles are
+// summed through LDS in a fixed order (deterministic) and written by one wave per row tile.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kSkinnyWaves = 8;
+
+template <typename TA, typename TC, int MT>
+__global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const GemmArgs g) {
+  __shared__ f32x4 red[kSkinnyWaves][MT][64];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int n0 = blockIdx.x * 16;
+  const TA* A = static_cast<const TA*>(g.A);
+  const uint16_t* B = static_cast<const uint16_t*>(g.B);
+  const int k_per_wave = ((g.K + kSkinnyWaves - 1) / kSkinnyWaves + 31) / 32 * 32;
+  const int k_begin = wave * k_per_wave, k_end = min(g.K, k_begin + k_per_wave);
+  const bool n_ok = n0 + ln < g.N;
+  const uint16_t* brow = B + (int64_t)(n0 + ln) * g.ldb + 8 * lg;
+  f32x4 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  constexpr int U = 4;  // k-steps in flight
+  for (int k0 = k_begin; k0 < k_end; k0 += 32 * U) {
+    u32x4 fb[U], fa[U][MT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = k0 + 32 * u + 8 * lg;
+      const bool k_ok = k < k_end;
+      fb[u] = (n_ok && k_ok) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(brow + k0 + 32 * u))
+                             : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = 16 * mt + ln;
+        fa[u][mt] = (k_ok && m < g.M) ? load_chunk<TA>(A + (int64_t)m * g.lda + k) : u32x4{0, 0, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        union { u32x4 u; bf16x8 v; } a, b;
+        a.u = fa[u][mt], b.u = fb[u];
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
+      }
+  }
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) red[wave][mt][lane] = acc[mt];
+  __syncthreads();
+  if (wave < MT) {  // wave w finishes row tile w. Register e of lane l is row 4 * (l / 16) + e, column l % 16.
+    f32x4 sum = red[0][wave][lane];
+#pragma unroll
+    for (int w = 1; w < kSkinnyWaves; ++w) sum += red[w][wave][lane];
+    const int n = n0 + ln;
+    if (n < g.N) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = 16 * wave + 4 * lg + e;
+        if (m >= g.M) continue;
+        if (g.mode == kProject) {
+          int side;
+          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(sum[e]);
+        } else {
+          store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
+        }
+      }
+    }
+  }
+}
+
+template <typename TA, typename TC>
+static void launch_skinny(const GemmArgs& a, hipStream_t st) {
+  const dim3 grid((a.N + 15) / 16), block(kSkinnyWaves * 64);
+  const int mt = (a.M + 15) / 16;
+  if (mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 1>), grid, block, 0, st, a);
+  else if (mt == 2) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 2>), grid, block, 0, st, a);
+  else if (mt == 3) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 3>), grid, block, 0, st, a);
+  else hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 4>), grid, block, 0, st, a);
+}
+
 static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
   const int H = lay->H;
   a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq;
@@ -238,6 +322,11 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
   if (lay->dtype == FDC_F32) {
     const dim3 grid((n_max + 15) / 16, (a.M + 15) / 16, groups);
     hipLaunchKernelGGL(gemm_f32_kernel<float>, grid, dim3(256), 0, st, a);
+  } else if (a.M <= 64 && (a.mode == kPlain || a.mode == kProject)) {
+    if (a_f32 && c_f32) launch_skinny<float, float>(a, st);
+    else if (a_f32) launch_skinny<float, uint16_t>(a, st);
+    else if (c_f32) launch_skinny<uint16_t, float>(a, st);
+    else launch_skinny<uint16_t, uint16_t>(a, st);
   } else {
     const dim3 grid((n_max + BN - 1) / BN, (a.M + BM - 1) / BM, groups);
     if (a_f32 && c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, float>), grid, dim3(256), 0, st, a);

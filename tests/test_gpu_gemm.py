@@ -36,6 +36,11 @@ CASES = [
     (3, 64, 32, [16, 32, 16], [32, 16, 16], 5),
     (8, 512, 128, [16, 32, 48, 64, 80, 96, 112, 128], [128, 16, 48, 64, 32, 112, 96, 80], 300),
     (4, 1000, 64, [64, 16, 48, 32], [16, 64, 64, 48], 129),
+    # few rows: the weight-streaming kernel (decode batches), 1 to 4 row tiles
+    (8, 512, 128, [16, 32, 48, 64, 80, 96, 112, 128], [128, 16, 48, 64, 32, 112, 96, 80], 16),
+    (4, 1000, 64, [64, 16, 48, 32], [16, 64, 64, 48], 64),
+    (3, 264, 32, [16, 32, 16], [32, 16, 16], 33),
+    (32, 4096, 128, [64] * 32, [64] * 32, 48),
 ]
 
 
