@@ -22,8 +22,19 @@
 
 namespace fdc {
 
+#ifndef FDC_DECODE_LOADS
+#define FDC_DECODE_LOADS 8
+#endif
+constexpr int kTokLanes = 64 * FDC_DECODE_LOADS;  // a block holds FDC_DECODE_LOADS wave-wide loads of the wider operand
 constexpr int kWavesPerBlock = 4;
-constexpr int kLdsFloatsPerWave = 256;
+constexpr int kLdsFloatsPerWave = kTokLanes / 2 > 256 ? kTokLanes / 2 : 256;
+
+// Tokens per block: FDC_DECODE_LOADS loads of the wider operand, at least one load of the narrower.
+constexpr int block_tokens(int lk, int lv) {
+  int t = kTokLanes / (lk > lv ? lk : lv);
+  const int need = 64 / (lk < lv ? lk : lv);
+  return t > need ? t : need;
+}
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRaiseMargin = 6.0f;  // in log2 units: p never exceeds 2^6 between raises
 constexpr int kBufferFlags = 0x00020000;  // word 3 of a gfx9 raw buffer descriptor: 32-bit data format
@@ -96,7 +107,7 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
                                             float* __restrict__ o_lat, float* __restrict__ partials, float* lds,
                                             const int lane) {
   constexpr int EL = Elem<T>::EL;
-  constexpr int TB = (512 / LK) < (512 / LV) ? (512 / LK) : (512 / LV);  // tokens per block
+  constexpr int TB = block_tokens(LK, LV);                              // tokens per block
   constexpr int RK_ROWS = 64 / LK, RV_ROWS = 64 / LV;                    // rows per wave-wide load
   constexpr int NK = TB / RK_ROWS, NV = TB / RV_ROWS;                    // loads per lane per block
   constexpr int NS = (TB + 63) / 64;                                     // scores per lane per block
@@ -152,6 +163,21 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
   __builtin_amdgcn_sched_barrier(0);  // keep issue order K' then V': the wait counters rely on it
   load_v(0);
   __builtin_amdgcn_sched_barrier(0);
+#ifdef FDC_DECODE_STRIP  // measurement experiment only: same loads, trivial arithmetic
+  for (int t0 = 0; t0 < len; t0 += TB) {
+#pragma unroll
+    for (int i = 0; i < NK; ++i) l += __uint_as_float(kreg[i][0] ^ kreg[i][1] ^ kreg[i][2] ^ kreg[i][3]);
+    __builtin_amdgcn_sched_barrier(0);
+    load_k(t0 + TB);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) acc[0] += __uint_as_float(vreg[i][0] ^ vreg[i][1] ^ vreg[i][2] ^ vreg[i][3]);
+    __builtin_amdgcn_sched_barrier(0);
+    load_v(t0 + TB);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  m = 0.f;
+#else
   for (int t0 = 0; t0 < len; t0 += TB) {
     // scores of the block -> LDS strip
 #pragma unroll
@@ -210,6 +236,7 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
     __builtin_amdgcn_sched_barrier(0);
     wave_lds_sync();
   }
+#endif
 
   // tile result: l over all lanes, acc over the lanes that share a column group
   l = group_sum<64>(l);
@@ -242,21 +269,21 @@ __device__ __forceinline__ int lane_class(int r) {
 
 template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
-    const DecTile* __restrict__ tiles, const int32_t* __restrict__ worker_ptr,
-    const int32_t* __restrict__ worker_items, const float* __restrict__ q_lat, const T* __restrict__ kc,
-    const T* __restrict__ vc, float scale_log2, float* __restrict__ o_lat, float* __restrict__ partials,
-    int n_workers) {
+    const DecWorker* __restrict__ workers, const DecTile* __restrict__ wtiles, const float* __restrict__ q_lat,
+    const T* __restrict__ kc, const T* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
+    float* __restrict__ partials, int n_workers) {
   __shared__ float lds_all[kWavesPerBlock][kLdsFloatsPerWave];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int lane = threadIdx.x % 64;
   const int worker = blockIdx.x * kWavesPerBlock + wave;
   if (worker >= n_workers) return;
   float* lds = lds_all[wave];
-  const int i0 = worker_ptr[worker], i1 = worker_ptr[worker + 1];
+  const DecWorker* hd = workers + worker;
+  const int count = hd->count, begin = hd->begin;
+  if (count == 0) return;
+  DecTile td = hd->first;
   constexpr int BASE = Elem<T>::EL == 8 ? 1 : 2;  // smallest lane class of this element type
-  for (int i = i0; i < i1; ++i) {
-    const int tid = __builtin_amdgcn_readfirstlane(worker_items[i]);
-    const DecTile td = tiles[tid];
+  for (int i = 0;;) {
     const int ck = lane_class<T>(td.rk_rv & 0xffff) - BASE, cvv = lane_class<T>(td.rk_rv >> 16) - BASE;
 #define FDC_CASE(a, b)                                                                                      \
   case (a)*4 + (b):                                                                                         \
@@ -272,57 +299,58 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
       default: break;
     }
 #undef FDC_CASE
+    if (++i >= count) break;
+    td = wtiles[begin + i];
   }
 }
 
 // ---- split-K merge --------------------------------------------------------------------------
-// One workgroup per unit. o' = sum_j acc_j 2^(m_j - M) / sum_j l_j 2^(m_j - M), M = max_j m_j.
-constexpr int kMergeThreads = 256;
-__global__ __launch_bounds__(kMergeThreads) void decode_merge_kernel(const DecUnit* __restrict__ units,
-                                                                     const float* __restrict__ partials,
-                                                                     float* __restrict__ o_lat) {
+// One workgroup per unit: o' = sum_j acc_j 2^(m_j - M) / sum_j l_j 2^(m_j - M), M = max_j m_j.
+// Thread (q, g) owns column quad q (4 floats of acc) and the tiles j = g, g + G, ...; a group first
+// combines its own tiles against the group's maximum, then the G group states are combined
+// through LDS in a fixed order. One pass over the partial states, one barrier.
+template <int G>
+__global__ __launch_bounds__(32 * G) void decode_merge_kernel(const DecUnit* __restrict__ units,
+                                                              const float* __restrict__ partials,
+                                                              float* __restrict__ o_lat) {
   const DecUnit u = units[blockIdx.x];
   const int n = u.tile_end - u.tile_begin;
   const int tid = threadIdx.x;
   if (n == 1) return;  // the tile kernel wrote the normalised output itself
   if (n == 0) {
-    for (int c = tid; c < u.rv; c += kMergeThreads) o_lat[u.o_elem + c] = 0.f;
+    for (int c = tid; c < u.rv; c += 32 * G) o_lat[u.o_elem + c] = 0.f;
     return;
   }
-  __shared__ float red[kMergeThreads];
-  __shared__ float accs[8][132];
-  // M
-  float mx = -INFINITY;
-  for (int j = tid; j < n; j += kMergeThreads) mx = fmaxf(mx, partials[(int64_t)(u.tile_begin + j) * kPartialStride]);
-  red[tid] = mx;
-  __syncthreads();
-  for (int s = kMergeThreads / 2; s > 0; s >>= 1) {
-    if (tid < s) red[tid] = fmaxf(red[tid], red[tid + s]);
-    __syncthreads();
-  }
-  const float M = red[0];
-  __syncthreads();
-  // 32 column quads x 8 tile groups; column quad 32 (threads with q == 0 reuse) carries l
+  __shared__ float accs[G][132];  // [g][0..127] acc, [128] l, [129] m
   const int q = tid % 32, g = tid / 32;
+  const bool col_on = q * 4 < u.rv;
+  const float* base = partials + (int64_t)u.tile_begin * kPartialStride;
+  float mg = -INFINITY;
+  for (int j = g; j < n; j += G) mg = fmaxf(mg, base[(int64_t)j * kPartialStride]);
   float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
   float lsum = 0.f;
-  const bool col_on = q * 4 < u.rv;
-  for (int j = g; j < n; j += 8) {
-    const float* pp = partials + (int64_t)(u.tile_begin + j) * kPartialStride;
-    const float w = __builtin_amdgcn_exp2f(pp[0] - M);
-    if (q == 0) lsum += pp[1] * w;
+  for (int j = g; j < n; j += G) {
+    const float* pp = base + (int64_t)j * kPartialStride;
+    const float w = __builtin_amdgcn_exp2f(pp[0] - mg);
+    lsum += pp[1] * w;
     if (col_on) {
       const float4 v = *reinterpret_cast<const float4*>(pp + 4 + q * 4);
       a.x += v.x * w, a.y += v.y * w, a.z += v.z * w, a.w += v.w * w;
     }
   }
   accs[g][q * 4 + 0] = a.x, accs[g][q * 4 + 1] = a.y, accs[g][q * 4 + 2] = a.z, accs[g][q * 4 + 3] = a.w;
-  if (q == 0) accs[g][128] = lsum;
+  if (q == 0) accs[g][128] = lsum, accs[g][129] = mg;
   __syncthreads();
   if (tid < u.rv) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < G; ++k) M = fmaxf(M, accs[k][129]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) num += accs[k][tid], den += accs[k][128];
+    for (int k = 0; k < G; ++k) {
+      const float w = __builtin_amdgcn_exp2f(accs[k][129] - M);  // groups without tiles: m = -inf, w = 0
+      num += accs[k][tid] * w, den += accs[k][128] * w;
+    }
     o_lat[u.o_elem + tid] = num / den;
   }
 }
@@ -391,10 +419,9 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
     FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_latent_attn_decode: pointers must be 16-byte aligned (workspace 256)");
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  const DecTile* tiles = reinterpret_cast<const DecTile*>(ws + plan->off_items);
+  const DecTile* wtiles = reinterpret_cast<const DecTile*>(ws + plan->off_items);
   const DecUnit* units = reinterpret_cast<const DecUnit*>(ws + plan->off_units);
-  const int32_t* wptr = reinterpret_cast<const int32_t*>(ws + plan->off_worker_ptr);
-  const int32_t* witems = reinterpret_cast<const int32_t*>(ws + plan->off_worker_items);
+  const DecWorker* heads = reinterpret_cast<const DecWorker*>(ws + plan->off_worker_ptr);
   float* partials = reinterpret_cast<float*>(ws + plan->off_partials);
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
@@ -404,18 +431,23 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   if (!plan->item_b.empty()) {
     if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
     if (lay->dtype == FDC_BF16)
-      hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, tiles, wptr, witems,
+      hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
                          static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
     else
-      hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, tiles, wptr, witems,
+      hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),
                          static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
     FDC_HIP_CHECK(hipGetLastError());
     if (ev1) FDC_HIP_CHECK(hipEventRecord(ev1, st));
   }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(plan->n_units), dim3(kMergeThreads), 0, st, units, partials,
-                     static_cast<float*>(o_lat));
+  // wide workgroups only when some unit has many tiles (long contexts)
+  if (plan->max_items_per_unit > 64)
+    hipLaunchKernelGGL(decode_merge_kernel<32>, dim3(plan->n_units), dim3(1024), 0, st, units, partials,
+                       static_cast<float*>(o_lat));
+  else
+    hipLaunchKernelGGL(decode_merge_kernel<4>, dim3(plan->n_units), dim3(128), 0, st, units, partials,
+                       static_cast<float*>(o_lat));
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

@@ -242,7 +242,10 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     p->item_cost[tid] = (int64_t)(pc.t1 - pc.t0) * d_sum[pc.h];
     p->unit_item_ptr[(size_t)pc.b * H + pc.h + 1] += 1;
   }
-  for (int u = 0; u < p->n_units; ++u) p->unit_item_ptr[u + 1] += p->unit_item_ptr[u];
+  for (int u = 0; u < p->n_units; ++u) {
+    p->max_items_per_unit = std::max(p->max_items_per_unit, p->unit_item_ptr[u + 1]);
+    p->unit_item_ptr[u + 1] += p->unit_item_ptr[u];
+  }
   std::vector<std::vector<int32_t>> lists(W);
   p->worker_load.assign(W, 0);
   for (size_t k = 0; k < n; ++k) {  // pieces are in hand-out order
@@ -275,10 +278,20 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     const int b = u / H, h = u % H;
     units[u] = {p->unit_item_ptr[u], p->unit_item_ptr[u + 1], b * p->RV + voff_r[h], rv[h]};
   }
-  p->off_items = append_aligned(p->image, tiles.data(), tiles.size());
+  // tiles in worker (hand-out) order plus one header per worker
+  std::vector<DecTile> wtiles(n);
+  for (size_t i = 0; i < n; ++i) wtiles[i] = tiles[p->worker_items[i]];
+  std::vector<DecWorker> heads(W);
+  for (int w = 0; w < W; ++w) {
+    std::memset(&heads[w], 0, sizeof(DecWorker));
+    heads[w].begin = p->worker_ptr[w];
+    heads[w].count = p->worker_ptr[w + 1] - p->worker_ptr[w];
+    if (heads[w].count > 0) heads[w].first = wtiles[heads[w].begin];
+  }
+  p->off_items = append_aligned(p->image, wtiles.data(), wtiles.size());
   p->off_units = append_aligned(p->image, units.data(), units.size());
-  p->off_worker_ptr = append_aligned(p->image, p->worker_ptr.data(), p->worker_ptr.size());
-  p->off_worker_items = append_aligned(p->image, p->worker_items.data(), p->worker_items.size());
+  p->off_worker_ptr = append_aligned(p->image, heads.data(), heads.size());
+  p->off_worker_items = p->off_worker_ptr;
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = std::max<size_t>(n, 1) * kPartialStride * sizeof(float);
   p->workspace_bytes = p->off_partials + p->partial_bytes;

@@ -44,6 +44,17 @@ struct DecTile {
 };
 static_assert(sizeof(DecTile) == 48, "DecTile layout");
 
+// What a decode worker (one wavefront) reads first: how many tiles it has, where the rest of them
+// are in the worker-ordered tile array, and its first tile inline, so that the cache stream starts
+// after a single dependent load. 64 bytes.
+struct DecWorker {
+  int32_t begin;   // index of the worker's first tile in the worker-ordered tile array
+  int32_t count;   // tiles of this worker
+  int32_t pad[2];
+  DecTile first;
+};
+static_assert(sizeof(DecWorker) == 64, "DecWorker layout");
+
 // One (sequence, head) unit for the split-K merge. 16 bytes.
 struct DecUnit {
   int32_t tile_begin, tile_end;  // partial slots of the unit
@@ -94,6 +105,7 @@ struct fdc_plan {
   const fdc_layout* lay;  // identity check only (the plan copies what it needs)
   int RK, RV;
   int64_t total_q_rows;   // prefill: T
+  int max_items_per_unit = 0;  // decode: most tiles any unit was cut into
   // exported tables
   std::vector<int32_t> item_b, item_h, item_lo, item_hi, unit_item_ptr, worker_ptr, worker_items, br;
   std::vector<int64_t> item_cost, worker_load;
