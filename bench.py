@@ -182,11 +182,22 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     torch.cuda.synchronize()
     attn_us_per_layer = (time.perf_counter() - t0) * 1e6 / (reps * L)
 
+    # HBM bytes per launch of the tile kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
+    # WRITE_SIZE, each scaled by a plain copy of known size); null when that summary is for another workload
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "decode_tiles_traffic.json")) as fh:
+            tj = json.load(fh)["decode_tiles_kernel"]
+        if tj["workload"] == wl.name and wl.n_layers == gen.CONFIGS[wl.name].n_layers:
+            traffic = tj["fetch_bytes_per_launch"] + tj["write_bytes_per_launch"]
+    except (OSError, KeyError, ValueError):
+        traffic = None
+
     result = {
         "ms_per_step": ms_per_step,
         "value": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "roofline": {"bound": "hbm", "kernel": "decode_tiles_kernel", "achieved": achieved, "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "avg_launch_us": avg_kernel_ms * 1e3, "algorithmic_bytes_per_launch": avg_bytes,
                      "launches_timed": int(kern_ms.size)},
         "decode_attn": {"us_per_layer_call": attn_us_per_layer,
@@ -314,6 +325,8 @@ def main():
     ap.add_argument("--workers", type=int, default=0, help="decode workers (0 = resident wavefronts of the device)")
     ap.add_argument("--granule", type=int, default=0)
     ap.add_argument("--layers", type=int, default=0, help="use only the first N layers (own experiments)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (known HBM traffic) for scaling rocprofv3 counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     args = ap.parse_args()
@@ -335,6 +348,12 @@ def main():
         wl = copy.copy(wl)
         wl._ranks = wl.ranks()[:args.layers].copy()
         wl.n_layers = args.layers
+    if args.pmc_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(3)
+        dst = torch.empty_like(src)
+        dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     res, state = run_decode_workload(fdc, gen, wl, args.steps, args.warmup, args)
     line = {
         "metric": "latent-KV decode step: achieved HBM GB/s (algorithmic bytes of the whole step / step time)",
