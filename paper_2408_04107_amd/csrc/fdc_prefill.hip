@@ -3,16 +3,19 @@
 //
 // Design for gfx950. A worker is one workgroup of four waves; it walks the Q-block tasks the
 // planner gave it. A task is processed in passes of 128 query rows, 32 rows (two 16-row MFMA
-// tiles) per wave. K' and V' blocks of 64 tokens are staged through LDS once per workgroup: K'
-// row-major (rank padded to a multiple of 32 with zeros), V' transposed so that both MFMA
-// operands are read with vector LDS loads. All products are transposed ones,
+// tiles) per wave. K' and V' blocks of 64 tokens are staged through LDS once per workgroup, both
+// row-major as they sit in the cache (K' with its rank zero-padded to a multiple of 32), in two
+// alternating buffers so that a block costs one barrier. All products are transposed ones,
 //     S^T = K' Q'^T          (A = K' rows,   B = Q' rows)      v_mfma_f32_16x16x32_bf16
 //     O^T = V'^T P^T         (A = V'^T rows, B = P^T)          v_mfma_f32_16x16x32_bf16
 // because then every quantity a lane holds belongs to ONE query row (column l%16 of the MFMA
 // output): the score tile comes out of the first product already in the operand layout of the
 // second (no LDS round trip for P), the running max / sum live in the lanes that use them, and
-// the rescale of O needs no cross-lane traffic. The k index of the second product (tokens) is
-// spread over lanes in the order the first product delivers it; both operands use the same order.
+// the rescale of O needs no cross-lane traffic. The V'^T operand is read from the row-major tile
+// with the transposing LDS load of gfx950 (ds_read_b64_tr_b16): inside a group of 16 lanes, lane s
+// supplies the address of 4 consecutive columns of token s/4, and lane L receives column L of the
+// four tokens. The k index of the second product (tokens) is spread over lanes in the order the
+// first product delivers it; both operands use the same order.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -22,22 +25,27 @@
 namespace fdc {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPreThreads = 256;
 constexpr int BC = 64;                   // tokens per K'/V' block
 constexpr int kRowsPerWave = 32;         // two MFMA row tiles
 constexpr int kRowsPerPass = 128;        // four waves
-constexpr int kKPad = 8, kVPad = 8;      // LDS row padding in elements
+constexpr int KROW = 128 + 8;            // LDS row length of the K' tile in elements (272 bytes)
+constexpr int VROW = 128 + 16;           // LDS row length of the V' tile in elements (288 bytes)
+constexpr int kStageElems = BC * KROW + BC * VROW;  // one buffer: K' tile then V' tile
 constexpr float kLog2eP = 1.4426950408889634f;
+constexpr int RK32 = 4, RV16 = 8;        // unroll bounds: ceil(rk / 32) <= 4, rv / 16 <= 8
 
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-  a += 0x7fffu + ((a >> 16) & 1u);
-  b += 0x7fffu + ((b >> 16) & 1u);
-  return (a >> 16) | (b & 0xffff0000u);
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32, round to nearest even
+  union { bf16x2 v; uint32_t u; } r;
+  r.v = __builtin_convertvector(f32x2{lo, hi}, bf16x2);
+  return r.u;
 }
 
 union Frag {
@@ -45,29 +53,26 @@ union Frag {
   bf16x8 v;
 };
 
-// One instantiation serves every rank: the k-steps of the score product (ceil(rk / 32) <= 4) and
-// the column tiles of the output (rv / 16 <= 8) are fully unrolled loops with wave-uniform guards,
-// so register arrays keep compile-time indices and narrow heads skip the unused steps.
-constexpr int RK32 = 4, RV16 = 8;
+// One instantiation serves every rank: the k-steps of the score product and the column tiles of
+// the output are fully unrolled loops with wave-uniform guards, so register arrays keep
+// compile-time indices and narrow heads skip the unused steps.
 __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* __restrict__ q_lat,
                                              const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
                                              float scale_log2, int causal, uint16_t* __restrict__ o_lat,
-                                             uint16_t* lds_k, uint16_t* lds_vt) {
-  constexpr int KROW = 128 + kKPad;       // LDS row length of the K' tile
-  constexpr int VROW = BC + kVPad;        // LDS row length of the V'^T tile
+                                             uint16_t* lds) {
   const int rk = t.rk_rv & 0xffff, rv = t.rk_rv >> 16;
   const int rk32 = (rk + 31) / 32, rv16 = rv / 16;
-  const int RKP = rk32 * 32;              // rank of the K' rows in LDS, padded with zeros
+  const int RKP = rk32 * 32;  // rank of the K' rows in LDS, padded with zeros
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
   const uint16_t* kbase = kc + t.k_elem;
   const uint16_t* vbase = vc + t.v_elem;
 
-  // zero the rank padding of the K' tile once: staging never writes those columns
+  // zero the rank padding of both K' tiles once: staging never writes those columns
   if (RKP != rk) {
-    for (int i = tid; i < BC * (RKP - rk); i += kPreThreads) {
-      const int r = i / (RKP - rk), c = rk + i % (RKP - rk);
-      lds_k[r * KROW + c] = 0;
+    for (int i = tid; i < 2 * BC * (RKP - rk); i += kPreThreads) {
+      const int buf = i / (BC * (RKP - rk)), j = i % (BC * (RKP - rk));
+      lds[buf * kStageElems + (j / (RKP - rk)) * KROW + rk + j % (RKP - rk)] = 0;
     }
   }
 
@@ -95,6 +100,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int c = 0; c < RV16; ++c) oacc[i][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // running maximum of the raw (unscaled) scores and running sum, per query row
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     const int pos_base = t.pos0 + wrow0 + ln;  // absolute position of this lane's row in tile 0 (+16 for tile 1)
 
@@ -116,111 +122,118 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
                                                     : u32x4{0, 0, 0, 0};
       }
     };
-    auto stage = [&]() {
+    auto stage = [&](int buf) {
+      uint16_t* lk = lds + buf * kStageElems;
+      uint16_t* lv = lk + BC * KROW;
 #pragma unroll
       for (int i = 0; i < kMaxChunks; ++i) {
         const int c = tid + i * kPreThreads;
-        if (c < k_chunks) {
-          const int r = c / (rk / 8), col = (c % (rk / 8)) * 8;
-          *reinterpret_cast<u32x4*>(&lds_k[r * KROW + col]) = kst[i];
-        }
-        if (c < v_chunks) {
-          const int r = c / (rv / 8), col = (c % (rv / 8)) * 8;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            lds_vt[(col + 2 * e) * VROW + r] = (uint16_t)(vst[i][e] & 0xffffu);
-            lds_vt[(col + 2 * e + 1) * VROW + r] = (uint16_t)(vst[i][e] >> 16);
-          }
-        }
+        if (c < k_chunks) *reinterpret_cast<u32x4*>(&lk[(c / (rk / 8)) * KROW + (c % (rk / 8)) * 8]) = kst[i];
+        if (c < v_chunks) *reinterpret_cast<u32x4*>(&lv[(c / (rv / 8)) * VROW + (c % (rv / 8)) * 8]) = vst[i];
       }
     };
 
-    if (kv_end > 0) fetch(0);
-    for (int c0 = 0; c0 < kv_end; c0 += BC) {
-      __syncthreads();  // all waves are done reading the previous block
-      stage();
-      __syncthreads();
-      if (c0 + BC < kv_end) fetch(c0 + BC);
-      if (!wave_on || (causal && c0 > wave_last_pos)) continue;  // nothing visible for this wave (uniform)
-
-      // S^T tiles: st[j][i] = tokens 16 j .. of the block x query rows of tile i
-      f32x4 st[4][2];
+    __syncthreads();  // the previous pass / task (and the padding zeroing) is done with both buffers
+    if (kv_end > 0) {
+      fetch(0);
+      stage(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int c0 = 0; c0 < kv_end; c0 += BC, buf ^= 1) {
+      const bool more = c0 + BC < kv_end;
+      if (more) fetch(c0 + BC);
+      if (wave_on && !(causal && c0 > wave_last_pos)) {  // otherwise nothing visible for this wave (uniform)
+        const uint16_t* lk = lds + buf * kStageElems;
+        const uint16_t* lv = lk + BC * KROW;
+        // S^T tiles: st[j][i] = tokens 16 j .. of the block x query rows of tile i
+        f32x4 st[4][2];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        st[j][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-        st[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < 4; ++j) {
+          st[j][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+          st[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int ks = 0; ks < RK32; ++ks) {
-          if (ks >= rk32) break;
-          Frag kf;
-          kf.u = *reinterpret_cast<const u32x4*>(&lds_k[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
-          st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][ks].v, st[j][0], 0, 0, 0);
-          st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][ks].v, st[j][1], 0, 0, 0);
+          for (int ks = 0; ks < RK32; ++ks) {
+            if (ks >= rk32) break;
+            Frag kf;
+            kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
+            st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][ks].v, st[j][0], 0, 0, 0);
+            st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][ks].v, st[j][1], 0, 0, 0);
+          }
         }
-      }
-      // scale, mask, online softmax. Lane (ln, lg) holds tokens c0 + 16 j + 4 lg + e of row ln.
-      const bool need_mask = (causal && c0 + BC - 1 > t.pos0 + wrow0) || c0 + BC > t.kv_len;
-      Frag pf[2][2];
+        // mask, online softmax. Lane (ln, lg) holds tokens c0 + 16 j + 4 lg + e of row ln.
+        // p = 2^((s - m) * scale * log2 e) as one fma per score.
+        const bool need_mask = (causal && c0 + BC - 1 > t.pos0 + wrow0) || c0 + BC > t.kv_len;
+        Frag pf[2][2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int pos = pos_base + 16 * i;
-        float mx = -INFINITY;
+        for (int i = 0; i < 2; ++i) {
+          const int pos = pos_base + 16 * i;
+          if (need_mask) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            float s = st[j][i][e] * scale_log2;
-            if (need_mask) {
-              const int tok = c0 + 16 * j + 4 * lg + e;
-              if ((causal && tok > pos) || tok >= t.kv_len) s = -INFINITY;
+              for (int e = 0; e < 4; ++e) {
+                const int tok = c0 + 16 * j + 4 * lg + e;
+                if ((causal && tok > pos) || tok >= t.kv_len) st[j][i][e] = -INFINITY;
+              }
+          }
+          float mx = -INFINITY;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[j][i][e]);
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float m_new = fmaxf(m_run[i], mx);
+          // a row with nothing visible yet keeps m = -inf; use 0 as the reference to avoid inf - inf
+          const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+          const float alpha = __builtin_amdgcn_exp2f((m_run[i] - m_ref) * scale_log2);
+          m_run[i] = m_new;
+          const float neg = -m_ref * scale_log2;
+          float psum = 0.f;
+          float p[4][4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              p[j][e] = __builtin_amdgcn_exp2f(fmaf(st[j][i][e], scale_log2, neg));
+              psum += p[j][e];
             }
-            st[j][i][e] = s;
-            mx = fmaxf(mx, s);
+          l_run[i] = l_run[i] * alpha + psum;
+#pragma unroll
+          for (int c = 0; c < RV16; ++c)
+            if (c < rv16) oacc[i][c] *= alpha;
+          // P^T operand of token pair-tiles (2 jp, 2 jp + 1): 8 bf16 per lane
+#pragma unroll
+          for (int jp = 0; jp < 2; ++jp) {
+            pf[i][jp].u[0] = pack_bf16(p[2 * jp][0], p[2 * jp][1]);
+            pf[i][jp].u[1] = pack_bf16(p[2 * jp][2], p[2 * jp][3]);
+            pf[i][jp].u[2] = pack_bf16(p[2 * jp + 1][0], p[2 * jp + 1][1]);
+            pf[i][jp].u[3] = pack_bf16(p[2 * jp + 1][2], p[2 * jp + 1][3]);
           }
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[i], mx);
-        // a row with nothing visible yet keeps m = -inf; use 0 as the reference to avoid inf - inf
-        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run[i] - m_ref);
-        m_run[i] = m_new;
-        float psum = 0.f;
-        float p[4][4];
+        }
+        // O^T += V'^T P^T. A operand: lane (ln, lg) must hold column 16 c + ln for the tokens
+        // 32 jp + 4 lg + e and 32 jp + 16 + 4 lg + e (the order P has them). Transposing load: inside
+        // the 16-lane group lg, source lane s addresses token 4 lg + s / 4, columns 16 c + 4 (s % 4) ..
+        const uint16_t* vsrc = lv + (4 * lg + ln / 4) * VROW + 4 * (ln % 4);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int c = 0; c < RV16; ++c) {
+          if (c >= rv16) break;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            p[j][e] = __builtin_amdgcn_exp2f(st[j][i][e] - m_ref);
-            psum += p[j][e];
+          for (int jp = 0; jp < 2; ++jp) {
+            const uint16_t* a0 = vsrc + (32 * jp) * VROW + 16 * c;
+            union { s16x4 s; u32x2 u; } lo, hi;
+            lo.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+            hi.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 16 * VROW));
+            Frag vf;
+            vf.u = u32x4{lo.u[0], lo.u[1], hi.u[0], hi.u[1]};
+            oacc[0][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[0][jp].v, oacc[0][c], 0, 0, 0);
+            oacc[1][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[1][jp].v, oacc[1][c], 0, 0, 0);
           }
-        l_run[i] = l_run[i] * alpha + psum;
-#pragma unroll
-        for (int c = 0; c < RV16; ++c)
-          if (c < rv16) oacc[i][c] *= alpha;
-        // P^T operand of token pair-tiles (2 jp, 2 jp + 1): 8 bf16 per lane
-#pragma unroll
-        for (int jp = 0; jp < 2; ++jp) {
-          pf[i][jp].u[0] = pack_bf16(p[2 * jp][0], p[2 * jp][1]);
-          pf[i][jp].u[1] = pack_bf16(p[2 * jp][2], p[2 * jp][3]);
-          pf[i][jp].u[2] = pack_bf16(p[2 * jp + 1][0], p[2 * jp + 1][1]);
-          pf[i][jp].u[3] = pack_bf16(p[2 * jp + 1][2], p[2 * jp + 1][3]);
         }
       }
-      // O^T += V'^T P^T. A operand: lane (ln, lg) holds column 16 c + ln, tokens in the same order as P.
-#pragma unroll
-      for (int c = 0; c < RV16; ++c) {
-        if (c >= rv16) break;
-#pragma unroll
-        for (int jp = 0; jp < 2; ++jp) {
-          Frag vf;
-          const uint16_t* vrow = &lds_vt[(16 * c + ln) * VROW + 32 * jp + 4 * lg];
-          const u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
-          const u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 16);
-          vf.u = u32x4{lo[0], lo[1], hi[0], hi[1]};
-          oacc[0][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[0][jp].v, oacc[0][c], 0, 0, 0);
-          oacc[1][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[1][jp].v, oacc[1][c], 0, 0, 0);
-        }
-      }
+      if (more) stage(buf ^ 1);  // the other buffer was last read before the previous barrier
+      __syncthreads();
     }
 
     // finish: l over the four lanes of a row, normalise, store. Lane (ln, lg) holds O[row ln][16 c + 4 lg + e].
@@ -244,23 +257,19 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
       }
     }
   }
-  __syncthreads();  // the next task may use another LDS tile geometry
 }
 
-__global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(const PreTask* __restrict__ tasks,
-                                                              const int32_t* __restrict__ worker_ptr,
-                                                              const int32_t* __restrict__ worker_items,
-                                                              const uint16_t* __restrict__ q_lat,
-                                                              const uint16_t* __restrict__ kc,
-                                                              const uint16_t* __restrict__ vc, float scale_log2,
-                                                              int causal, uint16_t* __restrict__ o_lat) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[BC * (128 + kKPad)];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_vt[128 * (BC + kVPad)];
+__global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
+    const PreTask* __restrict__ tasks, const int32_t* __restrict__ worker_ptr,
+    const int32_t* __restrict__ worker_items, const uint16_t* __restrict__ q_lat,
+    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, int causal,
+    uint16_t* __restrict__ o_lat) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStageElems];
   const int w = blockIdx.x;
   const int i0 = worker_ptr[w], i1 = worker_ptr[w + 1];
   for (int it = i0; it < i1; ++it) {
     const PreTask t = tasks[worker_items[it]];
-    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, lds_k, lds_vt);
+    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, lds);
   }
 }
 
