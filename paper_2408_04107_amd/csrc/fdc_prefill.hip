@@ -40,6 +40,7 @@ constexpr int KROW = 128 + 8;            // LDS row length of the K' tile in ele
 constexpr int VROW = 128 + 16;           // LDS row length of the V' tile in elements (288 bytes)
 constexpr int kStageElems = BC * KROW + BC * VROW;  // one buffer: K' tile then V' tile
 constexpr float kLog2eP = 1.4426950408889634f;
+constexpr float kRaise = 5.0f;           // lazy softmax reference: p <= 2^5 between raises
 constexpr int RK32 = 4, RV16 = 8;        // unroll bounds: ceil(rk / 32) <= 4, rv / 16 <= 8
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32, round to nearest even
@@ -76,8 +77,18 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     }
   }
 
-  const int k_chunks = BC * rk / 8, v_chunks = BC * rv / 8;  // 16-byte chunks per block
-  constexpr int kMaxChunks = (BC * 128 / 8 + kPreThreads - 1) / kPreThreads;  // 4
+  // staging map: 16 lanes per token row (a row has at most 16 chunks of 16 bytes), 16 rows per
+  // sweep, 4 sweeps per block; narrow heads leave the upper lanes of a row idle. No divisions.
+  constexpr int kSweeps = BC / 16;
+  const int s_row = tid / 16, s_cc = tid % 16;
+  const bool k_lane = s_cc * 8 < rk, v_lane = s_cc * 8 < rv;
+  // the unit's K' and V' rows [0, kv_len) as raw buffers (at most 131072 * 256 bytes each)
+  const __amdgpu_buffer_rsrc_t k_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kbase), 0, t.kv_len * rk * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vbase), 0, t.kv_len * rv * 2, 0x00020000);
+  const uint32_t k_lane_off = k_lane ? (uint32_t)(s_cc * 16) : 0x80000000u;
+  const uint32_t v_lane_off = v_lane ? (uint32_t)(s_cc * 16) : 0x80000000u;
 
   for (int r0 = 0; r0 < t.rows; r0 += kRowsPerPass) {
     const int pass_rows = min(kRowsPerPass, t.rows - r0);
@@ -110,26 +121,23 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     const int wave_last_pos = t.pos0 + min(wrow0 + kRowsPerWave, t.rows) - 1;
 
     // register staging of the next block
-    u32x4 kst[kMaxChunks], vst[kMaxChunks];
-    auto fetch = [&](int c0) {
+    u32x4 kst[kSweeps], vst[kSweeps];
+    auto fetch = [&](int c0) {  // rows past kv_len and idle lanes read zeros through the range check
 #pragma unroll
-      for (int i = 0; i < kMaxChunks; ++i) {
-        const int c = tid + i * kPreThreads;
-        const int ktok = c0 + c / (rk / 8), vtok = c0 + c / (rv / 8);
-        kst[i] = (c < k_chunks && ktok < t.kv_len) ? *reinterpret_cast<const u32x4*>(kbase + (int64_t)c0 * rk + c * 8)
-                                                    : u32x4{0, 0, 0, 0};
-        vst[i] = (c < v_chunks && vtok < t.kv_len) ? *reinterpret_cast<const u32x4*>(vbase + (int64_t)c0 * rv + c * 8)
-                                                    : u32x4{0, 0, 0, 0};
+      for (int i = 0; i < kSweeps; ++i) {
+        const uint32_t tok = (uint32_t)(c0 + s_row + 16 * i);
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(k_lane_off + tok * (uint32_t)(rk * 2)), 0, 0);
+        vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(v_lane_off + tok * (uint32_t)(rv * 2)), 0, 0);
       }
     };
     auto stage = [&](int buf) {
       uint16_t* lk = lds + buf * kStageElems;
       uint16_t* lv = lk + BC * KROW;
 #pragma unroll
-      for (int i = 0; i < kMaxChunks; ++i) {
-        const int c = tid + i * kPreThreads;
-        if (c < k_chunks) *reinterpret_cast<u32x4*>(&lk[(c / (rk / 8)) * KROW + (c % (rk / 8)) * 8]) = kst[i];
-        if (c < v_chunks) *reinterpret_cast<u32x4*>(&lv[(c / (rv / 8)) * VROW + (c % (rv / 8)) * 8]) = vst[i];
+      for (int i = 0; i < kSweeps; ++i) {
+        const int r = s_row + 16 * i;
+        if (k_lane) *reinterpret_cast<u32x4*>(&lk[r * KROW + s_cc * 8]) = kst[i];
+        if (v_lane) *reinterpret_cast<u32x4*>(&lv[r * VROW + s_cc * 8]) = vst[i];
       }
     };
 
@@ -150,10 +158,15 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         f32x4 st[4][2];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          st[j][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-          st[j][1] = f32x4{0.f, 0.f, 0.f, 0.f};
+          {  // first k-step starts from a constant zero accumulator (no register clearing)
+            Frag kf;
+            kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 8 * lg]);
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][0].v, zero, 0, 0, 0);
+            st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][0].v, zero, 0, 0, 0);
+          }
 #pragma unroll
-          for (int ks = 0; ks < RK32; ++ks) {
+          for (int ks = 1; ks < RK32; ++ks) {
             if (ks >= rk32) break;
             Frag kf;
             kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
@@ -184,12 +197,20 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
             for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[j][i][e]);
           mx = fmaxf(mx, __shfl_xor(mx, 16));
           mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float m_new = fmaxf(m_run[i], mx);
-          // a row with nothing visible yet keeps m = -inf; use 0 as the reference to avoid inf - inf
-          const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f((m_run[i] - m_ref) * scale_log2);
-          m_run[i] = m_new;
-          const float neg = -m_ref * scale_log2;
+          // The reference m of a row is raised only when the block beats it by kRaise (in log2 units of
+          // the scaled score), so p stays below 2^kRaise and most blocks need no rescale of O at all.
+          if (__any(mx * scale_log2 > m_run[i] * scale_log2 + kRaise)) {
+            const float m_new = fmaxf(m_run[i], mx);
+            // a row with nothing visible yet keeps m = -inf; exp2(-inf - 0) = 0 scales the empty state
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f((m_run[i] - m_ref) * scale_log2);
+            m_run[i] = m_new;
+            l_run[i] *= alpha;
+#pragma unroll
+            for (int c = 0; c < RV16; ++c)
+              if (c < rv16) oacc[i][c] *= alpha;
+          }
+          const float neg = m_run[i] == -INFINITY ? 0.f : -m_run[i] * scale_log2;
           float psum = 0.f;
           float p[4][4];
 #pragma unroll
@@ -199,10 +220,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
               p[j][e] = __builtin_amdgcn_exp2f(fmaf(st[j][i][e], scale_log2, neg));
               psum += p[j][e];
             }
-          l_run[i] = l_run[i] * alpha + psum;
-#pragma unroll
-          for (int c = 0; c < RV16; ++c)
-            if (c < rv16) oacc[i][c] *= alpha;
+          l_run[i] += psum;
           // P^T operand of token pair-tiles (2 jp, 2 jp + 1): 8 bf16 per lane
 #pragma unroll
           for (int jp = 0; jp < 2; ++jp) {
