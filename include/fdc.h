@@ -109,6 +109,8 @@ typedef struct {
   int32_t br_base;   /* prefill: base row block (default 64) */
   int32_t br_cap;    /* prefill: largest row block (default 256) */
   int32_t cost_mode; /* prefill: 0 = paper, 1 = causal */
+  int32_t softmax_cost; /* the "+ 1" of d_sum = rk + rv + 1 (default 1 = the paper's flop count); a larger
+                           value weighs the per-score softmax work as that many multiply-adds */
 } fdc_plan_params;
 
 /* Fills *p with the defaults above and n_workers = 0 (the caller must set it, e.g. from

@@ -30,6 +30,9 @@ Readings taken where the paper is silent (all integer, all deterministic):
     rounds. The paper never mentions the mask.
   * the paper's last-round hand-out is "sequentially ... one at a time" with
     no sort; it is done in task order.
+  * softmax_cost: the paper's d_sum = d_qk + d_v + 1 charges the softmax one unit
+    per score. The parameter replaces that 1 (default 1 = the paper) for kernels
+    whose per-score softmax work weighs more than one multiply-add.
 """
 from __future__ import annotations
 
@@ -63,11 +66,13 @@ def lpt_assign(costs, n_workers: int, presorted: bool = False):
 
 
 def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: int = 1,
-                split: bool = True):
+                split: bool = True, softmax_cost: int = 1):
     """Decode plan for one layer.
 
     seq_len int [B]; rk, rv int [H]. Steps:
-      1. unit (b, h) has cost seq_len[b] * d_sum[h], d_sum = rk + rv + 1 (the paper's task cost).
+      1. unit (b, h) has cost seq_len[b] * d_sum[h], d_sum = rk + rv + 1 (the paper's task cost;
+         softmax_cost replaces the "+ 1" when a kernel's softmax work weighs more than one
+         multiply-add per score).
       2. every non-empty unit is pre-cut into min(min_split, ceil(S/G)) near-equal chunks whose
          boundaries are multiples of the granule G (min_split = 1: the unit itself).
       3. the chunks are sorted by (cost descending, id ascending) and handed, one at a time, to
@@ -87,7 +92,7 @@ def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: i
     """
     B, H = len(seq_len), len(rk)
     W, G = int(n_workers), int(granule)
-    d_sum = [int(rk[h]) + int(rv[h]) + 1 for h in range(H)]
+    d_sum = [int(rk[h]) + int(rv[h]) + int(softmax_cost) for h in range(H)]
     total = sum(int(seq_len[b]) * d_sum[h] for b in range(B) for h in range(H))
 
     chunks = []  # (b, h, t0, t1)
@@ -149,9 +154,9 @@ def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: i
     }
 
 
-def prefill_row_blocks(rk, rv, br_base: int = 64, br_cap: int = 256):
+def prefill_row_blocks(rk, rv, br_base: int = 64, br_cap: int = 256, softmax_cost: int = 1):
     """B_r per head: round_up_16(ceil(br_base * d_sum_max / d_sum_h)), capped at br_cap."""
-    d_sum = [int(a) + int(b) + 1 for a, b in zip(rk, rv)]
+    d_sum = [int(a) + int(b) + int(softmax_cost) for a, b in zip(rk, rv)]
     d_max = max(d_sum)
     return [min(int(br_cap), _round_up(_ceil_div(int(br_base) * d_max, ds), 16)) for ds in d_sum]
 
@@ -164,7 +169,7 @@ def _q_block_cost(q0: int, q1: int, q_len: int, kv_len: int, d_sum: int, causal_
 
 
 def plan_prefill(q_len, kv_len, rk, rv, n_workers: int, br_base: int = 64, br_cap: int = 256,
-                 cost_mode: str = "paper"):
+                 cost_mode: str = "paper", softmax_cost: int = 1):
     """Prefill plan for one layer.
 
     q_len, kv_len int [B] (queries are the last q_len positions of kv_len);
@@ -175,8 +180,8 @@ def plan_prefill(q_len, kv_len, rk, rv, n_workers: int, br_base: int = 64, br_ca
     assert cost_mode in ("paper", "causal")
     causal_cost = cost_mode == "causal"
     B, H, W = len(q_len), len(rk), int(n_workers)
-    d_sum = [int(rk[h]) + int(rv[h]) + 1 for h in range(H)]
-    br = prefill_row_blocks(rk, rv, br_base, br_cap)
+    d_sum = [int(rk[h]) + int(rv[h]) + int(softmax_cost) for h in range(H)]
+    br = prefill_row_blocks(rk, rv, br_base, br_cap, softmax_cost)
 
     tasks = []  # (b, h, q0, q1)
     for b in range(B):

@@ -37,7 +37,7 @@ class FdcError(RuntimeError):
 class PlanParams(C.Structure):
     _fields_ = [("n_workers", C.c_int32), ("granule", C.c_int32), ("min_split", C.c_int32),
                 ("split", C.c_int32), ("br_base", C.c_int32), ("br_cap", C.c_int32),
-                ("cost_mode", C.c_int32)]
+                ("cost_mode", C.c_int32), ("softmax_cost", C.c_int32)]
 
 
 class PlanTables(C.Structure):

@@ -136,6 +136,7 @@ void fdc_plan_params_default(fdc_plan_params* p) {
   p->br_base = 64;
   p->br_cap = 256;
   p->cost_mode = 0;
+  p->softmax_cost = 1;
 }
 
 static fdc_status check_plan_args(const char* fn, const fdc_layout* lay, int layer, int batch,
@@ -147,6 +148,7 @@ static fdc_status check_plan_args(const char* fn, const fdc_layout* lay, int lay
   if (batch <= 0 || batch > lay->max_batch)
     FDC_FAIL(FDC_BAD_SHAPE, "%s: batch %d outside [1, %d]", fn, batch, lay->max_batch);
   if (pr->n_workers <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: n_workers must be positive", fn);
+  if (pr->softmax_cost <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: softmax_cost must be positive", fn);
   return FDC_OK;
 }
 
@@ -166,7 +168,7 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
   const int32_t* rv = &lay->rv[(size_t)layer * H];
   std::vector<int64_t> d_sum(H);
   int64_t d_max = 0;
-  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + 1, d_max = std::max(d_max, d_sum[h]);
+  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost, d_max = std::max(d_max, d_sum[h]);
   int64_t total = 0;
   for (int b = 0; b < batch; ++b)
     for (int h = 0; h < H; ++h) total += seq_len[b] * d_sum[h];
@@ -317,7 +319,7 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
   const int32_t* rv = &lay->rv[(size_t)layer * H];
   std::vector<int64_t> d_sum(H);
   int64_t d_max = 0;
-  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + 1, d_max = std::max(d_max, d_sum[h]);
+  for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost, d_max = std::max(d_max, d_sum[h]);
 
   fdc_plan* p = new (std::nothrow) fdc_plan();
   if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: out of host memory");

@@ -22,7 +22,7 @@ def say(msg):
 
 
 def run_prefill(rk, rv, q_len, kv_len, W, cost_mode=1, causal=True, seed=0, br_base=64, br_cap=256,
-                decay=32.0, sample_rows=None, device_fill=False, q_gain=1.0):
+                decay=32.0, sample_rows=None, device_fill=False, q_gain=1.0, softmax_cost=1):
     H, B = len(rk), len(q_len)
     S_max = max(max(kv_len), 1)
     lay = fdc.Layout(1, H, 256, 128, [rk], [rv], B, S_max, fdc.FDC_BF16)
@@ -45,7 +45,7 @@ def run_prefill(rk, rv, q_len, kv_len, W, cost_mode=1, causal=True, seed=0, br_b
     q_lat = (torch.randn(T, cache.RK, generator=tg, device="cuda:0") * q_gain).to(torch.bfloat16)
     o_lat = torch.full((T, cache.RV), float("nan"), dtype=torch.bfloat16, device="cuda:0")
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = W, cost_mode, br_base, br_cap
+    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap, pp.softmax_cost = W, cost_mode, br_base, br_cap, softmax_cost
     plan = fdc.fdc_plan_prefill(lay, 0, q_len, kv_len, pp)
     ws = workspace_for(plan)
     scale = 1.0 / math.sqrt(128)
@@ -128,5 +128,5 @@ def test_prefill_config5_size_sampled_rows():
         return fixed + [int(x) for x in g.integers(0, S, 6)]
 
     ma, rl, n = run_prefill(r, r, [S] * wl.batch, [S] * wl.batch, W, cost_mode=1, device_fill=True,
-                            sample_rows=rows, seed=12, br_base=128, br_cap=256)
+                            sample_rows=rows, seed=12, br_base=256, br_cap=256, softmax_cost=400)   # bench.py's launch configuration
     say(f"  tasks={n} max_abs={ma:.2e} rel_l2={rl:.2e}")

@@ -56,12 +56,12 @@ PRE_PAIRS = [("item_b", "task_b"), ("item_h", "task_h"), ("item_lo", "task_q0"),
              ("worker_load", "worker_load"), ("br", "br")]
 
 
-def _decode_case(rk, rv, seq, W, G, ms, split):
+def _decode_case(rk, rv, seq, W, G, ms, split, sc=1):
     lay = _layout([rk], [rv], len(seq), max(max(seq), 1))
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.granule, pp.min_split, pp.split = W, G, ms, int(split)
+    pp.n_workers, pp.granule, pp.min_split, pp.split, pp.softmax_cost = W, G, ms, int(split), sc
     got = fdc.fdc_plan_decode(lay, 0, seq, pp).export()
-    ref = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms, split=split)
+    ref = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms, split=split, softmax_cost=sc)
     for a, b in DEC_PAIRS:
         assert got[a].dtype == ref[b].dtype and np.array_equal(got[a], ref[b]), (a, W, G, ms, split)
 
@@ -90,15 +90,16 @@ def test_decode_plan_random_bit_exact():
         rv = (16 * g.integers(1, 9, size=H)).tolist()
         seq = [int(x) for x in g.integers(0, 3000, size=B)]
         _decode_case(rk, rv, seq, int(g.integers(1, 200)), int(g.choice([16, 32, 64, 128])),
-                     int(g.integers(1, 5)), bool(g.integers(0, 2)))
+                     int(g.integers(1, 5)), bool(g.integers(0, 2)), sc=int(g.choice([1, 1, 7, 400])))
 
 
-def _prefill_case(rk, rv, q, kv, W, mode, base=64, cap=256):
+def _prefill_case(rk, rv, q, kv, W, mode, base=64, cap=256, sc=1):
     lay = _layout([rk], [rv], len(q), max(max(kv), 1))
     pp = fdc.fdc_plan_params_default()
     pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = W, {"paper": 0, "causal": 1}[mode], base, cap
+    pp.softmax_cost = sc
     got = fdc.fdc_plan_prefill(lay, 0, q, kv, pp).export()
-    ref = op.plan_prefill(q, kv, rk, rv, W, br_base=base, br_cap=cap, cost_mode=mode)
+    ref = op.plan_prefill(q, kv, rk, rv, W, br_base=base, br_cap=cap, cost_mode=mode, softmax_cost=sc)
     for a, b in PRE_PAIRS:
         assert got[a].dtype == ref[b].dtype and np.array_equal(got[a], ref[b]), (a, W, mode)
 
@@ -111,6 +112,7 @@ def test_prefill_plan_bit_exact(mode):
     wl = gen.CONFIGS["c5_prefill"]
     r = wl.ranks()[0].tolist()
     _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 256, mode)
+    _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 512, mode, base=128, cap=128, sc=400)
     g = gen.make_rng(78)
     for _ in range(10):
         H, B = int(g.integers(1, 6)), int(g.integers(1, 4))
@@ -118,7 +120,7 @@ def test_prefill_plan_bit_exact(mode):
         rv = (16 * g.integers(1, 9, size=H)).tolist()
         q = [int(x) for x in g.integers(0, 700, size=B)]
         kv = [x + int(y) for x, y in zip(q, g.integers(0, 500, size=B))]
-        _prefill_case(rk, rv, q, kv, int(g.integers(1, 70)), mode)
+        _prefill_case(rk, rv, q, kv, int(g.integers(1, 70)), mode, sc=int(g.choice([1, 3, 400])))
 
 
 def test_error_codes_without_gpu():
@@ -152,4 +154,4 @@ def test_error_codes_without_gpu():
     plan = fdc.fdc_plan_decode(lay, 0, [100, 3], pp)
     assert plan.workspace_bytes() % 4 == 0 and plan.workspace_bytes() > 0
     d = fdc.fdc_plan_params_default()
-    assert (d.granule, d.min_split, d.split, d.br_base, d.br_cap, d.cost_mode) == (64, 1, 1, 64, 256, 0)
+    assert (d.granule, d.min_split, d.split, d.br_base, d.br_cap, d.cost_mode, d.softmax_cost) == (64, 1, 1, 64, 256, 0, 1)
