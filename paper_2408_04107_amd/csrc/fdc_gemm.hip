@@ -24,6 +24,7 @@ struct GemmArgs {
   void* C2;  // project: the V' cache
   int64_t lda, ldb, ldc;
   int M, N, K;
+  int nt;    // column tiles of the large kernel (of the widest group)
   int mode;
   int H, d_head, max_seq;
   int RK, RV;
@@ -107,15 +108,26 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
 }
 
 // ---- bf16 MFMA kernel --------------------------------------------------------------------------
-// Workgroup tile 128 x 128, k step 32, four waves in a 2 x 2 grid, each wave 64 x 64 as 2 x 2
-// v_mfma_f32_32x32x16_bf16 tiles. Both operands are staged through LDS with rows padded by 16
-// bytes; fragments are read with one 16-byte LDS load per lane (8 consecutive k of one row).
+// Workgroup tile 256 x 128, k step 64, four waves in a 2 x 2 grid, each wave 128 x 64 as 4 x 2
+// v_mfma_f32_32x32x16_bf16 tiles (128 accumulator registers). Both operands are staged through LDS
+// with rows padded by 16 bytes; fragments are read with one 16-byte LDS load per lane (8
+// consecutive k of one row). The next k step is fetched into registers while the current one is
+// multiplied, so a stage has 64 MFMAs per wave between its two barriers and two workgroups per
+// compute unit cover each other's global-load latency.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2g __attribute__((ext_vector_type(2)));
+typedef float f32x2g __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
-constexpr int kLdsRow = BK + 8;  // elements per padded LDS row (80 bytes)
+constexpr int BM = 256, BN = 128, BK = 64;
+constexpr int kLdsRow = BK + 8;  // elements per padded LDS row (144 bytes)
+
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32 (round to nearest even)
+  union { bf16x2g v; uint32_t u; } r;
+  r.v = __builtin_convertvector(f32x2g{lo, hi}, bf16x2g);
+  return r.u;
+}
 
 template <typename TA>
 __device__ __forceinline__ u32x4 load_chunk(const TA* p);  // 8 consecutive elements -> 8 bf16
@@ -126,53 +138,97 @@ __device__ __forceinline__ u32x4 load_chunk<uint16_t>(const uint16_t* p) {
 template <>
 __device__ __forceinline__ u32x4 load_chunk<float>(const float* p) {
   const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-  u32x4 r;
-  r[0] = f32_to_bf16(a.x) | ((uint32_t)f32_to_bf16(a.y) << 16);
-  r[1] = f32_to_bf16(a.z) | ((uint32_t)f32_to_bf16(a.w) << 16);
-  r[2] = f32_to_bf16(b.x) | ((uint32_t)f32_to_bf16(b.y) << 16);
-  r[3] = f32_to_bf16(b.z) | ((uint32_t)f32_to_bf16(b.w) << 16);
-  return r;
+  return u32x4{cvt_pk_bf16(a.x, a.y), cvt_pk_bf16(a.z, a.w), cvt_pk_bf16(b.x, b.y), cvt_pk_bf16(b.z, b.w)};
 }
 
 template <typename TA, typename TC>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_bf16_kernel(const GemmArgs g) {
   const Group gr = group_of(g, blockIdx.z);
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Tile order. Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so the
+  // linear id is first turned into "XCD-major" order: XCD x walks the contiguous tile range
+  // [x * T/8, (x+1) * T/8). Inside that range tiles go down 8 row-tiles before moving to the next
+  // column tile, so the ~64 workgroups resident on one XCD form an 8 x 8 patch that shares its A
+  // and B panels through that XCD's L2 while all of them advance along k together.
+  const int mt = (g.M + BM - 1) / BM, nt = g.nt;
+  const int tiles = mt * nt, per_xcd = (tiles + 7) / 8;
+  const int lin = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (lin >= tiles) return;
+  constexpr int GM = 8;
+  const int band = lin / (GM * nt), in_band = lin % (GM * nt);
+  const int band_rows = min(GM, mt - band * GM);
+  const int tm = band * GM + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
   if (n0 >= gr.N) return;
   __shared__ __attribute__((aligned(16))) uint16_t lds_a[BM * kLdsRow];
   __shared__ __attribute__((aligned(16))) uint16_t lds_b[BN * kLdsRow];
 
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
-  const int wm = (wave / 2) * 64, wn = (wave % 2) * 64;
+  const int wm = (wave / 2) * 128, wn = (wave % 2) * 64;
   const TA* A = static_cast<const TA*>(g.A) + gr.a_off;
   const uint16_t* B = static_cast<const uint16_t*>(g.B) + gr.b_off;
 
-  // staging: 128 rows x 4 chunks of 8 elements per operand, two chunks per thread
-  const int s_row = tid / 4, s_kc = (tid % 4) * 8;  // rows s_row and s_row + 64
-  u32x4 ra[2], rb[2];
-  auto fetch = [&](int k0) {
+  // staging: a row of the stage is 8 chunks of 8 elements; 8 lanes per row, 32 rows per sweep.
+  // The block's row panels are raw buffers that end with the last valid row, so rows past M / N
+  // read zeros through the hardware range check and a stage needs no address arithmetic: the lane's
+  // byte offsets are fixed and k0 goes into the scalar offset. Only the last, partial k stage
+  // (K not a multiple of 64) compares k.
+  constexpr int SA = BM / 32, SB = BN / 32;
+  constexpr int ES = (int)sizeof(TA);
+  const int s_row = tid / 8, s_kc = (tid % 8) * 8;
+  const int a_rows = min(BM, g.M - m0), b_rows = min(BN, gr.N - n0);
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<TA*>(A + (int64_t)m0 * g.lda), 0, (int)(((int64_t)(a_rows - 1) * g.lda + g.K) * ES), 0x00020000);
+  const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(B + (int64_t)n0 * g.ldb), 0, (int)(((int64_t)(b_rows - 1) * g.ldb + g.K) * 2), 0x00020000);
+  uint32_t a_off[SA], b_off[SB];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int row = s_row + 64 * i;
+  for (int i = 0; i < SA; ++i) a_off[i] = (uint32_t)(((int64_t)(s_row + 32 * i) * g.lda + s_kc) * ES);
+#pragma unroll
+  for (int i = 0; i < SB; ++i) b_off[i] = (uint32_t)(((int64_t)(s_row + 32 * i) * g.ldb + s_kc) * 2);
+  u32x4 ra[SA], rb[SB];
+  auto load_a = [&](uint32_t voff, int soff) -> u32x4 {
+    if constexpr (ES == 2) {
+      return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)voff, soff, 0);
+    } else {
+      const u32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)voff, soff, 0);
+      const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(voff + 16), soff, 0);
+      return u32x4{cvt_pk_bf16(__uint_as_float(lo[0]), __uint_as_float(lo[1])),
+                   cvt_pk_bf16(__uint_as_float(lo[2]), __uint_as_float(lo[3])),
+                   cvt_pk_bf16(__uint_as_float(hi[0]), __uint_as_float(hi[1])),
+                   cvt_pk_bf16(__uint_as_float(hi[2]), __uint_as_float(hi[3]))};
+    }
+  };
+  auto fetch = [&](int k0) {
+    if (k0 + BK <= g.K) {  // full stage (uniform)
+#pragma unroll
+      for (int i = 0; i < SA; ++i) ra[i] = load_a(a_off[i], k0 * ES);
+#pragma unroll
+      for (int i = 0; i < SB; ++i) rb[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (int)b_off[i], k0 * 2, 0);
+    } else {               // last partial stage: chunks at k >= K are zero. k0 is added to the checked
+                           // (vector) offset here, so nothing past the last row's end is touched.
       const bool k_ok = k0 + s_kc < g.K;
-      ra[i] = (k_ok && m0 + row < g.M) ? load_chunk<TA>(A + (int64_t)(m0 + row) * g.lda + k0 + s_kc)
-                                       : u32x4{0, 0, 0, 0};
-      rb[i] = (k_ok && n0 + row < gr.N) ? load_chunk<uint16_t>(B + (int64_t)(n0 + row) * g.ldb + k0 + s_kc)
-                                        : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int i = 0; i < SA; ++i) {
+        const u32x4 v = load_a(a_off[i] + (uint32_t)(k0 * ES), 0);
+        ra[i] = k_ok ? v : u32x4{0, 0, 0, 0};
+      }
+#pragma unroll
+      for (int i = 0; i < SB; ++i) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (int)(b_off[i] + (uint32_t)(k0 * 2)), 0, 0);
+        rb[i] = k_ok ? v : u32x4{0, 0, 0, 0};
+      }
     }
   };
   auto stage = [&]() {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int row = s_row + 64 * i;
-      *reinterpret_cast<u32x4*>(&lds_a[row * kLdsRow + s_kc]) = ra[i];
-      *reinterpret_cast<u32x4*>(&lds_b[row * kLdsRow + s_kc]) = rb[i];
-    }
+    for (int i = 0; i < SA; ++i) *reinterpret_cast<u32x4*>(&lds_a[(s_row + 32 * i) * kLdsRow + s_kc]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < SB; ++i) *reinterpret_cast<u32x4*>(&lds_b[(s_row + 32 * i) * kLdsRow + s_kc]) = rb[i];
   };
 
-  f32x16 acc[2][2];
+  f32x16 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -186,14 +242,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
     if (k0 + BK < g.K) fetch(k0 + BK);
 #pragma unroll
     for (int ks = 0; ks < BK; ks += 16) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[4], fb[2];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < 4; ++i)
         fa[i] = *reinterpret_cast<const bf16x8*>(&lds_a[(wm + i * 32 + lane % 32) * kLdsRow + ks + (lane / 32) * 8]);
-        fb[i] = *reinterpret_cast<const bf16x8*>(&lds_b[(wn + i * 32 + lane % 32) * kLdsRow + ks + (lane / 32) * 8]);
-      }
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int j = 0; j < 2; ++j)
+        fb[j] = *reinterpret_cast<const bf16x8*>(&lds_b[(wn + j * 32 + lane % 32) * kLdsRow + ks + (lane / 32) * 8]);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
@@ -204,16 +261,25 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const GemmArgs g) {
   for (int j = 0; j < 2; ++j) {
     const int n = n0 + wn + j * 32 + lane % 32;
     if (n >= gr.N) continue;
+    // project: the column decides buffer, head block and rank once; the row adds b and pos
+    int side = 0;
+    int64_t col_off = 0, seq_stride = 0;
+    int rank = 0;
+    if (g.mode == kProject) {
+      col_off = project_dst(g, n, 0, 0, &side);
+      const int64_t one = project_dst(g, n, 0, 1, &side);
+      rank = (int)(one - col_off);
+      seq_stride = (int64_t)g.max_seq * (side ? g.RV : g.RK);
+    }
+    uint16_t* cache = static_cast<uint16_t*>(side ? g.C2 : g.C);
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int m = m0 + wm + i * 32 + (e / 4) * 8 + (lane / 32) * 4 + e % 4;
         if (m >= g.M) continue;
         if (g.mode == kProject) {
-          int side;
-          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
-          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(acc[i][j][e]);
+          cache[(int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank] = f32_to_bf16(acc[i][j][e]);
         } else {
           store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc[i][j][e]);
         }
@@ -328,11 +394,14 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     else if (c_f32) launch_skinny<uint16_t, float>(a, st);
     else launch_skinny<uint16_t, uint16_t>(a, st);
   } else {
-    const dim3 grid((n_max + BN - 1) / BN, (a.M + BM - 1) / BM, groups);
-    if (a_f32 && c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, float>), grid, dim3(256), 0, st, a);
-    else if (a_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, uint16_t>), grid, dim3(256), 0, st, a);
-    else if (c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, float>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st, a);
+    GemmArgs b = a;
+    b.nt = (n_max + BN - 1) / BN;
+    const int tiles = b.nt * ((a.M + BM - 1) / BM);
+    const dim3 grid((tiles + 7) / 8 * 8, 1, groups);
+    if (a_f32 && c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, float>), grid, dim3(256), 0, st, b);
+    else if (a_f32) hipLaunchKernelGGL((gemm_bf16_kernel<float, uint16_t>), grid, dim3(256), 0, st, b);
+    else if (c_f32) hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, float>), grid, dim3(256), 0, st, b);
+    else hipLaunchKernelGGL((gemm_bf16_kernel<uint16_t, uint16_t>), grid, dim3(256), 0, st, b);
   }
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
