@@ -298,52 +298,105 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSkinnyWaves = 8;
 
+constexpr int kSkinnyChunkK = 512;             // k covered by one wave-wide 16-byte-per-lane load of a row
+constexpr int kSkinnyRow = kSkinnyChunkK + 8;  // padded LDS row (elements)
+
 template <typename TA, typename TC, int MT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const GemmArgs g) {
-  __shared__ f32x4 red[kSkinnyWaves][MT][64];
+  // per wave: 16 weight rows x 512 k, staged so that global reads are 1 KiB contiguous per row
+  // (HBM-friendly) while the MFMA operand wants 16 rows x 64 bytes per instruction
+  extern __shared__ __attribute__((aligned(16))) uint16_t skinny_lds[];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
   const int n0 = blockIdx.x * 16;
   const TA* A = static_cast<const TA*>(g.A);
   const uint16_t* B = static_cast<const uint16_t*>(g.B);
+  uint16_t* wl = skinny_lds + wave * 16 * kSkinnyRow;
   const int k_per_wave = ((g.K + kSkinnyWaves - 1) / kSkinnyWaves + 31) / 32 * 32;
   const int k_begin = wave * k_per_wave, k_end = min(g.K, k_begin + k_per_wave);
-  const bool n_ok = n0 + ln < g.N;
-  const uint16_t* brow = B + (int64_t)(n0 + ln) * g.ldb + 8 * lg;
   f32x4 acc[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-  constexpr int U = 4;  // k-steps in flight
-  for (int k0 = k_begin; k0 < k_end; k0 += 32 * U) {
-    u32x4 fb[U], fa[U][MT];
+  // Every load below is unconditional: the raw-buffer range check returns zeros for rows past N / M
+  // (their offsets are forced out of range) and a guarded load would cost a branch and a wait each.
+  const int b_rows = min(16, g.N - n0);
+  const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(B + (int64_t)n0 * g.ldb), 0, (int)(((int64_t)(b_rows - 1) * g.ldb + g.K) * 2), 0x00020000);
+  constexpr int ES = (int)sizeof(TA);
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<TA*>(A), 0, (int)(((int64_t)(g.M - 1) * g.lda + g.K) * ES), 0x00020000);
+  uint32_t a_row[MT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = k0 + 32 * u + 8 * lg;
-      const bool k_ok = k < k_end;
-      fb[u] = (n_ok && k_ok) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(brow + k0 + 32 * u))
-                             : u32x4{0, 0, 0, 0};
+  for (int mt = 0; mt < MT; ++mt)
+    a_row[mt] = 16 * mt + ln < g.M ? (uint32_t)((int64_t)(16 * mt + ln) * g.lda * ES) : 0x80000000u;
+  auto load_a = [&](uint32_t voff) -> u32x4 {
+    if constexpr (ES == 2) {
+      return __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)voff, 0, 0);
+    } else {
+      const u32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)voff, 0, 0);
+      const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(voff + 16), 0, 0);
+      return u32x4{cvt_pk_bf16(__uint_as_float(lo[0]), __uint_as_float(lo[1])),
+                   cvt_pk_bf16(__uint_as_float(lo[2]), __uint_as_float(lo[3])),
+                   cvt_pk_bf16(__uint_as_float(hi[0]), __uint_as_float(hi[1])),
+                   cvt_pk_bf16(__uint_as_float(hi[2]), __uint_as_float(hi[3]))};
+    }
+  };
+  constexpr int SG = 16 / MT;  // MFMA steps whose A chunks are requested together
+  for (int kc = k_begin; kc < k_end; kc += kSkinnyChunkK) {
+    // 1. sixteen row loads in flight, each 1 KiB contiguous across the wave
+    u32x4 rows[16];
+    const uint32_t k_lane = (uint32_t)(kc + lane * 8);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = 16 * mt + ln;
-        fa[u][mt] = (k_ok && m < g.M) ? load_chunk<TA>(A + (int64_t)m * g.lda + k) : u32x4{0, 0, 0, 0};
+    for (int i = 0; i < 16; ++i)
+      rows[i] = __builtin_amdgcn_raw_buffer_load_b128(
+          b_rsrc, (int)(i < b_rows ? (uint32_t)(((int64_t)i * g.ldb + k_lane) * 2) : 0x80000000u), 0, 2);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(&wl[i * kSkinnyRow + lane * 8]) = rows[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // 2. MFMA steps of 32 k: B operand from the wave's LDS strip, A operand (few rows, cache resident)
+    //    from global, SG steps requested at a time. Chunks at k >= K are zeroed in A (the B strip may
+    //    hold the neighbouring range there).
+    const int steps = (min(kSkinnyChunkK, k_end - kc) + 31) / 32;
+    for (int s0 = 0; s0 < steps; s0 += SG) {
+      u32x4 fa[SG][MT];
+#pragma unroll
+      for (int u = 0; u < SG; ++u) {
+        const int k = kc + 32 * (s0 + u) + 8 * lg;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const u32x4 v = load_a(a_row[mt] + (uint32_t)(k * ES));
+          fa[u][mt] = k < g.K ? v : u32x4{0, 0, 0, 0};
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < SG; ++u) {
+        if (s0 + u >= steps) break;
+        union { u32x4 u4; bf16x8 v; } b;
+        b.u4 = *reinterpret_cast<const u32x4*>(&wl[ln * kSkinnyRow + 32 * (s0 + u) + 8 * lg]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          union { u32x4 u4; bf16x8 v; } a;
+          a.u4 = fa[u][mt];
+          acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
+        }
       }
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        union { u32x4 u; bf16x8 v; } a, b;
-        a.u = fa[u][mt], b.u = fb[u];
-        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc[mt], 0, 0, 0);
-      }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
+  // 3. sum the eight k ranges through LDS in a fixed order; the strip is reused as [wave][mt][lane] f32x4
+  __syncthreads();
+  f32x4* red = reinterpret_cast<f32x4*>(skinny_lds);
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) red[wave][mt][lane] = acc[mt];
+  for (int mt = 0; mt < MT; ++mt) red[(wave * MT + mt) * 64 + lane] = acc[mt];
   __syncthreads();
   if (wave < MT) {  // wave w finishes row tile w. Register e of lane l is row 4 * (l / 16) + e, column l % 16.
-    f32x4 sum = red[0][wave][lane];
+    f32x4 sum = red[wave * 64 + lane];
 #pragma unroll
-    for (int w = 1; w < kSkinnyWaves; ++w) sum += red[w][wave][lane];
+    for (int w = 1; w < kSkinnyWaves; ++w) sum += red[(w * MT + wave) * 64 + lane];
     const int n = n0 + ln;
     if (n < g.N) {
 #pragma unroll
@@ -362,14 +415,26 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const Ge
   }
 }
 
+constexpr size_t kSkinnyLdsBytes = (size_t)kSkinnyWaves * 16 * kSkinnyRow * sizeof(uint16_t);  // 133120
+
 template <typename TA, typename TC>
 static void launch_skinny(const GemmArgs& a, hipStream_t st) {
   const dim3 grid((a.N + 15) / 16), block(kSkinnyWaves * 64);
   const int mt = (a.M + 15) / 16;
-  if (mt == 1) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 1>), grid, block, 0, st, a);
-  else if (mt == 2) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 2>), grid, block, 0, st, a);
-  else if (mt == 3) hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 3>), grid, block, 0, st, a);
-  else hipLaunchKernelGGL((gemm_skinny_kernel<TA, TC, 4>), grid, block, 0, st, a);
+  auto go = [&](auto kern) {
+    // more than 64 KiB of dynamic LDS needs the attribute, once per kernel instance
+    static bool raised = false;
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)kSkinnyLdsBytes);
+      raised = true;
+    }
+    hipLaunchKernelGGL(kern, grid, block, kSkinnyLdsBytes, st, a);
+  };
+  if (mt == 1) go(gemm_skinny_kernel<TA, TC, 1>);
+  else if (mt == 2) go(gemm_skinny_kernel<TA, TC, 2>);
+  else if (mt == 3) go(gemm_skinny_kernel<TA, TC, 3>);
+  else go(gemm_skinny_kernel<TA, TC, 4>);
 }
 
 static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
