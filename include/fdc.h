@@ -83,6 +83,14 @@ fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff
 
 void fdc_layout_destroy(fdc_layout* lay);
 
+/* Per-head kept rank from singular values and the shared removal rate r (Section 5.2, Eq. 1):
+ * the last kept dimension j is the largest index with sum_{i >= j} theta_i > r * sum_i theta_i (the
+ * removed tail carries at most a fraction r of the singular-value mass); the kept rank is j + 1,
+ * rounded up to `multiple` (16 for the kernels, Section 6.1). Host arrays: theta double [n, d_head],
+ * each row in descending order; ranks int32 [n]. Tails are accumulated in double from the last
+ * dimension backwards, so the decision is reproducible. r >= 1 keeps one dimension. */
+fdc_status fdc_select_ranks(int n, int d_head, const double* theta, double r, int multiple, int32_t* ranks);
+
 /* ------------------------------------------------------------------------------------------
  * Work partitioner (Section 5.3). Host side, integer arithmetic only, deterministic.
  *

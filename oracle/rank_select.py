@@ -20,13 +20,21 @@ import numpy as np
 
 
 def last_kept_index(theta, r: float) -> int:
-    """j of Eq. (1): the largest j whose tail sum_{i >= j} theta_i / total exceeds r."""
-    theta = np.asarray(theta, dtype=np.float64)
-    total = float(np.sum(theta))
+    """j of Eq. (1): the largest j whose tail sum_{i >= j} theta_i / total exceeds r.
+
+    The tails are accumulated in float64 from the last dimension backwards,
+    tail_j = tail_{j+1} + theta_j, total = tail_0, and the test is written without the division,
+    tail_j > r * total, so that the decision is reproducible operation by operation.
+    """
+    theta = [float(t) for t in np.asarray(theta, dtype=np.float64)]
+    n = len(theta)
+    tails = [0.0] * (n + 1)
+    for j in range(n - 1, -1, -1):
+        tails[j] = tails[j + 1] + theta[j]
+    total = tails[0]
     j_found = 0
-    for j in range(len(theta)):
-        tail_j = float(np.sum(theta[j:])) / total
-        if tail_j > r:
+    for j in range(n):
+        if tails[j] > float(r) * total:
             j_found = j
     return j_found
 

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_prefill",
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
-    "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events",
+    "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
 ]
 
 
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
         l.fdc_profile_decode_events.argtypes = [vp, vp]
+        l.fdc_select_ranks.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.c_double, C.c_int, i32p]
         _lib = l
     return _lib
 
@@ -264,3 +265,14 @@ def fdc_absorb_output(layout: Layout, layer: int, mode: int, Bv, Wo, M, o_lat, o
 def fdc_profile_decode_events(start_event: Optional[int], stop_event: Optional[int]) -> None:
     """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
     _check(lib().fdc_profile_decode_events(start_event, stop_event))
+
+
+def fdc_select_ranks(theta, r: float, multiple: int = 16) -> np.ndarray:
+    """theta: float64 [n, d_head] singular values per head (descending). Returns int32 [n]."""
+    th = np.ascontiguousarray(np.asarray(theta, dtype=np.float64))
+    if th.ndim != 2:
+        raise ValueError("theta must be [n, d_head]")
+    out = np.zeros(th.shape[0], dtype=np.int32)
+    _check(lib().fdc_select_ranks(th.shape[0], th.shape[1], th.ctypes.data_as(C.POINTER(C.c_double)), float(r),
+                                  int(multiple), _p32(out)))
+    return out

@@ -126,6 +126,24 @@ fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff
 
 void fdc_layout_destroy(fdc_layout* lay) { delete lay; }
 
+// ------------------------------------------------------------------------------------ rank selection
+fdc_status fdc_select_ranks(int n, int d_head, const double* theta, double r, int multiple, int32_t* ranks) {
+  if (!theta || !ranks) FDC_FAIL(FDC_INVALID_ARG, "fdc_select_ranks: NULL argument");
+  if (n < 0 || d_head <= 0 || multiple <= 0) FDC_FAIL(FDC_BAD_SHAPE, "fdc_select_ranks: bad sizes");
+  std::vector<double> tails((size_t)d_head + 1);
+  for (int h = 0; h < n; ++h) {
+    const double* th = theta + (size_t)h * d_head;
+    tails[d_head] = 0.0;
+    for (int j = d_head - 1; j >= 0; --j) tails[j] = tails[j + 1] + th[j];
+    const double bound = r * tails[0];
+    int j_found = 0;
+    for (int j = 0; j < d_head; ++j)
+      if (tails[j] > bound) j_found = j;
+    ranks[h] = (int32_t)((j_found + 1 + multiple - 1) / multiple * multiple);
+  }
+  return FDC_OK;
+}
+
 // ------------------------------------------------------------------------------------ planner
 void fdc_plan_params_default(fdc_plan_params* p) {
   if (!p) return;

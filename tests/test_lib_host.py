@@ -123,6 +123,27 @@ def test_prefill_plan_bit_exact(mode):
         _prefill_case(rk, rv, q, kv, int(g.integers(1, 70)), mode, sc=int(g.choice([1, 3, 400])))
 
 
+def test_select_ranks_bit_exact_with_oracle():
+    """Eq. (1): the library's rank choice equals the oracle's on planted, random and tie-prone spectra."""
+    from oracle import rank_select as ors
+    g = gen.make_rng(5)
+    spectra = [np.exp(-np.arange(128) / 32.0), np.exp(-np.arange(64) / 8.0), np.ones(48),
+               np.sort(g.random(128))[::-1], np.sort(g.random(16))[::-1] ** 4,
+               np.array([8.0, 4.0, 2.0, 1.0, 1.0, 0.0, 0.0, 0.0])]
+    for th in spectra:
+        # removal rates including exact tail fractions of the flat / dyadic spectra (ties)
+        rates = [0.0, 1e-9, 0.001, 0.01, 0.0625, 0.125, 0.25, 0.3, 0.5, 0.75, 0.9, 0.999, 1.0, 2.0]
+        for mult in (1, 16):
+            for r in rates:
+                ref = ors.kept_rank(th, r, mult)
+                got = fdc.fdc_select_ranks(th[None, :], r, mult)
+                assert got.tolist() == [ref], (len(th), r, mult)
+    th = np.stack([np.exp(-np.arange(128) / c) for c in (4.0, 8.0, 16.0, 32.0, 64.0)])
+    got = fdc.fdc_select_ranks(th, 0.05)
+    assert got.tolist() == [ors.kept_rank(t, 0.05) for t in th]
+    assert np.all(np.diff(got) >= 0)            # slower decay keeps more dimensions
+
+
 def test_error_codes_without_gpu():
     with pytest.raises(fdc.FdcError) as e:
         _layout([[16, 24]], [[16, 16]], 1, 8)
