@@ -297,6 +297,16 @@ def run_prefill_workload(fdc, gen, iters=3):
         "absorb_output_fold": (lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_FOLD, Bv, Wo_t, Mt, None, 0, 0, None, 0), 2.0 * RV * dh * d),
         "absorb_output_apply": (lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt, o_lat, fdc.FDC_BF16, T, y, fdc.FDC_BF16), 2.0 * T * RV * d),
     }
+    # post-RoPE variant of the K / Q side (Section 5.1): RoPE + rotation truncated to r_h columns
+    k_pre = torch.randn(T, H, dh, generator=gt, device=dev).to(bf)
+    R_t = (torch.randn(RK, dh, generator=gt, device=dev) / math.sqrt(dh)).to(bf)
+    ang = torch.arange(S, device=dev, dtype=torch.float32)[:, None] * \
+        (10000.0 ** (-2.0 * torch.arange(dh // 2, device=dev, dtype=torch.float32) / dh))[None, :]
+    cos_t, sin_t = torch.cos(ang).contiguous(), torch.sin(ang).contiguous()
+    calls["rope_compress_keys"] = (lambda: fdc.fdc_rope_compress_keys(lay, 0, k_pre, tb, tp, cos_t, sin_t, R_t, kc),
+                                   2.0 * T * dh * RK)
+    calls["rope_absorb_query"] = (lambda: fdc.fdc_rope_absorb_query(lay, 0, q, tp, cos_t, sin_t, R_t, q_lat, fdc.FDC_BF16),
+                                  2.0 * T * dh * RK)
     out = {"workload": "config 5: B=4, S=4096, d_model 4096, 32 heads, adaptive ranks", "plan_host_ms": plan_ms}
     total_ms = 0.0
     for name, (fn, flops) in calls.items():
@@ -309,7 +319,8 @@ def run_prefill_workload(fdc, gen, iters=3):
         e.record()
         torch.cuda.synchronize()
         ms = s.elapsed_time(e) / iters
-        total_ms += ms
+        if not name.startswith("rope_"):
+            total_ms += ms          # the five calls of the RoPE-free chain; the post-RoPE calls are alternatives
         out[name] = {"ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     out["total_ms"] = total_ms
     return out

@@ -181,7 +181,8 @@ void fdc_plan_destroy(fdc_plan* plan);
  *                                               (the "out x in" order of a linear layer); rows: all K
  *                                               heads (head-major), then all V heads
  *   k_cache, v_cache    the layer's K' / V' buffers (sizes from fdc_layout_tables)
- * T = 0 is a no-op. */
+ * k_cache may be NULL: then A_cat_t holds only the RV value rows and only V' is written (post-RoPE
+ * path, where K' comes from fdc_rope_compress_keys). T = 0 is a no-op. */
 fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x, int T,
                                  const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
                                  void* k_cache, void* v_cache, void* stream);
@@ -192,6 +193,25 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
  *   q_lat  [T, RK]               q_lat_dtype (F32 for decode, BF16 for prefill) */
 fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const void* Bk,
                             void* q_lat, fdc_dtype q_lat_dtype, void* stream);
+
+/* Post-RoPE compression of Q and K (Section 5.1; steps 5 and 6 of the design overview): RoPE, then
+ * the common rotation R of the head truncated to its first r_h columns, (Q_p R_p)(K_p R_p)^T ~= Q_p K_p^T.
+ * Attention, planning and the V path are unchanged; K' of the cache is written by
+ * fdc_rope_compress_keys instead of fdc_project_latent_kv. BF16 layouts only.
+ *   q, k      [T, H, d_head]   pre-RoPE rows of every head (outputs of the model's own W_Q / W_K)
+ *   tok_pos   int32 [T]        position of each row, 0 <= tok_pos < n_pos (and < max_seq for keys)
+ *   tok_batch int32 [T]        sequence of each key row
+ *   cos_t, sin_t  f32 [n_pos, d_head / 2]   RoPE angles; the pair (2i, 2i+1) of a row at position p is
+ *                              rotated by the angle whose cosine / sine is cos_t[p, i] / sin_t[p, i]
+ *   R_t       [RK, d_head]     head h = rows koff_r[h] .. koff_r[h+1]: the first rk[h] columns of R^h,
+ *                              one kept direction per row (the layout of Bk)
+ *   q_lat     [T, RK] (q_lat_dtype);   k_cache: the layer's K' buffer. */
+fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const int32_t* tok_pos,
+                                 const float* cos_t, const float* sin_t, int n_pos, const void* R_t,
+                                 void* q_lat, fdc_dtype q_lat_dtype, void* stream);
+fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* k, int T,
+                                  const int32_t* tok_batch, const int32_t* tok_pos, const float* cos_t,
+                                  const float* sin_t, int n_pos, const void* R_t, void* k_cache, void* stream);
 
 /* Decode attention on the latent cache, one query per sequence (Section 5, step 7; Section 5.3
  * decode scheduling): o'_h = softmax_t(scale * <q'_h, K'_h[t]>) . V'_h over t < seq_len[b].

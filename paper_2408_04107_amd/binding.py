@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
+    "fdc_rope_absorb_query", "fdc_rope_compress_keys",
 ]
 
 
@@ -85,6 +86,8 @@ def lib() -> C.CDLL:
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
         l.fdc_profile_decode_events.argtypes = [vp, vp]
+        l.fdc_rope_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, C.c_int, vp]
+        l.fdc_rope_compress_keys.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp]
         l.fdc_select_ranks.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.c_double, C.c_int, i32p]
         _lib = l
     return _lib
@@ -276,3 +279,17 @@ def fdc_select_ranks(theta, r: float, multiple: int = 16) -> np.ndarray:
     _check(lib().fdc_select_ranks(th.shape[0], th.shape[1], th.ctypes.data_as(C.POINTER(C.c_double)), float(r),
                                   int(multiple), _p32(out)))
     return out
+
+
+def fdc_rope_absorb_query(layout: Layout, layer: int, q, tok_pos, cos_t, sin_t, R_t, q_lat, q_lat_dtype: int,
+                          stream=None) -> None:
+    _check(lib().fdc_rope_absorb_query(layout.handle, layer, _dev(q), int(q.shape[0]), _dev(tok_pos), _dev(cos_t),
+                                       _dev(sin_t), int(cos_t.shape[0]), _dev(R_t), _dev(q_lat), q_lat_dtype,
+                                       _stream(stream)))
+
+
+def fdc_rope_compress_keys(layout: Layout, layer: int, k, tok_batch, tok_pos, cos_t, sin_t, R_t, k_cache,
+                           stream=None) -> None:
+    _check(lib().fdc_rope_compress_keys(layout.handle, layer, _dev(k), int(k.shape[0]), _dev(tok_batch),
+                                        _dev(tok_pos), _dev(cos_t), _dev(sin_t), int(cos_t.shape[0]), _dev(R_t),
+                                        _dev(k_cache), _stream(stream)))

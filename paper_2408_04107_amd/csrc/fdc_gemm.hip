@@ -30,6 +30,10 @@ struct GemmArgs {
   int RK, RV;
   const int32_t* tok_batch;
   const int32_t* tok_pos;
+  int v_only;             // project: B holds only the V' rows, every column goes to the V' cache
+  const float* rope_cos;  // post-RoPE path: [n_pos, d_head / 2]
+  const float* rope_sin;
+  int n_pos;
   int32_t koff_r[kMaxHeads + 1];
   int32_t voff_r[kMaxHeads + 1];
 };
@@ -73,8 +77,8 @@ __device__ __forceinline__ void store_out<uint16_t>(uint16_t* p, float v) { *p =
 // Cache element for output column n of the concatenated [K heads | V heads] projection.
 // Returns the buffer (0 = K', 1 = V') and the element offset for token (b, pos).
 __device__ __forceinline__ int64_t project_dst(const GemmArgs& g, int n, int b, int pos, int* side) {
-  const int s = n >= g.RK;
-  const int c = s ? n - g.RK : n;
+  const int s = g.v_only ? 1 : n >= g.RK;
+  const int c = (s && !g.v_only) ? n - g.RK : n;
   const int32_t* off_r = s ? g.voff_r : g.koff_r;
   int lo = 0, hi = g.H;  // largest h with off_r[h] <= c
   while (hi - lo > 1) {
@@ -437,6 +441,79 @@ static void launch_skinny(const GemmArgs& a, hipStream_t st) {
   else go(gemm_skinny_kernel<TA, TC, 4>);
 }
 
+// ---- post-RoPE compression (Section 5.1: RoPE, then the rotation R truncated to r_h columns) ----
+// One workgroup = 64 token rows of one head. The pre-RoPE rows are rotated pair-wise in fp32 while
+// they are staged (pairs (2i, 2i+1), angles from the caller's cos / sin tables), rounded to bf16 and
+// multiplied with the head's R_t rows (r_h x d_head, K = d_head <= 128, so the whole product is one
+// LDS stage and 4 k-steps of v_mfma_f32_16x16x32_bf16). Queries go to q_lat, keys into the K' cache.
+constexpr int kRopeRows = 64;
+constexpr int kRopeLdsRow = 128 + 8;
+
+template <typename TC, bool KEYS>
+__global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_a[kRopeRows * kRopeLdsRow];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRopeLdsRow];
+  const int h = blockIdx.y, t0 = blockIdx.x * kRopeRows;
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int r = g.koff_r[h + 1] - g.koff_r[h];
+  const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)h * g.d_head;  // row stride lda = H * d_head
+  const uint16_t* Rt = static_cast<const uint16_t*>(g.B) + (int64_t)g.koff_r[h] * g.d_head;
+  const int half = g.d_head / 2;
+  // stage A with RoPE: 64 rows x 16 chunks of 8 elements
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = tid + 256 * i, row = c / 16, kc = c % 16;
+    u32x4 out = {0, 0, 0, 0};
+    if (t0 + row < g.M && kc * 8 < g.d_head) {
+      const u32x4 raw = *reinterpret_cast<const u32x4*>(X + (int64_t)(t0 + row) * g.lda + kc * 8);
+      const int pos = min(max(g.tok_pos[t0 + row], 0), g.n_pos - 1);
+      const float4 cs = *reinterpret_cast<const float4*>(g.rope_cos + (int64_t)pos * half + kc * 4);
+      const float4 sn = *reinterpret_cast<const float4*>(g.rope_sin + (int64_t)pos * half + kc * 4);
+      const float cc[4] = {cs.x, cs.y, cs.z, cs.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float xe = __uint_as_float(raw[j] << 16), xo = __uint_as_float(raw[j] & 0xffff0000u);
+        out[j] = cvt_pk_bf16(xe * cc[j] - xo * ss[j], xe * ss[j] + xo * cc[j]);
+      }
+    }
+    *reinterpret_cast<u32x4*>(&lds_a[row * kRopeLdsRow + kc * 8]) = out;
+  }
+  // stage B: the head's kept directions, 128 rows x 16 chunks (rows >= r and columns >= d_head are zero)
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int c = tid + 256 * i, row = c / 16, kc = c % 16;
+    const u32x4 v = (row < r && kc * 8 < g.d_head) ? *reinterpret_cast<const u32x4*>(Rt + (int64_t)row * g.d_head + kc * 8)
+                                                   : u32x4{0, 0, 0, 0};
+    *reinterpret_cast<u32x4*>(&lds_b[row * kRopeLdsRow + kc * 8]) = v;
+  }
+  __syncthreads();
+  const int ksteps = (g.d_head + 31) / 32;
+  for (int nt = 0; nt < r / 16; ++nt) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < ksteps; ++ks) {
+      union { u32x4 u; bf16x8 v; } a, b;
+      a.u = *reinterpret_cast<const u32x4*>(&lds_a[(16 * wave + ln) * kRopeLdsRow + 32 * ks + 8 * lg]);
+      b.u = *reinterpret_cast<const u32x4*>(&lds_b[(16 * nt + ln) * kRopeLdsRow + 32 * ks + 8 * lg]);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc, 0, 0, 0);
+    }
+    // register e of lane l is row 4 * (l / 16) + e, column l % 16
+    const int n = 16 * nt + ln;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int t = t0 + 16 * wave + 4 * lg + e;
+      if (t >= g.M) continue;
+      if constexpr (KEYS) {
+        const int64_t dst = (int64_t)g.tok_batch[t] * g.max_seq * g.RK + (int64_t)g.max_seq * g.koff_r[h] +
+                            (int64_t)g.tok_pos[t] * r + n;
+        static_cast<uint16_t*>(g.C)[dst] = f32_to_bf16(acc[e]);
+      } else {
+        store_out(static_cast<TC*>(g.C) + (int64_t)t * g.RK + g.koff_r[h] + n, acc[e]);
+      }
+    }
+  }
+}
+
 static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
   const int H = lay->H;
   a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq;
@@ -492,15 +569,16 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
   fdc_status s = check_common("fdc_project_latent_kv", lay, layer, T);
   if (s != FDC_OK) return s;
   if (T == 0) return FDC_OK;
-  if (!x || !tok_batch || !tok_pos || !A_cat_t || !k_cache || !v_cache)
+  if (!x || !tok_batch || !tok_pos || !A_cat_t || !v_cache)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_project_latent_kv: NULL argument");
-  if (!aligned16(x) || !aligned16(A_cat_t) || !aligned16(k_cache) || !aligned16(v_cache))
+  if (!aligned16(x) || !aligned16(A_cat_t) || (k_cache && !aligned16(k_cache)) || !aligned16(v_cache))
     FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_project_latent_kv: pointers must be 16-byte aligned");
   GemmArgs a{};
   fill_tables(a, lay, layer);
   a.A = x, a.B = A_cat_t, a.C = k_cache, a.C2 = v_cache;
   a.lda = lay->d_model, a.ldb = lay->d_model, a.ldc = 0;
-  a.M = T, a.N = a.RK + a.RV, a.K = lay->d_model;
+  a.v_only = k_cache == nullptr;
+  a.M = T, a.N = a.v_only ? a.RV : a.RK + a.RV, a.K = lay->d_model;
   a.mode = kProject;
   a.tok_batch = tok_batch, a.tok_pos = tok_pos;
   return launch(lay, a, 1, a.N, false, false, static_cast<hipStream_t>(stream));
@@ -563,6 +641,56 @@ fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const v
     return launch(lay, a, 1, a.N, o_lat_dtype == FDC_F32, y_dtype == FDC_F32, st);
   }
   FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output: mode %d", mode);
+}
+
+static fdc_status rope_common(const char* fn, const fdc_layout* lay, int layer, const void* x, int T,
+                              const int32_t* tok_pos, const float* cos_t, const float* sin_t, int n_pos,
+                              const void* R_t, void* out, GemmArgs* a) {
+  fdc_status s = check_common(fn, lay, layer, T);
+  if (s != FDC_OK) return s;
+  if (lay->dtype != FDC_BF16) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "%s: bf16 layouts only", fn);
+  if (!x || !tok_pos || !cos_t || !sin_t || !R_t || !out) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
+  if (n_pos <= 0) FDC_FAIL(FDC_BAD_SHAPE, "%s: n_pos must be positive", fn);
+  if (!aligned16(x) || !aligned16(cos_t) || !aligned16(sin_t) || !aligned16(R_t) || !aligned16(out))
+    FDC_FAIL(FDC_BAD_ALIGNMENT, "%s: pointers must be 16-byte aligned", fn);
+  fill_tables(*a, lay, layer);
+  a->A = x, a->B = R_t, a->C = out;
+  a->lda = (int64_t)lay->H * lay->d_head;
+  a->M = T, a->K = lay->d_head;
+  a->tok_pos = tok_pos, a->rope_cos = cos_t, a->rope_sin = sin_t, a->n_pos = n_pos;
+  return FDC_OK;
+}
+
+fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const int32_t* tok_pos,
+                                 const float* cos_t, const float* sin_t, int n_pos, const void* R_t, void* q_lat,
+                                 fdc_dtype q_lat_dtype, void* stream) {
+  if (T == 0 && lay) return FDC_OK;
+  GemmArgs a{};
+  fdc_status s = rope_common("fdc_rope_absorb_query", lay, layer, q, T, tok_pos, cos_t, sin_t, n_pos, R_t, q_lat, &a);
+  if (s != FDC_OK) return s;
+  if (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_rope_absorb_query: q_lat_dtype");
+  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H);
+  if (q_lat_dtype == FDC_F32)
+    hipLaunchKernelGGL((rope_compress_kernel<float, false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  else
+    hipLaunchKernelGGL((rope_compress_kernel<uint16_t, false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
+}
+
+fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* k, int T, const int32_t* tok_batch,
+                                  const int32_t* tok_pos, const float* cos_t, const float* sin_t, int n_pos,
+                                  const void* R_t, void* k_cache, void* stream) {
+  if (T == 0 && lay) return FDC_OK;
+  GemmArgs a{};
+  fdc_status s = rope_common("fdc_rope_compress_keys", lay, layer, k, T, tok_pos, cos_t, sin_t, n_pos, R_t, k_cache, &a);
+  if (s != FDC_OK) return s;
+  if (!tok_batch) FDC_FAIL(FDC_INVALID_ARG, "fdc_rope_compress_keys: tok_batch is NULL");
+  a.tok_batch = tok_batch;
+  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H);
+  hipLaunchKernelGGL((rope_compress_kernel<uint16_t, true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
 }
 
 }  // extern "C"
