@@ -292,6 +292,258 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
+// ---- bf16 MFMA kernel for the large products (prefill: M = tokens of the batch) ----------------
+// Workgroup tile 256 x 256, k stage 64, eight waves in a 2 x 4 grid, each wave 128 x 64 as 4 x 2
+// v_mfma_f32_32x32x16_bf16 tiles. Both operands go from global memory straight into LDS
+// (buffer_load ... lds, 16 bytes per lane), two stages of 64 KiB in a ring: while stage t is
+// multiplied, stage t+1 is in flight, and stage t+2 is requested as soon as every wave has read the
+// last fragment of stage t. A wave-wide load fills 1 KiB of LDS in lane order, so the padding that
+// keeps fragment reads conflict free is replaced by a swizzle: tile row r keeps its 16-byte chunk c
+// at position c ^ ((r / 2) % 8) of its 128-byte LDS row, which the loading lane applies to its
+// global address and the reading lane to its LDS address. Rows past M / N and the k tail are
+// zero-filled by the buffer range check (their offsets are forced out of range), so the loop has
+// no conditional loads. The loads are issued through inline assembly: the compiler then keeps no
+// dependency between them and the LDS reads, and the kernel orders the two itself with vmcnt waits
+// in front of its barriers.
+// The chip is power limited on this kernel (the shader clock falls from 2.4 to about 1.3-1.5 GHz
+// while it runs), so what counts is work per byte moved: the 256 x 256 tile halves the L2 -> LDS
+// traffic per flop of a 256 x 128 tile, and the epilogue writes full 128-byte lines.
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+constexpr int DM = 256, DN = 256, DK = 64;
+constexpr int kDmaStage = (DM + DN) * DK;     // elements per ring stage (A rows, then B rows)
+constexpr int kDmaLoads = (DM + DN) / 64;     // wave-wide loads per wave and stage (8 tile rows each)
+
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, int soff) {
+  // lane l of the wave lands at lds_addr + 16 * l
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32)),
+               __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+constexpr int vm_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x70 | 0xF00; }  // s_waitcnt vmcnt(n) only
+
+template <typename TC>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_dma_kernel(const GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * kDmaStage];
+  // tile order: XCD-major, then 8 row tiles down before the next column tile (see gemm_bf16_kernel)
+  const int mt = (g.M + DM - 1) / DM, nt = g.nt;
+  const int tiles = mt * nt, per_xcd = (tiles + 7) / 8;
+  const int lin = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (lin >= tiles) return;
+  constexpr int GM = 8;
+  const int band = lin / (GM * nt), in_band = lin % (GM * nt);
+  const int band_rows = min(GM, mt - band * GM);
+  const int tm = band * GM + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * DM, n0 = tn * DN;
+  const int M = g.M, N = g.N, K = g.K;
+
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
+  const int wm = (wave / 4) * 128, wn = (wave % 4) * 64;
+  const uint16_t* A = static_cast<const uint16_t*>(g.A);
+  const uint16_t* B = static_cast<const uint16_t*>(g.B);
+  const int a_rows = min(DM, M - m0), b_rows = min(DN, N - n0);
+  const i32x4 a_rsrc = make_rsrc(A + (int64_t)m0 * g.lda, (uint32_t)(((int64_t)(a_rows - 1) * g.lda + K) * 2));
+  const i32x4 b_rsrc = make_rsrc(B + (int64_t)n0 * g.ldb, (uint32_t)(((int64_t)(b_rows - 1) * g.ldb + K) * 2));
+
+  // the lane's source in a wave-wide load: tile row lane / 8 of the wave's 8 rows, LDS chunk lane % 8
+  const int l_row = wave * 8 + lane / 8;
+  const int l_chunk = (lane % 8) ^ ((l_row / 2) % 8);
+  constexpr uint32_t kOob = 0x80000000u;
+  const int nk = (K + DK - 1) / DK;
+  const int k_tail0 = (nk - 1) * DK;
+  const bool has_tail = (K % DK) != 0;
+  const bool tail_ok = k_tail0 + l_chunk * 8 < K;
+  uint32_t a_off[4], b_off[4], a_tail[4], b_tail[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = j * 64 + l_row;
+    a_off[j] = row < a_rows ? (uint32_t)(((int64_t)row * g.lda + l_chunk * 8) * 2) : kOob;
+    b_off[j] = row < b_rows ? (uint32_t)(((int64_t)row * g.ldb + l_chunk * 8) * 2) : kOob;
+    // the tail stage carries k0 in the range-checked offset, so nothing past a row's end is read
+    a_tail[j] = (row < a_rows && tail_ok) ? a_off[j] + (uint32_t)(k_tail0 * 2) : kOob;
+    b_tail[j] = (row < b_rows && tail_ok) ? b_off[j] + (uint32_t)(k_tail0 * 2) : kOob;
+  }
+  const uint32_t lds0 = lds_addr_of(lds) + (uint32_t)(wave * 8 * DK * 2);
+  // load q (0..3: A rows, 4..7: B rows) of stage t into ring buffer s
+  auto issue1 = [&](int s, int t, int q) {
+    const bool is_a = q < 4;
+    const int j = q & 3;
+    const uint32_t dst = lds0 + (uint32_t)((s * kDmaStage + (is_a ? 0 : DM * DK) + j * 64 * DK) * 2);
+    const bool tail = has_tail && t == nk - 1;
+    const uint32_t voff = is_a ? (tail ? a_tail[j] : a_off[j]) : (tail ? b_tail[j] : b_off[j]);
+    dma16(is_a ? a_rsrc : b_rsrc, dst, voff, tail ? 0 : t * DK * 2);
+  };
+
+  // fragment addressing: row lane % 32 of a 32-row block, chunk 2 * kstep + lane / 32
+  const int f_row = lane % 32;
+  int f_off[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) f_off[s] = f_row * DK + (((2 * s + lane / 32) ^ ((f_row / 2) % 8)) * 8);
+
+  f32x16 acc[4][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
+  auto load_frag = [&](int s, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
+    const uint16_t* sa = lds + s * kDmaStage + wm * DK;
+    const uint16_t* sb = lds + s * kDmaStage + DM * DK + wn * DK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sa[i * 32 * DK + f_off[ks]]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&sb[j * 32 * DK + f_off[ks]]);
+  };
+  // operands swapped: the accumulator tile is C^T, a lane holds one m and runs of four n
+  auto mma = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+  };
+  constexpr int kVm0Lgkm0 = 0x0070;   // s_waitcnt vmcnt(0) lgkmcnt(0)
+
+  // Stage t in ring buffer s; fragments of its k step 0 are in fa0/fb0 on entry. Straight-line
+  // (the last stage reads the other buffer into registers nobody uses) so that the compiler's wait
+  // counters see one path and leave the reads in flight across the multiplies. The scheduling
+  // barriers pin "reads of the next k step first, then the multiplies that hide them".
+  auto step = [&](int s, int t) {
+    load_frag(s, 1, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frag(s, 2, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frag(s, 3, fa1, fb1);
+    __builtin_amdgcn_sched_barrier(0);
+    mma(fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    // this wave's reads of stage t have returned and its part of stage t+1 has landed; after the
+    // barrier that holds for every wave and buffer s can be refilled with stage t+2
+    __builtin_amdgcn_s_waitcnt(kVm0Lgkm0);
+    asm volatile("s_barrier" ::: "memory");
+    load_frag(1 - s, 0, fa0, fb0);
+    __builtin_amdgcn_sched_barrier(0);
+    const bool more = t + 2 < nk;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {   // the eight loads of stage t+2 go between the last eight multiplies
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[j], fa1[i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue1(s, t + 2, i * 2 + j);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+  };
+
+#pragma unroll
+  for (int q = 0; q < kDmaLoads; ++q) issue1(0, 0, q);
+  if (1 < nk) {
+#pragma unroll
+    for (int q = 0; q < kDmaLoads; ++q) issue1(1, 1, q);
+    __builtin_amdgcn_s_waitcnt(vm_imm(kDmaLoads));
+  } else {
+    __builtin_amdgcn_s_waitcnt(vm_imm(0));
+  }
+  asm volatile("s_barrier" ::: "memory");
+  load_frag(0, 0, fa0, fb0);
+  const int pairs = (nk - 1) / 2;   // pairs of stages in which every stage has a successor
+  int t = 0;
+  for (int p = 0; p < pairs; ++p, t += 2) {
+    step(0, t);
+    step(1, t + 1);
+  }
+  step(0, t);
+  if (nk - t > 1) step(1, t + 1);
+
+  // Epilogue. Accumulator (i, j): register e of lane l is n = wn + j*32 + (e/4)*8 + (l/32)*4 + e%4,
+  // m = wm + i*32 + l%32.
+  if constexpr (sizeof(TC) == 4) {
+    // fp32 C (plain mode only): 16 bytes per lane straight from the registers
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + wm + i * 32 + lane % 32;
+      if (m >= M) continue;
+      float* crow = static_cast<float*>(g.C) + (int64_t)m * g.ldc;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int n = n0 + wn + j * 32 + gq * 8 + (lane / 32) * 4;
+          if (n + 3 < N && g.ldc % 4 == 0) {
+            *reinterpret_cast<float4*>(crow + n) = float4{acc[i][j][gq * 4], acc[i][j][gq * 4 + 1], acc[i][j][gq * 4 + 2], acc[i][j][gq * 4 + 3]};
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) if (n + e < N) crow[n + e] = acc[i][j][gq * 4 + e];
+          }
+        }
+    }
+  } else {
+    // bf16 C: each wave turns 64 of its rows at a time into bf16 in a private LDS region (row
+    // stride 144 bytes) and streams them out as 16-byte chunks; 8 lanes cover one 128-byte row of
+    // the wave's tile, so a store instruction writes 8 full lines (plain) or 8 runs of 128 bytes
+    // of one token's latent rows (project).
+    asm volatile("s_barrier" ::: "memory");   // every wave is done with the last stage
+    constexpr int EROW = 72;
+    uint16_t* ep = lds + wave * (64 * EROW);
+    const int c = lane % 8;
+    const int n = n0 + wn + c * 8;
+    int side = 0, rank = 0;
+    int64_t col_off = 0, seq_stride = 0;
+    if (g.mode == kProject && n < N) {   // the 8 columns of a chunk lie in one head: ranks are multiples of 16
+      col_off = project_dst(g, n, 0, 0, &side);
+      rank = (int)(project_dst(g, n, 0, 1, &side) - col_off);
+      seq_stride = (int64_t)g.max_seq * (side ? g.RV : g.RK);
+    }
+    uint16_t* cbase = static_cast<uint16_t*>((g.mode == kProject && side) ? g.C2 : g.C);
+    const bool wide = g.mode == kProject || g.ldc % 8 == 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const int i = 2 * h + ii;
+            uint2 v;
+            v.x = cvt_pk_bf16(acc[i][j][gq * 4 + 0], acc[i][j][gq * 4 + 1]);
+            v.y = cvt_pk_bf16(acc[i][j][gq * 4 + 2], acc[i][j][gq * 4 + 3]);
+            *reinterpret_cast<uint2*>(&ep[(ii * 32 + lane % 32) * EROW + j * 32 + gq * 8 + (lane / 32) * 4]) = v;
+          }
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row = it * 8 + lane / 8;
+        const int m = m0 + wm + h * 64 + row;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(&ep[row * EROW + c * 8]);
+        if (m >= M || n >= N) continue;
+        uint16_t* dst = g.mode == kProject
+                            ? cbase + (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank
+                            : cbase + (int64_t)m * g.ldc + n;
+        if (n + 7 < N && wide) {
+          *reinterpret_cast<u32x4*>(dst) = v;
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (n + e < N) dst[e] = (uint16_t)(v[e / 2] >> (16 * (e % 2)));
+        }
+      }
+    }
+  }
+}
+
 // ---- bf16 MFMA kernel for few rows (decode: M = batch) ------------------------------------------
 // With M <= 64 the product is a weight stream: every B row (K contiguous bf16) is read once and
 // the kernel is bound by HBM, not by MFMA. A workgroup of eight waves owns 16 rows of B; the
@@ -535,6 +787,14 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     else if (a_f32) launch_skinny<float, uint16_t>(a, st);
     else if (c_f32) launch_skinny<uint16_t, float>(a, st);
     else launch_skinny<uint16_t, uint16_t>(a, st);
+  } else if (!a_f32 && groups == 1 && (a.mode == kPlain || a.mode == kProject) && a.K % 8 == 0 && a.lda % 8 == 0 &&
+             a.ldb % 8 == 0) {
+    GemmArgs b = a;
+    b.nt = (a.N + DN - 1) / DN;
+    const int tiles = b.nt * ((a.M + DM - 1) / DM);
+    const dim3 grid((tiles + 7) / 8 * 8);
+    if (c_f32) hipLaunchKernelGGL(gemm_dma_kernel<float>, grid, dim3(512), 0, st, b);
+    else hipLaunchKernelGGL(gemm_dma_kernel<uint16_t>, grid, dim3(512), 0, st, b);
   } else {
     GemmArgs b = a;
     b.nt = (n_max + BN - 1) / BN;
