@@ -49,6 +49,23 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {  // v_cvt_pk
   return r.u;
 }
 
+// Reductions over the four lanes l, l ^ 16, l ^ 32, l ^ 48 that share a query row, with the lane
+// swaps of gfx950 (v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the
+// even rows of its second, v_permlane32_swap the upper half of the first with the lower half of
+// the second), which stay in the vector ALU instead of going through LDS like a generic shuffle.
+__device__ __forceinline__ float row_max(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float row_sum(float v) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 union Frag {
   u32x4 u;
   bf16x8 v;
@@ -195,11 +212,11 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
           for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e) mx = fmaxf(mx, st[j][i][e]);
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
           // The reference m of a row is raised only when the block beats it by kRaise (in log2 units of
           // the scaled score), so p stays below 2^kRaise and most blocks need no rescale of O at all.
+          // The test needs no row maximum: a row beats its reference iff one of its four lanes does.
           if (__any(mx * scale_log2 > m_run[i] * scale_log2 + kRaise)) {
+            mx = row_max(mx);
             const float m_new = fmaxf(m_run[i], mx);
             // a row with nothing visible yet keeps m = -inf; exp2(-inf - 0) = 0 scales the empty state
             const float m_ref = m_new == -INFINITY ? 0.f : m_new;
@@ -257,9 +274,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     // finish: l over the four lanes of a row, normalise, store. Lane (ln, lg) holds O[row ln][16 c + 4 lg + e].
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      float l = l_run[i];
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
+      const float l = row_sum(l_run[i]);
       const float inv = l > 0.f ? 1.f / l : 0.f;
       const int row = wrow0 + 16 * i + ln;
       if (row < t.rows) {
