@@ -74,6 +74,22 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
                              const int32_t* rk, const int32_t* rv, int max_batch, int max_seq,
                              fdc_dtype dtype, fdc_layout** out);
 
+/* Grouped-query layout (Section 5.1, GQA paragraph): n_kv_heads key/value heads, each shared by
+ * q_per_kv consecutive query heads (query head hq uses key/value head hq / q_per_kv); 1 <= q_per_kv
+ * <= 16 and n_kv_heads * q_per_kv <= 128. The cache, rk, rv and every table above are per key/value
+ * head exactly as in fdc_layout_create (which is q_per_kv = 1). What changes is the width of the
+ * query-side tensors, ragged by QUERY head in head order:
+ *     q [T, Hq, d_head], Hq = n_kv_heads * q_per_kv
+ *     q_lat [T, g*RK]: query head hq at columns g*koff_r[h] + j*rk[h] .. + rk[h]   (h = hq / g, j = hq % g)
+ *     o_lat [T, g*RV]: the same with voff_r, rv
+ *     Wo_t [d_model, Hq*d_head], Mt [d_model, g*RV]   (M_hq = B_v^h . W_o^hq)
+ * Bk, Bv, R_t, A_cat_t stay per key/value head. fdc_latent_attn_decode reads K', V' of a head once for
+ * its whole query group; prefill plans one task list per query head (item_h is the query head).
+ * Grouped decode attention needs a BF16 layout. */
+fdc_status fdc_layout_create_gqa(int n_layers, int n_kv_heads, int q_per_kv, int d_model, int d_head,
+                                 const int32_t* rk, const int32_t* rv, int max_batch, int max_seq,
+                                 fdc_dtype dtype, fdc_layout** out);
+
 /* Writes the offset tables to host arrays (any pointer may be NULL to skip it):
  *   koff, voff  int64 [L*H]      element offset of unit (0, h) inside the layer's buffer
  *   koff_r, voff_r int32 [L*(H+1)] prefix sums of the ranks (column offsets in [T, RK] tensors)
@@ -126,7 +142,8 @@ typedef struct {
 void fdc_plan_params_default(fdc_plan_params* p);
 
 /* Number of workers that are resident at once on the current HIP device for the decode
- * (kind 0) or prefill (kind 1) kernel. Needs a GPU (FDC_HIP_ERROR otherwise). */
+ * (kind 0), prefill (kind 1) or grouped-query decode (kind 2, layouts with q_per_kv > 1) kernel.
+ * Needs a GPU (FDC_HIP_ERROR otherwise). */
 fdc_status fdc_suggest_workers(int kind, int32_t* n_workers);
 
 /* seq_len: host int32 [batch], 0 <= seq_len[b] <= max_seq. */

@@ -20,7 +20,7 @@ FDC_BF16, FDC_F32 = 0, 1
 FDC_FOLD, FDC_APPLY = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "fdc_last_error", "fdc_layout_create", "fdc_layout_tables", "fdc_layout_destroy",
+    "fdc_last_error", "fdc_layout_create", "fdc_layout_create_gqa", "fdc_layout_tables", "fdc_layout_destroy",
     "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_prefill",
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
@@ -66,6 +66,7 @@ def lib() -> C.CDLL:
         l.fdc_last_error.argtypes = [C.c_char_p, C.c_size_t]
         l.fdc_last_error.restype = None
         l.fdc_layout_create.argtypes = [C.c_int] * 4 + [i32p, i32p, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
+        l.fdc_layout_create_gqa.argtypes = [C.c_int] * 5 + [i32p, i32p, C.c_int, C.c_int, C.c_int, C.POINTER(vp)]
         l.fdc_layout_tables.argtypes = [vp, i64p, i64p, i32p, i32p, i64p, i64p]
         l.fdc_layout_destroy.argtypes = [vp]
         l.fdc_layout_destroy.restype = None
@@ -129,15 +130,20 @@ def _stream(stream) -> Optional[int]:
 
 
 class Layout:
-    """Owns an fdc_layout*. rk, rv: int [L, H]."""
+    """Owns an fdc_layout*. rk, rv: int [L, H] (H = key/value heads); q_per_kv query heads share one."""
 
-    def __init__(self, n_layers, n_heads, d_model, d_head, rk, rv, max_batch, max_seq, dtype):
+    def __init__(self, n_layers, n_heads, d_model, d_head, rk, rv, max_batch, max_seq, dtype, q_per_kv=1):
         rk, rv = _i32(rk).reshape(-1), _i32(rv).reshape(-1)
         if rk.size != n_layers * n_heads or rv.size != n_layers * n_heads:
             raise ValueError("rk/rv must have n_layers * n_heads entries")
         self.handle = C.c_void_p()
-        _check(lib().fdc_layout_create(n_layers, n_heads, d_model, d_head, _p32(rk), _p32(rv), max_batch, max_seq,
-                                       dtype, C.byref(self.handle)))
+        if q_per_kv == 1:
+            _check(lib().fdc_layout_create(n_layers, n_heads, d_model, d_head, _p32(rk), _p32(rv), max_batch,
+                                           max_seq, dtype, C.byref(self.handle)))
+        else:
+            _check(lib().fdc_layout_create_gqa(n_layers, n_heads, q_per_kv, d_model, d_head, _p32(rk), _p32(rv),
+                                               max_batch, max_seq, dtype, C.byref(self.handle)))
+        self.q_per_kv = q_per_kv
         self.n_layers, self.n_heads, self.d_model, self.d_head = n_layers, n_heads, d_model, d_head
         self.max_batch, self.max_seq, self.dtype = max_batch, max_seq, dtype
         self.rk = rk.reshape(n_layers, n_heads).copy()
@@ -198,7 +204,7 @@ class Plan:
         if t.kind == 0:
             out["unit_item_ptr"] = arr(t.unit_item_ptr, U + 1, np.int32)
         else:
-            out["br"] = arr(t.br, self.layout.n_heads, np.int32)
+            out["br"] = arr(t.br, self.layout.n_heads * self.layout.q_per_kv, np.int32)
         return out
 
     def workspace_bytes(self) -> int:

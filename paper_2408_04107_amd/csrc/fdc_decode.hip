@@ -382,6 +382,11 @@ fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
     FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<uint16_t>,
                                                                kWavesPerBlock * 64, 0));
     *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
+  } else if (kind == 2) {
+    int waves = 0;
+    fdc_status st = decode_gqa_workers_per_cu(&waves);
+    if (st != FDC_OK) return st;
+    *n_workers = prop.multiProcessorCount * waves;
   } else if (kind == 1) {
     int nb = 0;
     fdc_status st = prefill_blocks_per_cu(&nb);
@@ -428,9 +433,16 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   const float scale_log2 = scale * kLog2e;
   hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
+  if (plan->G > 1 && lay->dtype != FDC_BF16)
+    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 layout");
   if (!plan->item_b.empty()) {
     if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
-    if (lay->dtype == FDC_BF16)
+    if (plan->G > 1) {
+      fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat),
+                                        static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
+                                        scale, static_cast<float*>(o_lat), partials, W, st);
+      if (gs != FDC_OK) return gs;
+    } else if (lay->dtype == FDC_BF16)
       hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
                          static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
@@ -443,10 +455,10 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   }
   // wide workgroups only when some unit has many tiles (long contexts)
   if (plan->max_items_per_unit > 64)
-    hipLaunchKernelGGL(decode_merge_kernel<32>, dim3(plan->n_units), dim3(1024), 0, st, units, partials,
+    hipLaunchKernelGGL(decode_merge_kernel<32>, dim3(plan->n_merge_units), dim3(1024), 0, st, units, partials,
                        static_cast<float*>(o_lat));
   else
-    hipLaunchKernelGGL(decode_merge_kernel<4>, dim3(plan->n_units), dim3(128), 0, st, units, partials,
+    hipLaunchKernelGGL(decode_merge_kernel<4>, dim3(plan->n_merge_units), dim3(128), 0, st, units, partials,
                        static_cast<float*>(o_lat));
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;

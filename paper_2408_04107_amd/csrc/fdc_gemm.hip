@@ -27,6 +27,7 @@ struct GemmArgs {
   int nt;    // column tiles of the large kernel (of the widest group)
   int mode;
   int H, d_head, max_seq;
+  int G;     // query heads per key/value head: grouped products run over the H * G query heads
   int RK, RV;
   const int32_t* tok_batch;
   const int32_t* tok_pos;
@@ -46,16 +47,18 @@ struct Group {
 
 __device__ __forceinline__ Group group_of(const GemmArgs& g, int z) {
   Group r{0, 0, 0, g.N};
-  if (g.mode == kAbsorbQuery) {  // A = q[:, z, :], B = Bk rows of head z, C = q_lat columns of head z
+  // z is a QUERY head; it uses the factors of key/value head h = z / G and is the j-th of its group
+  const int h = z / g.G, j = z % g.G;
+  if (g.mode == kAbsorbQuery) {  // A = q[:, z, :], B = Bk rows of head h, C = q_lat columns of query head z
+    r.N = g.koff_r[h + 1] - g.koff_r[h];
     r.a_off = (int64_t)z * g.d_head;
-    r.b_off = (int64_t)g.koff_r[z] * g.d_head;
-    r.c_off = g.koff_r[z];
-    r.N = g.koff_r[z + 1] - g.koff_r[z];
-  } else if (g.mode == kFold) {  // A = Wo_t[:, z*d_h ..], B = Bv rows of head z, C = Mt columns of head z
+    r.b_off = (int64_t)g.koff_r[h] * g.d_head;
+    r.c_off = g.G * g.koff_r[h] + j * r.N;
+  } else if (g.mode == kFold) {  // A = Wo_t[:, z*d_h ..], B = Bv rows of head h, C = Mt columns of query head z
+    r.N = g.voff_r[h + 1] - g.voff_r[h];
     r.a_off = (int64_t)z * g.d_head;
-    r.b_off = (int64_t)g.voff_r[z] * g.d_head;
-    r.c_off = g.voff_r[z];
-    r.N = g.voff_r[z + 1] - g.voff_r[z];
+    r.b_off = (int64_t)g.voff_r[h] * g.d_head;
+    r.c_off = g.G * g.voff_r[h] + j * r.N;
   }
   return r;
 }
@@ -705,11 +708,14 @@ template <typename TC, bool KEYS>
 __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_a[kRopeRows * kRopeLdsRow];
   __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRopeLdsRow];
-  const int h = blockIdx.y, t0 = blockIdx.x * kRopeRows;
+  // blockIdx.y is the head of the input rows: a key/value head for keys, a query head for queries
+  // (which then uses the rotation of key/value head hx / G and its own columns of q_lat)
+  const int hx = blockIdx.y, t0 = blockIdx.x * kRopeRows;
+  const int h = KEYS ? hx : hx / g.G, jq = KEYS ? 0 : hx % g.G;
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
   const int r = g.koff_r[h + 1] - g.koff_r[h];
-  const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)h * g.d_head;  // row stride lda = H * d_head
+  const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)hx * g.d_head;  // row stride lda = heads * d_head
   const uint16_t* Rt = static_cast<const uint16_t*>(g.B) + (int64_t)g.koff_r[h] * g.d_head;
   const int half = g.d_head / 2;
   // stage A with RoPE: 64 rows x 16 chunks of 8 elements
@@ -760,7 +766,7 @@ __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
                             (int64_t)g.tok_pos[t] * r + n;
         static_cast<uint16_t*>(g.C)[dst] = f32_to_bf16(acc[e]);
       } else {
-        store_out(static_cast<TC*>(g.C) + (int64_t)t * g.RK + g.koff_r[h] + n, acc[e]);
+        store_out(static_cast<TC*>(g.C) + (int64_t)t * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n, acc[e]);
       }
     }
   }
@@ -769,6 +775,7 @@ __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
 static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
   const int H = lay->H;
   a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq;
+  a.G = lay->G;
   a.RK = lay->RK(layer), a.RV = lay->RV(layer);
   std::copy_n(&lay->koff_r[(size_t)layer * (H + 1)], H + 1, a.koff_r);
   std::copy_n(&lay->voff_r[(size_t)layer * (H + 1)], H + 1, a.voff_r);
@@ -858,12 +865,12 @@ fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int
   GemmArgs a{};
   fill_tables(a, lay, layer);
   a.A = q, a.B = Bk, a.C = q_lat;
-  a.lda = (int64_t)lay->H * lay->d_head, a.ldb = lay->d_head, a.ldc = a.RK;
+  a.lda = (int64_t)lay->H * lay->G * lay->d_head, a.ldb = lay->d_head, a.ldc = (int64_t)lay->G * a.RK;
   a.M = T, a.N = 0, a.K = lay->d_head;
   a.mode = kAbsorbQuery;
   int n_max = 0;
   for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rk[(size_t)layer * lay->H + h]);
-  return launch(lay, a, lay->H, n_max, false, q_lat_dtype == FDC_F32, static_cast<hipStream_t>(stream));
+  return launch(lay, a, lay->H * lay->G, n_max, false, q_lat_dtype == FDC_F32, static_cast<hipStream_t>(stream));
 }
 
 fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const void* Bv, const void* Wo_t, void* Mt,
@@ -879,12 +886,12 @@ fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const v
     if (!Bv || !Wo_t) FDC_FAIL(FDC_INVALID_ARG, "fdc_absorb_output(FOLD): NULL argument");
     if (!aligned16(Bv) || !aligned16(Wo_t)) FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_absorb_output(FOLD): alignment");
     a.A = Wo_t, a.B = Bv, a.C = Mt;
-    a.lda = (int64_t)lay->H * lay->d_head, a.ldb = lay->d_head, a.ldc = a.RV;
+    a.lda = (int64_t)lay->H * lay->G * lay->d_head, a.ldb = lay->d_head, a.ldc = (int64_t)lay->G * a.RV;
     a.M = lay->d_model, a.N = 0, a.K = lay->d_head;
     a.mode = kFold;
     int n_max = 0;
     for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rv[(size_t)layer * lay->H + h]);
-    return launch(lay, a, lay->H, n_max, false, lay->dtype == FDC_F32, st);
+    return launch(lay, a, lay->H * lay->G, n_max, false, lay->dtype == FDC_F32, st);
   }
   if (mode == FDC_APPLY) {
     if (T == 0) return FDC_OK;
@@ -895,8 +902,8 @@ fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const v
     if (lay->dtype == FDC_F32 && (o_lat_dtype != FDC_F32 || y_dtype != FDC_F32))
       FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_absorb_output(APPLY): an fp32 layout takes and writes fp32");
     a.A = o_lat, a.B = Mt, a.C = y;
-    a.lda = a.RV, a.ldb = a.RV, a.ldc = lay->d_model;
-    a.M = T, a.N = lay->d_model, a.K = a.RV;
+    a.lda = (int64_t)lay->G * a.RV, a.ldb = (int64_t)lay->G * a.RV, a.ldc = lay->d_model;
+    a.M = T, a.N = lay->d_model, a.K = lay->G * a.RV;
     a.mode = kPlain;
     return launch(lay, a, 1, a.N, o_lat_dtype == FDC_F32, y_dtype == FDC_F32, st);
   }
@@ -915,7 +922,7 @@ static fdc_status rope_common(const char* fn, const fdc_layout* lay, int layer, 
     FDC_FAIL(FDC_BAD_ALIGNMENT, "%s: pointers must be 16-byte aligned", fn);
   fill_tables(*a, lay, layer);
   a->A = x, a->B = R_t, a->C = out;
-  a->lda = (int64_t)lay->H * lay->d_head;
+  a->lda = (int64_t)lay->H * lay->d_head;   // key rows; the query entry point widens it to the query heads
   a->M = T, a->K = lay->d_head;
   a->tok_pos = tok_pos, a->rope_cos = cos_t, a->rope_sin = sin_t, a->n_pos = n_pos;
   return FDC_OK;
@@ -929,7 +936,8 @@ fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q
   fdc_status s = rope_common("fdc_rope_absorb_query", lay, layer, q, T, tok_pos, cos_t, sin_t, n_pos, R_t, q_lat, &a);
   if (s != FDC_OK) return s;
   if (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_rope_absorb_query: q_lat_dtype");
-  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H);
+  a.lda = (int64_t)lay->H * lay->G * lay->d_head;
+  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H * lay->G);
   if (q_lat_dtype == FDC_F32)
     hipLaunchKernelGGL((rope_compress_kernel<float, false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
   else

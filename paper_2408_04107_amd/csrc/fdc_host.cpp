@@ -110,6 +110,19 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
   return FDC_OK;
 }
 
+fdc_status fdc_layout_create_gqa(int n_layers, int n_kv_heads, int q_per_kv, int d_model, int d_head, const int32_t* rk,
+                                 const int32_t* rv, int max_batch, int max_seq, fdc_dtype dtype, fdc_layout** out) {
+  if (!out) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create_gqa: out is NULL");
+  *out = nullptr;
+  if (q_per_kv < 1 || q_per_kv > 16)
+    FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create_gqa: q_per_kv %d outside [1, 16]", q_per_kv);
+  if (n_kv_heads > 0 && (int64_t)n_kv_heads * q_per_kv > 128)
+    FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create_gqa: more than 128 query heads");
+  fdc_status st = fdc_layout_create(n_layers, n_kv_heads, d_model, d_head, rk, rv, max_batch, max_seq, dtype, out);
+  if (st == FDC_OK) (*out)->G = q_per_kv;
+  return st;
+}
+
 fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff, int32_t* koff_r,
                              int32_t* voff_r, int64_t* k_bytes, int64_t* v_bytes) {
   if (!lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_tables: layout is NULL");
@@ -253,6 +266,7 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
   fdc_plan* p = new (std::nothrow) fdc_plan();
   if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: out of host memory");
   p->kind = 0, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
+  p->G = lay->G;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer), p->total_q_rows = batch;
   p->item_b.resize(n), p->item_h.resize(n), p->item_lo.resize(n), p->item_hi.resize(n), p->item_cost.resize(n);
   p->unit_item_ptr.assign((size_t)p->n_units + 1, 0);
@@ -288,15 +302,25 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     t.k_elem = (int64_t)b * lay->max_seq * p->RK + koff[h] + (int64_t)p->item_lo[tid] * rk[h];
     t.v_elem = (int64_t)b * lay->max_seq * p->RV + voff[h] + (int64_t)p->item_lo[tid] * rv[h];
     t.len = p->item_hi[tid] - p->item_lo[tid];
-    t.q_elem = b * p->RK + koff_r[h];
-    t.o_elem = b * p->RV + voff_r[h];
+    // with g query heads per unit the query-side tensors are g times as wide and the partial
+    // slots of a unit hold its tiles once per query head: slot = g * first + j * n_u + i
+    const int g = p->G, n_u = p->unit_item_ptr[u + 1] - p->unit_item_ptr[u];
+    t.q_elem = g * (b * p->RK + koff_r[h]);
+    t.o_elem = g * (b * p->RV + voff_r[h]);
     t.rk_rv = rk[h] | (rv[h] << 16);
-    t.slot = (p->unit_item_ptr[u + 1] - p->unit_item_ptr[u] == 1) ? -1 : (int32_t)tid;
+    t.g = g;
+    t.slot_stride = n_u;
+    t.slot = n_u == 1 ? -1 : g * p->unit_item_ptr[u] + ((int32_t)tid - p->unit_item_ptr[u]);
   }
-  std::vector<DecUnit> units(p->n_units);
+  p->n_merge_units = p->n_units * p->G;
+  std::vector<DecUnit> units(p->n_merge_units);
   for (int u = 0; u < p->n_units; ++u) {
-    const int b = u / H, h = u % H;
-    units[u] = {p->unit_item_ptr[u], p->unit_item_ptr[u + 1], b * p->RV + voff_r[h], rv[h]};
+    const int b = u / H, h = u % H, g = p->G;
+    const int n_u = p->unit_item_ptr[u + 1] - p->unit_item_ptr[u];
+    for (int j = 0; j < g; ++j) {
+      const int first = g * p->unit_item_ptr[u] + j * n_u;
+      units[(size_t)u * g + j] = {first, first + n_u, g * (b * p->RV + voff_r[h]) + j * rv[h], rv[h]};
+    }
   }
   // tiles in worker (hand-out) order plus one header per worker
   std::vector<DecTile> wtiles(n);
@@ -313,7 +337,7 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
   p->off_worker_ptr = append_aligned(p->image, heads.data(), heads.size());
   p->off_worker_items = p->off_worker_ptr;
   p->off_partials = (p->image.size() + 255) / 256 * 256;
-  p->partial_bytes = std::max<size_t>(n, 1) * kPartialStride * sizeof(float);
+  p->partial_bytes = std::max<size_t>(n * p->G, 1) * kPartialStride * sizeof(float);
   p->workspace_bytes = p->off_partials + p->partial_bytes;
   *out = p;
   return FDC_OK;
@@ -332,9 +356,11 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
       FDC_FAIL(FDC_BAD_SHAPE, "fdc_plan_prefill: need 0 <= q_len[%d]=%d <= kv_len=%d <= %d", b, q_len[b], kv_len[b],
                lay->max_seq);
 
-  const int H = lay->H, W = pr->n_workers;
-  const int32_t* rk = &lay->rk[(size_t)layer * H];
-  const int32_t* rv = &lay->rv[(size_t)layer * H];
+  // With grouped queries the planner's heads are the QUERY heads: query head hq has the ranks and
+  // the cache blocks of key/value head hq / g and its own columns in q_lat and o_lat.
+  const int g = lay->G, Hkv = lay->H, H = Hkv * g, W = pr->n_workers;
+  std::vector<int32_t> rk(H), rv(H);
+  for (int h = 0; h < H; ++h) rk[h] = lay->rk[(size_t)layer * Hkv + h / g], rv[h] = lay->rv[(size_t)layer * Hkv + h / g];
   std::vector<int64_t> d_sum(H);
   int64_t d_max = 0;
   for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost, d_max = std::max(d_max, d_sum[h]);
@@ -342,6 +368,7 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
   fdc_plan* p = new (std::nothrow) fdc_plan();
   if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: out of host memory");
   p->kind = 1, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
+  p->G = g;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
   p->br.resize(H);
   for (int h = 0; h < H; ++h)
@@ -418,10 +445,10 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
   worker_csr(lists, p);
 
   // device image
-  const int64_t* koff = &lay->koff[(size_t)layer * H];
-  const int64_t* voff = &lay->voff[(size_t)layer * H];
-  const int32_t* koff_r = &lay->koff_r[(size_t)layer * (H + 1)];
-  const int32_t* voff_r = &lay->voff_r[(size_t)layer * (H + 1)];
+  const int64_t* koff = &lay->koff[(size_t)layer * Hkv];
+  const int64_t* voff = &lay->voff[(size_t)layer * Hkv];
+  const int32_t* koff_r = &lay->koff_r[(size_t)layer * (Hkv + 1)];
+  const int32_t* voff_r = &lay->voff_r[(size_t)layer * (Hkv + 1)];
   std::vector<int64_t> row0(batch + 1, 0);
   for (int b = 0; b < batch; ++b) row0[b + 1] = row0[b] + q_len[b];
   p->total_q_rows = row0[batch];
@@ -430,15 +457,16 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
     const Task& t = tasks[i];
     PreTask& d = pt[i];
     std::memset(&d, 0, sizeof(d));
-    d.k_elem = (int64_t)t.b * lay->max_seq * p->RK + koff[t.h];
-    d.v_elem = (int64_t)t.b * lay->max_seq * p->RV + voff[t.h];
-    d.q_elem = (row0[t.b] + t.q0) * p->RK + koff_r[t.h];
-    d.o_elem = (row0[t.b] + t.q0) * p->RV + voff_r[t.h];
+    const int hk = t.h / g, j = t.h % g;
+    d.k_elem = (int64_t)t.b * lay->max_seq * p->RK + koff[hk];
+    d.v_elem = (int64_t)t.b * lay->max_seq * p->RV + voff[hk];
+    d.q_elem = (row0[t.b] + t.q0) * g * p->RK + g * koff_r[hk] + j * rk[t.h];
+    d.o_elem = (row0[t.b] + t.q0) * g * p->RV + g * voff_r[hk] + j * rv[t.h];
     d.rows = t.q1 - t.q0;
     d.pos0 = kv_len[t.b] - q_len[t.b] + t.q0;
     d.kv_len = kv_len[t.b];
     d.rk_rv = rk[t.h] | (rv[t.h] << 16);
-    d.ldq = p->RK, d.ldo = p->RV;
+    d.ldq = g * p->RK, d.ldo = g * p->RV;
   }
   p->off_items = append_aligned(p->image, pt.data(), pt.size());
   p->off_units = p->off_items;

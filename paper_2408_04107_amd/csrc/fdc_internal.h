@@ -40,7 +40,11 @@ struct DecTile {
   int32_t o_elem;   // element offset of o'_h in o_lat  (b * RV + voff_r[h])
   int32_t rk_rv;    // rk | rv << 16
   int32_t slot;     // partial-state slot, or -1: the unit has one tile, write the normalised output
-  int32_t pad[3];
+  int32_t g;        // query heads that share the unit's K'/V' (1 = multi-head); query j of the group
+                    // reads q' at q_elem + j * rk, writes o' at o_elem + j * rv and uses partial slot
+                    // slot + j * slot_stride
+  int32_t slot_stride;  // tiles of the unit
+  int32_t pad[1];
 };
 static_assert(sizeof(DecTile) == 48, "DecTile layout");
 
@@ -84,11 +88,26 @@ static_assert(sizeof(PreTask) == 64, "PreTask layout");
 // Resident workgroups per compute unit of the prefill kernel (occupancy query).
 fdc_status prefill_blocks_per_cu(int* nb);
 
+// Grouped-query decode tile kernel (fdc_decode_gqa.hip): resident workers per compute unit, and the
+// launch. Same tables, partial slots and outputs as the multi-head tile kernel.
+struct DecWorker;
+fdc_status decode_gqa_workers_per_cu(int* waves);
+
 }  // namespace fdc
+
+#ifdef __HIPCC__
+#include <hip/hip_runtime.h>
+namespace fdc {
+fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const uint16_t* kc,
+                             const uint16_t* vc, float scale, float* o_lat, float* partials, int n_workers,
+                             hipStream_t st);
+}
+#endif
 
 // ---- host objects ---------------------------------------------------------------------------
 struct fdc_layout {
   int L, H, d_model, d_head, max_batch, max_seq;
+  int G = 1;  // query heads per key/value head
   fdc_dtype dtype;
   int elem_size;
   std::vector<int32_t> rk, rv;          // [L*H]
@@ -102,6 +121,8 @@ struct fdc_layout {
 struct fdc_plan {
   int kind;  // 0 decode, 1 prefill
   int layer, batch, H, n_workers, n_units;
+  int G = 1;            // query heads per key/value head of the layout the plan was made for
+  int n_merge_units = 0;  // decode: records of the split-K merge (units x query heads of a group)
   const fdc_layout* lay;  // identity check only (the plan copies what it needs)
   int RK, RV;
   int64_t total_q_rows;   // prefill: T

@@ -123,6 +123,35 @@ def test_prefill_plan_bit_exact(mode):
         _prefill_case(rk, rv, q, kv, int(g.integers(1, 70)), mode, sc=int(g.choice([1, 3, 400])))
 
 
+def test_grouped_query_plans_bit_exact():
+    """Grouped queries: the decode plan is the plan of the key/value heads (the group rides along
+    in every tile); the prefill plan is the oracle's plan over the QUERY heads, each with the ranks
+    of its key/value head."""
+    rk, rv = [16, 64, 32], [32, 64, 16]
+    for g in (2, 4, 8):
+        lay = fdc.Layout(1, len(rk), 256, 128, [rk], [rv], 4, 4000, fdc.FDC_BF16, q_per_kv=g)
+        pp = fdc.fdc_plan_params_default()
+        pp.n_workers, pp.granule, pp.min_split = 37, 64, 2
+        seq = [0, 5, 1300, 4000]
+        got = fdc.fdc_plan_decode(lay, 0, seq, pp).export()
+        ref = op.plan_decode(seq, rk, rv, 37, granule=64, min_split=2, split=True)
+        for a, b in DEC_PAIRS:
+            assert np.array_equal(got[a], ref[b]), (a, g)
+        for mode in ("paper", "causal"):
+            pp = fdc.fdc_plan_params_default()
+            pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = 11, {"paper": 0, "causal": 1}[mode], 64, 256
+            q, kv = [0, 5, 130, 700], [0, 9, 130, 4000]
+            got = fdc.fdc_plan_prefill(lay, 0, q, kv, pp).export()
+            rkq, rvq = [rk[h // g] for h in range(len(rk) * g)], [rv[h // g] for h in range(len(rk) * g)]
+            ref = op.plan_prefill(q, kv, rkq, rvq, 11, br_base=64, br_cap=256, cost_mode=mode)
+            for a, b in PRE_PAIRS:
+                assert got[a].dtype == ref[b].dtype and np.array_equal(got[a], ref[b]), (a, g, mode)
+    with pytest.raises(fdc.FdcError):
+        fdc.Layout(1, 3, 256, 128, [rk], [rv], 1, 16, fdc.FDC_BF16, q_per_kv=17)
+    with pytest.raises(fdc.FdcError):
+        fdc.Layout(1, 3, 256, 128, [rk], [rv], 1, 16, fdc.FDC_BF16, q_per_kv=0)
+
+
 def test_select_ranks_bit_exact_with_oracle():
     """Eq. (1): the library's rank choice equals the oracle's on planted, random and tie-prone spectra."""
     from oracle import rank_select as ors
