@@ -326,6 +326,57 @@ def run_prefill_workload(fdc, gen, iters=3):
     return out
 
 
+def run_gqa_decode_workload(fdc, gen, iters=20):
+    """Grouped-query decode attention (Section 5.1, GQA paragraph): 8 key/value heads shared by 4 query
+    heads each (32 query heads), adaptive ranks, batch 64, context 8192, one layer."""
+    import torch
+    dev = "cuda:0"
+    H, g, B, S, dh = 8, 4, 64, 8192, 128
+    r = [int(x) for x in gen.adaptive_ranks(1, H, 11)[0]]
+    lay = fdc.Layout(1, H, 4096, dh, [r], [r], B, S, fdc.FDC_BF16, q_per_kv=g)
+    t = lay.tables()
+    RK = int(t["koff_r"][0, -1])
+    bf = torch.bfloat16
+    gt = torch.Generator(device=dev).manual_seed(5)
+    n = int(t["k_bytes"][0]) // 2
+    kc = torch.randn(n, generator=gt, device=dev).to(bf)
+    vc = torch.randn(n, generator=gt, device=dev).to(bf)
+    q_lat = torch.randn(B, g * RK, generator=gt, device=dev)
+    o_lat = torch.empty(B, g * RK, device=dev)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = fdc.fdc_suggest_workers(2)
+    plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
+    ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan.workspace_bytes()]
+    fdc.fdc_plan_upload(plan, ws)
+    fn = lambda: fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, 1.0 / math.sqrt(dh), o_lat, ws)
+    fn()
+    torch.cuda.synchronize()
+    ev = HipEvents(2)
+    tile_us = []
+    for _ in range(iters):
+        fdc.fdc_profile_decode_events(ev.ev[0], ev.ev[1])
+        fn()
+        torch.cuda.synchronize()
+        tile_us.append(ev.ms(0, 1) * 1e3)
+    ev.destroy()
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    torch.cuda.synchronize()
+    call_us = s.elapsed_time(e) / iters * 1e3
+    cache_bytes = float(B * S * 2 * sum(r) * 2)    # every cached element once, whatever the group size
+    tile = sum(tile_us) / len(tile_us)
+    return {"workload": "8 kv heads x 4 query heads, adaptive ranks %s, batch 64, context 8192" % r,
+            "n_workers": pp.n_workers, "tiles": int(plan.export()["n_items"]),
+            "tile_kernel_us": tile, "tile_kernel_GBps": cache_bytes / tile / 1e3,
+            "frac_of_hbm_peak": cache_bytes / tile / 1e3 / HBM_PEAK_GBPS,
+            "call_us": call_us, "call_GBps": cache_bytes / call_us / 1e3}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -340,6 +391,7 @@ def main():
                     help="also run one plain 1 GiB device copy (known HBM traffic) for scaling rocprofv3 counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
+    ap.add_argument("--no-gqa", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
@@ -384,6 +436,8 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_prefill:
         line["prefill"] = run_prefill_workload(fdc, gen)
+    if not args.no_gqa:
+        line["gqa_decode"] = run_gqa_decode_workload(fdc, gen)
     print(json.dumps(line))
 
 
