@@ -32,10 +32,16 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPreThreads = 256;
+#ifndef FDC_PREFILL_QT
+#define FDC_PREFILL_QT 1
+#endif
+constexpr int QT = FDC_PREFILL_QT;       // 16-row MFMA tiles of queries per wave
 constexpr int BC = 64;                   // tokens per K'/V' block
-constexpr int kRowsPerWave = 32;         // two MFMA row tiles
-constexpr int kRowsPerPass = 128;        // four waves
+constexpr int kRowsPerWave = 16 * QT;
+constexpr int kRowsPerPass = 128;
+constexpr int kPreThreads = 64 * (kRowsPerPass / kRowsPerWave);
+constexpr int kStageRows = kPreThreads / 16;  // token rows one staging sweep covers
+constexpr int kPreWavesPerSimd = QT == 1 ? 4 : 2;  // two workgroups per compute unit either way
 constexpr int KROW = 128 + 8;            // LDS row length of the K' tile in elements (272 bytes)
 constexpr int VROW = 128 + 16;           // LDS row length of the V' tile in elements (288 bytes)
 constexpr int kStageElems = BC * KROW + BC * VROW;  // one buffer: K' tile then V' tile
@@ -96,7 +102,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
 
   // staging map: 16 lanes per token row (a row has at most 16 chunks of 16 bytes), 16 rows per
   // sweep, 4 sweeps per block; narrow heads leave the upper lanes of a row idle. No divisions.
-  constexpr int kSweeps = BC / 16;
+  constexpr int kSweeps = BC / kStageRows;
   const int s_row = tid / 16, s_cc = tid % 16;
   const bool k_lane = s_cc * 8 < rk, v_lane = s_cc * 8 < rv;
   // the unit's K' and V' rows [0, kv_len) as raw buffers (at most 131072 * 256 bytes each)
@@ -111,9 +117,9 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     const int pass_rows = min(kRowsPerPass, t.rows - r0);
     const int wrow0 = r0 + wave * kRowsPerWave;  // first row of this wave inside the task
     // Q' fragments (B operand): lane (ln, lg) holds 8 consecutive k of query row 16 i + ln
-    Frag qf[2][RK32];
+    Frag qf[QT][RK32];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < QT; ++i) {
       const int row = wrow0 + 16 * i + ln;
 #pragma unroll
       for (int ks = 0; ks < RK32; ++ks) {
@@ -123,13 +129,15 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
                           : u32x4{0, 0, 0, 0};
       }
     }
-    f32x4 oacc[2][RV16];
+    f32x4 oacc[QT][RV16];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < QT; ++i)
 #pragma unroll
       for (int c = 0; c < RV16; ++c) oacc[i][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     // running maximum of the raw (unscaled) scores and running sum, per query row
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int i = 0; i < QT; ++i) m_run[i] = -INFINITY, l_run[i] = 0.f;
     const int pos_base = t.pos0 + wrow0 + ln;  // absolute position of this lane's row in tile 0 (+16 for tile 1)
 
     const int last_pos = t.pos0 + r0 + pass_rows - 1;
@@ -142,7 +150,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     auto fetch = [&](int c0) {  // rows past kv_len and idle lanes read zeros through the range check
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        const uint32_t tok = (uint32_t)(c0 + s_row + 16 * i);
+        const uint32_t tok = (uint32_t)(c0 + s_row + kStageRows * i);
         kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(k_lane_off + tok * (uint32_t)(rk * 2)), 0, 0);
         vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(v_lane_off + tok * (uint32_t)(rv * 2)), 0, 0);
       }
@@ -152,7 +160,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
       uint16_t* lv = lk + BC * KROW;
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        const int r = s_row + 16 * i;
+        const int r = s_row + kStageRows * i;
         if (k_lane) *reinterpret_cast<u32x4*>(&lk[r * KROW + s_cc * 8]) = kst[i];
         if (v_lane) *reinterpret_cast<u32x4*>(&lv[r * VROW + s_cc * 8]) = vst[i];
       }
@@ -172,31 +180,31 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         const uint16_t* lk = lds + buf * kStageElems;
         const uint16_t* lv = lk + BC * KROW;
         // S^T tiles: st[j][i] = tokens 16 j .. of the block x query rows of tile i
-        f32x4 st[4][2];
+        f32x4 st[4][QT];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           {  // first k-step starts from a constant zero accumulator (no register clearing)
             Frag kf;
             kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 8 * lg]);
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][0].v, zero, 0, 0, 0);
-            st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][0].v, zero, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < QT; ++i) st[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[i][0].v, zero, 0, 0, 0);
           }
 #pragma unroll
           for (int ks = 1; ks < RK32; ++ks) {
             if (ks >= rk32) break;
             Frag kf;
             kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
-            st[j][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0][ks].v, st[j][0], 0, 0, 0);
-            st[j][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[1][ks].v, st[j][1], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < QT; ++i) st[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[i][ks].v, st[j][i], 0, 0, 0);
           }
         }
         // mask, online softmax. Lane (ln, lg) holds tokens c0 + 16 j + 4 lg + e of row ln.
         // p = 2^((s - m) * scale * log2 e) as one fma per score.
         const bool need_mask = (causal && c0 + BC - 1 > t.pos0 + wrow0) || c0 + BC > t.kv_len;
-        Frag pf[2][2];
+        Frag pf[QT][2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < QT; ++i) {
           const int pos = pos_base + 16 * i;
           if (need_mask) {
 #pragma unroll
@@ -262,8 +270,8 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
             hi.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 16 * VROW));
             Frag vf;
             vf.u = u32x4{lo.u[0], lo.u[1], hi.u[0], hi.u[1]};
-            oacc[0][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[0][jp].v, oacc[0][c], 0, 0, 0);
-            oacc[1][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[1][jp].v, oacc[1][c], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < QT; ++i) oacc[i][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[i][jp].v, oacc[i][c], 0, 0, 0);
           }
         }
       }
@@ -273,7 +281,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
 
     // finish: l over the four lanes of a row, normalise, store. Lane (ln, lg) holds O[row ln][16 c + 4 lg + e].
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < QT; ++i) {
       const float l = row_sum(l_run[i]);
       const float inv = l > 0.f ? 1.f / l : 0.f;
       const int row = wrow0 + 16 * i + ln;
@@ -292,7 +300,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   }
 }
 
-__global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void prefill_kernel(
+__global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(kPreWavesPerSimd, kPreWavesPerSimd))) void prefill_kernel(
     const PreTask* __restrict__ tasks, const int32_t* __restrict__ worker_ptr,
     const int32_t* __restrict__ worker_items, const uint16_t* __restrict__ q_lat,
     const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, int causal,
