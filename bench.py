@@ -252,7 +252,7 @@ def cpu_baseline(state, budget_s=12.0):
             "us_per_unit": dt * 1e6 / n_units}
 
 
-def run_prefill_workload(fdc, gen, iters=3):
+def run_prefill_workload(fdc, gen, iters=10):
     """Config 5: projection of 16384 tokens, causal latent attention, output absorption (bf16 MFMA)."""
     import torch
     dev = "cuda:0"
