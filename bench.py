@@ -182,6 +182,26 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     torch.cuda.synchronize()
     attn_us_per_layer = (time.perf_counter() - t0) * 1e6 / (reps * L)
 
+    # the other calls of a step on layer 0, each alone (weight streams at decode batch: HBM-bound)
+    def timed_us(fn, n=30):
+        fn()
+        torch.cuda.synchronize()
+        s_, e_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s_.record()
+        for _ in range(n):
+            fn()
+        e_.record()
+        torch.cuda.synchronize()
+        return s_.elapsed_time(e_) * 1e3 / n
+    RK0, RV0 = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    small = {}
+    us = timed_us(lambda: fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A_cat_t[0], kc[0], vc[0]))
+    small["project_latent_kv"] = {"us": us, "weight_GBps": (RK0 + RV0) * d * 2 / us / 1e3}
+    us = timed_us(lambda: fdc.fdc_absorb_query(lay, 0, q, Bk[0], q_lat, fdc.FDC_F32))
+    small["absorb_query"] = {"us": us, "weight_GBps": RK0 * dh * 2 / us / 1e3}
+    us = timed_us(lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt[0], o_lat, fdc.FDC_F32, B, y, fdc.FDC_BF16))
+    small["absorb_output_apply"] = {"us": us, "weight_GBps": d * RV0 * 2 / us / 1e3}
+
     # HBM bytes per launch of the tile kernel from the committed rocprofv3 counter summary (FETCH_SIZE and
     # WRITE_SIZE, each scaled by a plain copy of known size); null when that summary is for another workload
     traffic = None
@@ -209,6 +229,7 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
                         "planner_imbalance_max_over_mean": {"mean": float(np.mean(imb)), "max": float(np.max(imb))},
                         "plan_host_ms_per_layer": t_plan * 1e3 / L, "n_workers": W,
                         "tiles_per_layer": float(np.mean([tb_["n_items"] for tb_ in tabs]))},
+        "decode_other_calls_layer0": small,
         "step_algorithmic_bytes": step_bytes,
     }
     state = dict(lay=lay, tables=t, kc=kc, vc=vc, ranks=ranks, q_lat=q_lat, scale=scale, B=B, S=S, H=H)
@@ -323,6 +344,35 @@ def run_prefill_workload(fdc, gen, iters=10):
             total_ms += ms          # the five calls of the RoPE-free chain; the post-RoPE calls are alternatives
         out[name] = {"ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
     out["total_ms"] = total_ms
+    # attention alone by rank bucket: every head at the same rank (MFMA-bound when wide, exp-bound when narrow)
+    buckets = {}
+    del x, y, q, k_pre
+    for rr in (16, 64, 128):
+        ru = [rr] * H
+        lay_u = fdc.Layout(1, H, d, dh, [ru], [ru], B, S, fdc.FDC_BF16)
+        tu = lay_u.tables()
+        kcu = torch.randn(int(tu["k_bytes"][0]) // 2, generator=gt, device=dev).to(bf)
+        vcu = torch.randn(int(tu["v_bytes"][0]) // 2, generator=gt, device=dev).to(bf)
+        qu = torch.randn(T, rr * H, generator=gt, device=dev).to(bf)
+        ou = torch.empty(T, rr * H, dtype=bf, device=dev)
+        plan_u = fdc.fdc_plan_prefill(lay_u, 0, [S] * B, [S] * B, pp)
+        wsu = torch.empty(plan_u.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+        offu = (-wsu.data_ptr()) % 256
+        wsu = wsu[offu:offu + plan_u.workspace_bytes()]
+        fdc.fdc_plan_upload(plan_u, wsu)
+        fn = lambda: fdc.fdc_latent_attn_prefill(lay_u, plan_u, qu, kcu, vcu, scale, True, ou, wsu)
+        fn()
+        torch.cuda.synchronize()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(iters):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        ms = s.elapsed_time(e) / iters
+        fl = float(B * H * rr * 2 * 2 * (S * (S + 1) // 2))
+        buckets["rank_%d" % rr] = {"ms": ms, "TFLOPs": fl / (ms * 1e-3) / 1e12}
+    out["latent_attn_prefill_by_uniform_rank"] = buckets
     return out
 
 
@@ -428,6 +478,7 @@ def main():
                    if wl.rank_seed is not None else "uniform 64", "kv_dtype": "bf16", "accumulate": "fp32"},
         "pct_of_hbm_peak": 100.0 * res["value"] / HBM_PEAK_GBPS,
         "roofline": res["roofline"], "decode_attn": res["decode_attn"],
+        "decode_other_calls_layer0": res["decode_other_calls_layer0"],
         "step_algorithmic_bytes": res["step_algorithmic_bytes"],
     }
     if not args.no_cpu_baseline:

@@ -211,3 +211,48 @@ def test_full_chain_config1_fp32():
     say(f"  chain max_abs={ma:.2e} rel_l2={rl:.2e}")
     ma, rl = assert_close(f64(o_lat), np.concatenate(ol, axis=1), "chain o_lat", rel_l2_tol=1e-4)
     say(f"  o_lat max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_config5_size_projection_and_apply_sampled_rows():
+    """The prefill-size products in the shape bench.py times (16384 tokens, d_model 4096, adaptive
+    ranks: N = 3360 with a ragged last column tile, K = 1680 with a k tail): 256 sampled token rows,
+    all columns, against the float64 oracle."""
+    wl = gen.CONFIGS["c5_prefill"]
+    r = wl.ranks()[0].tolist()
+    H, B, S, d, d_h = wl.n_heads, wl.batch, wl.context, wl.d_model, wl.d_head
+    T = B * S
+    say(f"config 5 size projections: T={T} d={d} RK+RV={2 * sum(r)}")
+    lay = fdc.Layout(1, H, d, d_h, [r], [r], B, S, fdc.FDC_BF16)
+    cache = Cache(lay)
+    bf = torch.bfloat16
+    gt = torch.Generator(device="cuda:0").manual_seed(3)
+    x = torch.randn(T, d, generator=gt, device="cuda:0").to(bf)
+    A_cat_t = (torch.randn(cache.RK + cache.RV, d, generator=gt, device="cuda:0") / math.sqrt(d)).to(bf)
+    tb = torch.arange(B, dtype=torch.int32, device="cuda:0").repeat_interleave(S)
+    tp = torch.arange(S, dtype=torch.int32, device="cuda:0").repeat(B)
+    fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A_cat_t, cache.k, cache.v)
+    o_lat = torch.randn(T, cache.RV, generator=gt, device="cuda:0").to(bf)
+    Mt = (torch.randn(d, cache.RV, generator=gt, device="cuda:0") / math.sqrt(cache.RV)).to(bf)
+    y = torch.full((T, d), float("nan"), dtype=bf, device="cuda:0")
+    fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt, o_lat, fdc.FDC_BF16, T, y, fdc.FDC_BF16)
+    torch.cuda.synchronize()
+    g = gen.make_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 257, S - 1, S, T - 257, T - 256, T - 1], g.integers(0, T, 246)]))
+    rows_t = torch.from_numpy(rows).cuda()
+    x64, A64 = f64(x[rows_t]), f64(A_cat_t)
+    kr, vr = cache.t["koff_r"][0], cache.t["voff_r"][0]
+    got, ref = [], []
+    for h in range(H):
+        Kh = oa.project_latent_kv(x64, [A64[kr[h]:kr[h + 1]].T])[0]
+        Vh = oa.project_latent_kv(x64, [A64[cache.RK + vr[h]:cache.RK + vr[h + 1]].T])[0]
+        for b in range(B):
+            sel = np.nonzero(rows // S == b)[0]
+            pos = torch.from_numpy(rows[sel] % S).cuda()
+            got.append(f64(cache.unit("k", b, h)[pos]).ravel()), ref.append(Kh[sel].ravel())
+            got.append(f64(cache.unit("v", b, h)[pos]).ravel()), ref.append(Vh[sel].ravel())
+    ma, rl = assert_close(np.concatenate(got), np.concatenate(ref), "config 5 latent rows")
+    say(f"  project max_abs={ma:.2e} rel_l2={rl:.2e}")
+    y_ref = f64(o_lat[rows_t]) @ f64(Mt).T
+    ma, rl = assert_close(f64(y[rows_t]), y_ref, "config 5 y rows")
+    say(f"  apply max_abs={ma:.2e} rel_l2={rl:.2e}")
+    assert torch.isfinite(y.float()).all().item()
