@@ -125,6 +125,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2g __attribute__((ext_vector_type(2)));
 typedef float f32x2g __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BN = 128, BK = 64;
@@ -291,6 +292,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
           store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc[i][j][e]);
         }
       }
+    }
+  }
+}
+
+// ---- query absorption for few rows (decode: T = batch) -------------------------------------------
+// q'_hq = q_hq . B_k^T has K = d_head <= 128: at most four MFMA steps. One wavefront per (query head,
+// 16 latent columns) keeps the whole B operand of its tile in registers and walks the row tiles;
+// with a few dozen rows this is a launch of a few hundred independent waves and no LDS.
+template <typename TC>
+__global__ __launch_bounds__(64) void absorb_query_small_kernel(const GemmArgs g) {
+  const Group gr = group_of(g, blockIdx.y);
+  const int n0 = blockIdx.x * 16;
+  if (n0 >= gr.N) return;
+  const int lane = threadIdx.x, ln = lane % 16, lg = lane / 16;
+  const uint16_t* A = static_cast<const uint16_t*>(g.A) + gr.a_off;
+  const uint16_t* B = static_cast<const uint16_t*>(g.B) + gr.b_off;
+  union Fr { u32x4 u; bf16x8 v; };
+  Fr b[4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int col = 32 * ks + 8 * lg;
+    b[ks].u = col < g.K ? *reinterpret_cast<const u32x4*>(B + (int64_t)(n0 + ln) * g.ldb + col) : u32x4{0, 0, 0, 0};
+  }
+  for (int m0 = 0; m0 < g.M; m0 += 16) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int col = 32 * ks + 8 * lg;
+      Fr a;
+      a.u = (m0 + ln < g.M && col < g.K) ? *reinterpret_cast<const u32x4*>(A + (int64_t)(m0 + ln) * g.lda + col)
+                                         : u32x4{0, 0, 0, 0};
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b[ks].v, acc, 0, 0, 0);
+    }
+    // register e of lane l is row 4 * (l / 16) + e, column l % 16
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int m = m0 + 4 * lg + e;
+      if (m < g.M) store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n0 + ln, acc[e]);
     }
   }
 }
@@ -554,7 +593,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // (about 1500 to 2000 at the 7B shapes) instead of the few 128 x 128 tiles of the large kernel.
 // Each wave accumulates MT 16 x 16 tiles (v_mfma_f32_16x16x32_bf16), the eight partial tiles are
 // summed through LDS in a fixed order (deterministic) and written by one wave per row tile.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kSkinnyWaves = 8;
 
 constexpr int kSkinnyChunkK = 512;             // k covered by one wave-wide 16-byte-per-lane load of a row
@@ -609,26 +647,31 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const Ge
     for (int i = 0; i < 16; ++i)
       rows[i] = __builtin_amdgcn_raw_buffer_load_b128(
           b_rsrc, (int)(i < b_rows ? (uint32_t)(((int64_t)i * g.ldb + k_lane) * 2) : 0x80000000u), 0, 2);
-#pragma unroll
-    for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(&wl[i * kSkinnyRow + lane * 8]) = rows[i];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     // 2. MFMA steps of 32 k: B operand from the wave's LDS strip, A operand (few rows, cache resident)
     //    from global, SG steps requested at a time. Chunks at k >= K are zeroed in A (the B strip may
-    //    hold the neighbouring range there).
+    //    hold the neighbouring range there). The first group of A chunks is requested before the B
+    //    rows are waited for, so the two latencies overlap.
     const int steps = (min(kSkinnyChunkK, k_end - kc) + 31) / 32;
-    for (int s0 = 0; s0 < steps; s0 += SG) {
-      u32x4 fa[SG][MT];
+    u32x4 fa[SG][MT];
+    auto request_a = [&](int s0) {
 #pragma unroll
       for (int u = 0; u < SG; ++u) {
         const int k = kc + 32 * (s0 + u) + 8 * lg;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          const u32x4 v = load_a(a_row[mt] + (uint32_t)(k * ES));
-          fa[u][mt] = k < g.K ? v : u32x4{0, 0, 0, 0};
+          const u32x4 v = load_a(k < g.K ? a_row[mt] + (uint32_t)(k * ES) : 0x80000000u);
+          fa[u][mt] = v;
         }
       }
+    };
+    request_a(0);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(&wl[i * kSkinnyRow + lane * 8]) = rows[i];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    for (int s0 = 0; s0 < steps; s0 += SG) {
+      if (s0 > 0) request_a(s0);
 #pragma unroll
       for (int u = 0; u < SG; ++u) {
         if (s0 + u >= steps) break;
@@ -789,6 +832,10 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
   if (lay->dtype == FDC_F32) {
     const dim3 grid((n_max + 15) / 16, (a.M + 15) / 16, groups);
     hipLaunchKernelGGL(gemm_f32_kernel<float>, grid, dim3(256), 0, st, a);
+  } else if (a.M <= 64 && a.mode == kAbsorbQuery && !a_f32 && a.K <= 128 && a.K % 8 == 0) {
+    const dim3 grid((n_max + 15) / 16, groups);
+    if (c_f32) hipLaunchKernelGGL(absorb_query_small_kernel<float>, grid, dim3(64), 0, st, a);
+    else hipLaunchKernelGGL(absorb_query_small_kernel<uint16_t>, grid, dim3(64), 0, st, a);
   } else if (a.M <= 64 && (a.mode == kPlain || a.mode == kProject)) {
     if (a_f32 && c_f32) launch_skinny<float, float>(a, st);
     else if (a_f32) launch_skinny<float, uint16_t>(a, st);
