@@ -250,18 +250,17 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     }
   }
 
-  // tiles = pieces numbered by (unit, t0)
+  // tiles = pieces numbered by (unit, t0): sort packed keys (unit, t0, piece) instead of indices
   const size_t n = pieces.size();
-  std::vector<int32_t> by_unit(n);
-  std::iota(by_unit.begin(), by_unit.end(), 0);
-  std::sort(by_unit.begin(), by_unit.end(), [&](int32_t a, int32_t c) {
-    const Piece &x = pieces[a], &y = pieces[c];
-    if (x.b != y.b) return x.b < y.b;
-    if (x.h != y.h) return x.h < y.h;
-    return x.t0 < y.t0;
-  });
-  std::vector<int32_t> tile_of_piece(n);
-  for (size_t tid = 0; tid < n; ++tid) tile_of_piece[by_unit[tid]] = (int32_t)tid;
+  std::vector<std::pair<uint64_t, int32_t>> keyed(n);
+  for (size_t k = 0; k < n; ++k)
+    keyed[k] = {((uint64_t)((int64_t)pieces[k].b * H + pieces[k].h) << 32) | (uint32_t)pieces[k].t0, (int32_t)k};
+  std::sort(keyed.begin(), keyed.end());
+  std::vector<int32_t> by_unit(n), tile_of_piece(n);
+  for (size_t tid = 0; tid < n; ++tid) {
+    by_unit[tid] = keyed[tid].second;
+    tile_of_piece[keyed[tid].second] = (int32_t)tid;
+  }
 
   fdc_plan* p = new (std::nothrow) fdc_plan();
   if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: out of host memory");
@@ -280,13 +279,19 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     p->max_items_per_unit = std::max(p->max_items_per_unit, p->unit_item_ptr[u + 1]);
     p->unit_item_ptr[u + 1] += p->unit_item_ptr[u];
   }
-  std::vector<std::vector<int32_t>> lists(W);
+  // worker lists in hand-out order (pieces are in that order): counting sort into CSR form
   p->worker_load.assign(W, 0);
-  for (size_t k = 0; k < n; ++k) {  // pieces are in hand-out order
-    lists[pieces[k].w].push_back(tile_of_piece[k]);
+  p->worker_ptr.assign((size_t)W + 1, 0);
+  for (size_t k = 0; k < n; ++k) {
+    p->worker_ptr[pieces[k].w + 1] += 1;
     p->worker_load[pieces[k].w] += (int64_t)(pieces[k].t1 - pieces[k].t0) * d_sum[pieces[k].h];
   }
-  worker_csr(lists, p);
+  for (int w = 0; w < W; ++w) p->worker_ptr[w + 1] += p->worker_ptr[w];
+  p->worker_items.resize(n);
+  {
+    std::vector<int32_t> fill(p->worker_ptr.begin(), p->worker_ptr.end() - 1);
+    for (size_t k = 0; k < n; ++k) p->worker_items[fill[pieces[k].w]++] = tile_of_piece[k];
+  }
 
   // device image
   const int64_t* koff = &lay->koff[(size_t)layer * H];
@@ -322,20 +327,27 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
       units[(size_t)u * g + j] = {first, first + n_u, g * (b * p->RV + voff_r[h]) + j * rv[h], rv[h]};
     }
   }
-  // tiles in worker (hand-out) order plus one header per worker
-  std::vector<DecTile> wtiles(n);
+  // device image: tiles in worker (hand-out) order, merge records, one header per worker; built in
+  // place (one allocation, no intermediate copies)
+  auto region = [&](size_t bytes) {
+    const size_t off = (p->image.size() + 255) / 256 * 256;
+    p->image.resize(off + std::max<size_t>(bytes, 16));
+    return off;
+  };
+  p->image.reserve(n * sizeof(DecTile) + units.size() * sizeof(DecUnit) + (size_t)W * sizeof(DecWorker) + 1024);
+  p->off_items = region(n * sizeof(DecTile));
+  p->off_units = region(units.size() * sizeof(DecUnit));
+  p->off_worker_ptr = region((size_t)W * sizeof(DecWorker));
+  p->off_worker_items = p->off_worker_ptr;
+  DecTile* wtiles = reinterpret_cast<DecTile*>(p->image.data() + p->off_items);
   for (size_t i = 0; i < n; ++i) wtiles[i] = tiles[p->worker_items[i]];
-  std::vector<DecWorker> heads(W);
+  if (!units.empty()) std::memcpy(p->image.data() + p->off_units, units.data(), units.size() * sizeof(DecUnit));
+  DecWorker* heads = reinterpret_cast<DecWorker*>(p->image.data() + p->off_worker_ptr);
   for (int w = 0; w < W; ++w) {
-    std::memset(&heads[w], 0, sizeof(DecWorker));
     heads[w].begin = p->worker_ptr[w];
     heads[w].count = p->worker_ptr[w + 1] - p->worker_ptr[w];
     if (heads[w].count > 0) heads[w].first = wtiles[heads[w].begin];
   }
-  p->off_items = append_aligned(p->image, wtiles.data(), wtiles.size());
-  p->off_units = append_aligned(p->image, units.data(), units.size());
-  p->off_worker_ptr = append_aligned(p->image, heads.data(), heads.size());
-  p->off_worker_items = p->off_worker_ptr;
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = std::max<size_t>(n * p->G, 1) * kPartialStride * sizeof(float);
   p->workspace_bytes = p->off_partials + p->partial_bytes;
