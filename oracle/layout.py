@@ -45,3 +45,20 @@ def element_index(tables, ranks, max_seq: int, l: int, b: int, h: int, t: int, i
     """Flat element index of latent component i of token t of unit (b, h) in layer l."""
     R = int(tables["off_r"][l, -1])
     return b * int(max_seq) * R + int(tables["off"][l, h]) + t * int(ranks[l][h]) + i
+
+
+def paged_element_index(ranks_layer, page_tokens: int, block_table_row, h: int, t: int, i: int) -> int:
+    """Flat element index of latent component i of token t of head h of ONE sequence in a paged buffer.
+
+    Paged storage (the usual block-table scheme of serving systems; the paper's system runs on
+    one, Section 6.1, but gives no layout): the buffer of a layer is an array of pages; a page is
+    the dense layout above for page_tokens tokens of one sequence, [head][token][component]:
+        index = page * page_tokens * R + page_tokens * sum_{h' < h} r[h'] + (t % P) * r[h] + i
+    with page = block_table_row[t // P] the physical page of the sequence's logical page t // P.
+    In terms of layout_tables this is a layout with max_batch = number of pages, max_seq = P.
+    """
+    P = int(page_tokens)
+    R = sum(int(x) for x in ranks_layer)
+    before = sum(int(ranks_layer[hh]) for hh in range(h))
+    page = int(block_table_row[t // P])
+    return page * P * R + P * before + (t % P) * int(ranks_layer[h]) + i

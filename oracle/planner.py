@@ -66,7 +66,7 @@ def lpt_assign(costs, n_workers: int, presorted: bool = False):
 
 
 def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: int = 1,
-                split: bool = True, softmax_cost: int = 1):
+                split: bool = True, softmax_cost: int = 1, page_tokens: int = 0):
     """Decode plan for one layer.
 
     seq_len int [B]; rk, rv int [H]. Steps:
@@ -83,6 +83,10 @@ def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: i
          chunk goes to the then least-loaded worker, and so on; no load exceeds
          mean + G * max d_sum. With split = False the room is unlimited and steps 1-3 are exactly
          the paper's scheduling.
+      5. paged cache (page_tokens = P > 0, P a multiple of G): a sequence's tokens live in pages
+         of P tokens that need not be adjacent in memory, so after step 4 every piece is cut at
+         the multiples of P it contains; the parts stay with the piece's worker, in order. The
+         schedule itself (steps 1-4) does not depend on P.
     The pieces become tiles, numbered by (unit, t0). Returns a dict of numpy tables:
       tile_b, tile_h, tile_t0, tile_t1 int32 [n_tiles]; tile_cost int64 [n_tiles]
       unit_tile_ptr int32 [B*H + 1]  (tiles of unit u = b*H + h are
@@ -121,7 +125,12 @@ def plan_decode(seq_len, rk, rv, n_workers: int, granule: int = 64, min_split: i
                 step = G * d_sum[h]
                 fit = max(1, (2 * room + step) // (2 * step)) * G   # nearest granule count, at least one
                 take = min(take, fit)
-            pieces.append((b, h, t0, t0 + take, w, len(pieces)))
+            end = t0 + take
+            lo = t0
+            while lo < end:                     # one piece per page it touches (all of it when unpaged)
+                hi = min(end, (lo // page_tokens + 1) * page_tokens) if page_tokens > 0 else end
+                pieces.append((b, h, lo, hi, w, len(pieces)))
+                lo = hi
             loads[w] += take * d_sum[h]
             t0 += take
 

@@ -260,3 +260,63 @@ def test_rank_selection_geometric_closed_form():
     # flat spectrum: removing m of n dimensions removes m/n of the mass
     flat = np.ones(10)
     assert ors.last_kept_index(flat, 0.35) == 6             # dims 7,8,9 removed (0.3 <= 0.35 < 0.4)
+
+
+def test_paged_plan_is_the_unpaged_plan_cut_at_page_boundaries():
+    """Paging must not change the schedule, only cut tiles where a page ends."""
+    rk, rv = [16, 64, 32], [32, 64, 16]
+    seq = [0, 5, 700, 1300, 256]
+    for W, G, P, ms in [(7, 64, 256, 1), (40, 16, 64, 2), (3, 64, 64, 1), (500, 32, 128, 3)]:
+        base = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms)
+        paged = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms, page_tokens=P)
+        assert np.array_equal(base["worker_load"], paged["worker_load"])
+        # no tile crosses a page boundary, and the tiles still tile every unit exactly
+        assert np.all(paged["tile_t0"] // P == (paged["tile_t1"] - 1) // P)
+        H = len(rk)
+        for b, S in enumerate(seq):
+            for h in range(H):
+                u = b * H + h
+                lo, hi = paged["unit_tile_ptr"][u], paged["unit_tile_ptr"][u + 1]
+                cover = sorted(zip(paged["tile_t0"][lo:hi], paged["tile_t1"][lo:hi]))
+                assert [c[0] for c in cover] == ([0] + [c[1] for c in cover[:-1]] if cover else [])
+                assert (cover[-1][1] if cover else 0) == S
+        # merging the parts of a worker's consecutive tiles gives back the unpaged worker lists
+        def spans(plan, w):
+            out = []
+            for t in plan["worker_tiles"][plan["worker_ptr"][w]:plan["worker_ptr"][w + 1]]:
+                key = (int(plan["tile_b"][t]), int(plan["tile_h"][t]))
+                a, b_ = int(plan["tile_t0"][t]), int(plan["tile_t1"][t])
+                if out and out[-1][0] == key and out[-1][2] == a and a % P == 0:
+                    out[-1] = (key, out[-1][1], b_)
+                else:
+                    out.append((key, a, b_))
+            return out
+        for w in range(W):
+            merged, ref = spans(paged, w), spans(base, w)
+            # a base piece that itself starts on a page boundary right after the previous one would merge
+            # too; compare the covered token sets per unit instead of the span lists in that case
+            cov = lambda sp: sorted((k, t) for k, a, b_ in sp for t in range(a, b_, G))
+            assert cov(merged) == cov(ref)
+    # P = 0 is the unpaged plan itself
+    a, b = op.plan_decode(seq, rk, rv, 9), op.plan_decode(seq, rk, rv, 9, page_tokens=0)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
+
+
+def test_paged_element_index_is_a_bijection_onto_the_pages():
+    from oracle import layout as ol
+    ranks = [16, 48, 32]
+    P, n_pages = 8, 5
+    table = [3, 0, 4]                      # a sequence of up to 24 tokens
+    seen = set()
+    for h in range(3):
+        for t in range(19):
+            for i in range(ranks[h]):
+                e = ol.paged_element_index(ranks, P, table, h, t, i)
+                assert 0 <= e < n_pages * P * sum(ranks) and e not in seen
+                seen.add(e)
+                # same element through the dense layout with batch = page, max_seq = P
+                tabs = ol.layout_tables([ranks], n_pages, P)
+                assert e == ol.element_index(tabs, [ranks], P, 0, table[t // P], h, t % P, i)
+    # tokens of one page and head are one contiguous run
+    run = [ol.paged_element_index(ranks, P, table, 1, t, i) for t in range(8, 16) for i in range(48)]
+    assert run == list(range(run[0], run[0] + 8 * 48))
