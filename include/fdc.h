@@ -150,6 +150,22 @@ fdc_status fdc_suggest_workers(int kind, int32_t* n_workers);
 fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
                            const fdc_plan_params* params, fdc_plan** out);
 
+/* Decode plan over a PAGED cache (block tables, as serving systems keep them; Section 6.1 runs on
+ * one). The layout describes the pages: its batch rows are the physical pages (max_batch = number of
+ * pages) and max_seq = P, the tokens per page; a page holds P tokens of one sequence in the dense
+ * [head][token][component] order of the layout, so fdc_project_latent_kv / fdc_rope_compress_keys
+ * write a token with tok_batch = its page and tok_pos = its offset inside the page.
+ *   seq_len      host int32 [batch], 0 <= seq_len[b] <= P * max_pages (batch is not limited by the layout)
+ *   block_table  host int32 [batch * max_pages]: block_table[b * max_pages + i] = page of tokens
+ *                i*P .. (i+1)*P - 1 of sequence b; entries past ceil(seq_len[b] / P) are not read
+ * P must be a multiple of params->granule. The schedule is that of fdc_plan_decode for the same
+ * seq_len; every piece is then cut at the page boundaries it contains (item_lo / item_hi are token
+ * positions in the sequence). fdc_latent_attn_decode takes the plan unchanged; q_lat and o_lat are
+ * indexed by sequence. Prefill attention needs the dense layout. */
+fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
+                                 const int32_t* block_table, int max_pages,
+                                 const fdc_plan_params* params, fdc_plan** out);
+
 /* q_len, kv_len: host int32 [batch]; the queries of sequence b are its last q_len[b] positions,
  * q_len[b] <= kv_len[b] <= max_seq. Query rows of all sequences are stacked b-major: T = sum q_len. */
 fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,

@@ -21,7 +21,7 @@ FDC_FOLD, FDC_APPLY = 0, 1
 
 EXPORTED_SYMBOLS = [
     "fdc_last_error", "fdc_layout_create", "fdc_layout_create_gqa", "fdc_layout_tables", "fdc_layout_destroy",
-    "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_prefill",
+    "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_decode_paged", "fdc_plan_prefill",
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
@@ -74,6 +74,8 @@ def lib() -> C.CDLL:
         l.fdc_plan_params_default.restype = None
         l.fdc_suggest_workers.argtypes = [C.c_int, i32p]
         l.fdc_plan_decode.argtypes = [vp, C.c_int, C.c_int, i32p, C.POINTER(PlanParams), C.POINTER(vp)]
+        l.fdc_plan_decode_paged.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, C.c_int, C.POINTER(PlanParams),
+                                            C.POINTER(vp)]
         l.fdc_plan_prefill.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, C.POINTER(PlanParams), C.POINTER(vp)]
         l.fdc_plan_export.argtypes = [vp, C.POINTER(PlanTables)]
         l.fdc_plan_workspace_bytes.argtypes = [vp]
@@ -220,6 +222,18 @@ def fdc_plan_decode(layout: Layout, layer: int, seq_len: Sequence[int], params: 
     s = _i32(seq_len)
     h = C.c_void_p()
     _check(lib().fdc_plan_decode(layout.handle, layer, int(s.size), _p32(s), C.byref(params), C.byref(h)))
+    return Plan(h, layout)
+
+
+def fdc_plan_decode_paged(layout: Layout, layer: int, seq_len: Sequence[int], block_table, params: PlanParams) -> Plan:
+    """block_table: int [batch, max_pages]; the layout's batch rows are the pages, max_seq the page size."""
+    s = _i32(seq_len)
+    bt = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if bt.ndim != 2 or bt.shape[0] != s.size:
+        raise ValueError("block_table must be [batch, max_pages]")
+    h = C.c_void_p()
+    _check(lib().fdc_plan_decode_paged(layout.handle, layer, int(s.size), _p32(s), _p32(bt.reshape(-1)),
+                                       int(bt.shape[1]), C.byref(params), C.byref(h)))
     return Plan(h, layout)
 
 

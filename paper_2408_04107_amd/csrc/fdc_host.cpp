@@ -183,15 +183,42 @@ static fdc_status check_plan_args(const char* fn, const fdc_layout* lay, int lay
   return FDC_OK;
 }
 
-fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
-                           const fdc_plan_params* pr, fdc_plan** out) {
-  fdc_status st = check_plan_args("fdc_plan_decode", lay, layer, batch, seq_len, pr, out);
-  if (st != FDC_OK) return st;
+}  // extern "C"
+
+// Decode planning. block_table == nullptr: the dense layout (sequence b is batch row b of the cache).
+// Otherwise the cache is paged: the layout's batch rows are pages of P = lay->max_seq tokens and
+// block_table[b * max_pages + i] is the page that holds tokens i*P .. of sequence b.
+static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int layer, int batch,
+                                   const int32_t* seq_len, const int32_t* block_table, int max_pages,
+                                   const fdc_plan_params* pr, fdc_plan** out) {
+  if (!out) FDC_FAIL(FDC_INVALID_ARG, "%s: out is NULL", fn);
+  *out = nullptr;
+  if (!lay || !seq_len || !pr) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
+  if (layer < 0 || layer >= lay->L) FDC_FAIL(FDC_BAD_SHAPE, "%s: layer %d outside [0, %d)", fn, layer, lay->L);
+  const bool paged = block_table != nullptr;
+  if (batch <= 0 || (!paged && batch > lay->max_batch))
+    FDC_FAIL(FDC_BAD_SHAPE, "%s: batch %d outside [1, %d]", fn, batch, lay->max_batch);
+  if (pr->n_workers <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: n_workers must be positive", fn);
+  if (pr->softmax_cost <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: softmax_cost must be positive", fn);
   if (pr->granule <= 0 || pr->min_split <= 0)
-    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: granule and min_split must be positive");
-  for (int b = 0; b < batch; ++b)
-    if (seq_len[b] < 0 || seq_len[b] > lay->max_seq)
-      FDC_FAIL(FDC_BAD_SHAPE, "fdc_plan_decode: seq_len[%d] = %d outside [0, %d]", b, seq_len[b], lay->max_seq);
+    FDC_FAIL(FDC_INVALID_ARG, "%s: granule and min_split must be positive", fn);
+  const int64_t P = paged ? lay->max_seq : 0;   // page size in tokens (0: not paged)
+  if (paged) {
+    if (max_pages <= 0) FDC_FAIL(FDC_BAD_SHAPE, "%s: max_pages must be positive", fn);
+    if (P % pr->granule != 0)
+      FDC_FAIL(FDC_INVALID_ARG, "%s: the page size %d must be a multiple of the granule %d", fn, (int)P, pr->granule);
+  }
+  const int64_t seq_cap = paged ? P * max_pages : lay->max_seq;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_len[b] < 0 || seq_len[b] > seq_cap)
+      FDC_FAIL(FDC_BAD_SHAPE, "%s: seq_len[%d] = %d outside [0, %lld]", fn, b, seq_len[b], (long long)seq_cap);
+    if (paged)
+      for (int64_t i = 0; i < ceil_div(seq_len[b], P); ++i) {
+        const int32_t pg = block_table[(size_t)b * max_pages + i];
+        if (pg < 0 || pg >= lay->max_batch)
+          FDC_FAIL(FDC_BAD_SHAPE, "%s: block_table[%d][%lld] = %d outside [0, %d)", fn, b, (long long)i, pg, lay->max_batch);
+      }
+  }
 
   const int H = lay->H, W = pr->n_workers;
   const int64_t G = pr->granule;
@@ -243,7 +270,11 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
         const int64_t fit = std::max<int64_t>(1, (2 * room + step) / (2 * step)) * G;
         take = std::min(take, fit);
       }
-      pieces.push_back({c.b, c.h, (int32_t)t0, (int32_t)(t0 + take), top.second});
+      for (int64_t lo = t0, end = t0 + take; lo < end;) {   // one piece per page it touches
+        const int64_t hi = P > 0 ? std::min(end, (lo / P + 1) * P) : end;
+        pieces.push_back({c.b, c.h, (int32_t)lo, (int32_t)hi, top.second});
+        lo = hi;
+      }
       top.first += take * d_sum[c.h];
       heap.push(top);
       t0 += take;
@@ -263,7 +294,7 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
   }
 
   fdc_plan* p = new (std::nothrow) fdc_plan();
-  if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode: out of host memory");
+  if (!p) FDC_FAIL(FDC_INVALID_ARG, "%s: out of host memory", fn);
   p->kind = 0, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
   p->G = lay->G;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer), p->total_q_rows = batch;
@@ -304,8 +335,12 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
     const int u = b * H + h;
     DecTile& t = tiles[tid];
     std::memset(&t, 0, sizeof(t));
-    t.k_elem = (int64_t)b * lay->max_seq * p->RK + koff[h] + (int64_t)p->item_lo[tid] * rk[h];
-    t.v_elem = (int64_t)b * lay->max_seq * p->RV + voff[h] + (int64_t)p->item_lo[tid] * rv[h];
+    // cache row of the tile's first token: the sequence's own batch row, or the page that holds it
+    const int64_t lo = p->item_lo[tid];
+    const int64_t row = paged ? block_table[(size_t)b * max_pages + lo / P] : b;
+    const int64_t in_row = paged ? lo % P : lo;
+    t.k_elem = row * lay->max_seq * p->RK + koff[h] + in_row * rk[h];
+    t.v_elem = row * lay->max_seq * p->RV + voff[h] + in_row * rv[h];
     t.len = p->item_hi[tid] - p->item_lo[tid];
     // with g query heads per unit the query-side tensors are g times as wide and the partial
     // slots of a unit hold its tiles once per query head: slot = g * first + j * n_u + i
@@ -353,6 +388,23 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
   p->workspace_bytes = p->off_partials + p->partial_bytes;
   *out = p;
   return FDC_OK;
+}
+
+extern "C" {
+
+fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
+                           const fdc_plan_params* pr, fdc_plan** out) {
+  return plan_decode_impl("fdc_plan_decode", lay, layer, batch, seq_len, nullptr, 0, pr, out);
+}
+
+fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
+                                 const int32_t* block_table, int max_pages, const fdc_plan_params* pr,
+                                 fdc_plan** out) {
+  if (!block_table) {
+    if (out) *out = nullptr;
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode_paged: block_table is NULL");
+  }
+  return plan_decode_impl("fdc_plan_decode_paged", lay, layer, batch, seq_len, block_table, max_pages, pr, out);
 }
 
 fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,

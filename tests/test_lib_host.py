@@ -152,6 +152,39 @@ def test_grouped_query_plans_bit_exact():
         fdc.Layout(1, 3, 256, 128, [rk], [rv], 1, 16, fdc.FDC_BF16, q_per_kv=0)
 
 
+def test_paged_decode_plan_bit_exact():
+    rk, rv = [16, 64, 32, 128], [32, 64, 16, 128]
+    g = gen.make_rng(5)
+    for P, G, W, ms in [(256, 64, 37, 1), (64, 64, 9, 2), (128, 32, 300, 1), (64, 16, 5, 3)]:
+        seq = [0, 5, 700, 1300, 256, 64]
+        max_pages = max(-(-x // P) for x in seq)
+        n_pages = sum(-(-x // P) for x in seq) + 3
+        perm = g.permutation(n_pages)
+        bt = np.full((len(seq), max_pages), -7, dtype=np.int32)      # entries past a sequence's end are never read
+        k = 0
+        for b, S in enumerate(seq):
+            for i in range(-(-S // P)):
+                bt[b, i] = perm[k]
+                k += 1
+        lay = fdc.Layout(1, len(rk), 256, 128, [rk], [rv], n_pages, P, fdc.FDC_BF16)
+        pp = fdc.fdc_plan_params_default()
+        pp.n_workers, pp.granule, pp.min_split = W, G, ms
+        got = fdc.fdc_plan_decode_paged(lay, 0, seq, bt, pp).export()
+        ref = op.plan_decode(seq, rk, rv, W, granule=G, min_split=ms, page_tokens=P)
+        for a, b_ in DEC_PAIRS:
+            assert got[a].dtype == ref[b_].dtype and np.array_equal(got[a], ref[b_]), (a, P, G, W)
+    lay = fdc.Layout(1, 4, 256, 128, [rk], [rv], 4, 64, fdc.FDC_BF16)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 4
+    with pytest.raises(fdc.FdcError):          # page id outside the layout
+        fdc.fdc_plan_decode_paged(lay, 0, [100], [[0, 4]], pp)
+    with pytest.raises(fdc.FdcError):          # sequence longer than its block table
+        fdc.fdc_plan_decode_paged(lay, 0, [129], [[0, 1]], pp)
+    pp.granule = 48
+    with pytest.raises(fdc.FdcError):          # page size not a multiple of the granule
+        fdc.fdc_plan_decode_paged(lay, 0, [100], [[0, 1]], pp)
+
+
 def test_select_ranks_bit_exact_with_oracle():
     """Eq. (1): the library's rank choice equals the oracle's on planted, random and tie-prone spectra."""
     from oracle import rank_select as ors
