@@ -40,7 +40,6 @@ constexpr int BC = 64;                   // tokens per K'/V' block
 constexpr int kRowsPerWave = 16 * QT;
 constexpr int kRowsPerPass = 128;
 constexpr int kPreThreads = 64 * (kRowsPerPass / kRowsPerWave);
-constexpr int kStageRows = kPreThreads / 16;  // token rows one staging sweep covers
 constexpr int kPreWavesPerSimd = QT == 1 ? 4 : 2;  // two workgroups per compute unit either way
 constexpr int KROW = 128 + 8;            // LDS row length of the K' tile in elements (272 bytes)
 constexpr int VROW = 128 + 16;           // LDS row length of the V' tile in elements (288 bytes)
@@ -100,18 +99,36 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     }
   }
 
-  // staging map: 16 lanes per token row (a row has at most 16 chunks of 16 bytes), 16 rows per
-  // sweep, 4 sweeps per block; narrow heads leave the upper lanes of a row idle. No divisions.
-  constexpr int kSweeps = BC / kStageRows;
-  const int s_row = tid / 16, s_cc = tid % 16;
-  const bool k_lane = s_cc * 8 < rk, v_lane = s_cc * 8 < rv;
+  // staging map: a token row of rank r is r / 8 chunks of 16 bytes; thread tid takes chunk
+  // tid % (r/8) of row tid / (r/8), so every lane of a sweep carries data whatever the rank (one
+  // division per task). A sweep covers kPreThreads / (r/8) >= 32 rows: one sweep per block for
+  // ranks <= 64, two above. K' and V' have their own maps (rk != rv).
+  constexpr int kSweeps = 2;
+  const int lpk = rk / 8, lpv = rv / 8;
+  const int k_rps = kPreThreads / lpk, v_rps = kPreThreads / lpv;
+  const int k_row = tid / lpk, k_cc = tid - k_row * lpk;
+  const int v_row = tid / lpv, v_cc = tid - v_row * lpv;
+  const int k_sweeps = (BC + k_rps - 1) / k_rps, v_sweeps = (BC + v_rps - 1) / v_rps;
   // the unit's K' and V' rows [0, kv_len) as raw buffers (at most 131072 * 256 bytes each)
   const __amdgpu_buffer_rsrc_t k_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kbase), 0, t.kv_len * rk * 2, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vbase), 0, t.kv_len * rv * 2, 0x00020000);
-  const uint32_t k_lane_off = k_lane ? (uint32_t)(s_cc * 16) : 0x80000000u;
-  const uint32_t v_lane_off = v_lane ? (uint32_t)(s_cc * 16) : 0x80000000u;
+  // per sweep: byte offset of the lane's chunk in block 0 (out of range when the lane has no row)
+  // and its LDS element offset
+  uint32_t k_goff[kSweeps], v_goff[kSweeps];
+  int k_loff[kSweeps], v_loff[kSweeps];
+  bool k_on[kSweeps], v_on[kSweeps];
+#pragma unroll
+  for (int i = 0; i < kSweeps; ++i) {
+    const int kr = k_row + i * k_rps, vr = v_row + i * v_rps;
+    k_on[i] = k_row < k_rps && kr < BC;
+    v_on[i] = v_row < v_rps && vr < BC;
+    k_goff[i] = k_on[i] ? (uint32_t)(kr * rk * 2 + k_cc * 16) : 0x80000000u;
+    v_goff[i] = v_on[i] ? (uint32_t)(vr * rv * 2 + v_cc * 16) : 0x80000000u;
+    k_loff[i] = kr * KROW + k_cc * 8;
+    v_loff[i] = vr * VROW + v_cc * 8;
+  }
 
   for (int r0 = 0; r0 < t.rows; r0 += kRowsPerPass) {
     const int pass_rows = min(kRowsPerPass, t.rows - r0);
@@ -147,12 +164,11 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
 
     // register staging of the next block
     u32x4 kst[kSweeps], vst[kSweeps];
-    auto fetch = [&](int c0) {  // rows past kv_len and idle lanes read zeros through the range check
+    auto fetch = [&](int c0) {  // rows past kv_len and lanes without a row read zeros through the range check
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        const uint32_t tok = (uint32_t)(c0 + s_row + kStageRows * i);
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(k_lane_off + tok * (uint32_t)(rk * 2)), 0, 0);
-        vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(v_lane_off + tok * (uint32_t)(rv * 2)), 0, 0);
+        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(k_goff[i] + (uint32_t)(c0 * rk * 2)), 0, 0);
+        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(v_goff[i] + (uint32_t)(c0 * rv * 2)), 0, 0);
       }
     };
     auto stage = [&](int buf) {
@@ -160,9 +176,8 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
       uint16_t* lv = lk + BC * KROW;
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        const int r = s_row + kStageRows * i;
-        if (k_lane) *reinterpret_cast<u32x4*>(&lk[r * KROW + s_cc * 8]) = kst[i];
-        if (v_lane) *reinterpret_cast<u32x4*>(&lv[r * VROW + s_cc * 8]) = vst[i];
+        if (i < k_sweeps && k_on[i]) *reinterpret_cast<u32x4*>(&lk[k_loff[i]]) = kst[i];
+        if (i < v_sweeps && v_on[i]) *reinterpret_cast<u32x4*>(&lv[v_loff[i]]) = vst[i];
       }
     };
 
@@ -170,12 +185,12 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     if (kv_end > 0) {
       fetch(0);
       stage(0);
+      if (BC < kv_end) fetch(BC);
     }
     __syncthreads();
     int buf = 0;
     for (int c0 = 0; c0 < kv_end; c0 += BC, buf ^= 1) {
-      const bool more = c0 + BC < kv_end;
-      if (more) fetch(c0 + BC);
+      const bool more = c0 + BC < kv_end;   // its rows are in flight or already in the staging registers
       if (wave_on && !(causal && c0 > wave_last_pos)) {  // otherwise nothing visible for this wave (uniform)
         const uint16_t* lk = lds + buf * kStageElems;
         const uint16_t* lv = lk + BC * KROW;
@@ -276,6 +291,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         }
       }
       if (more) stage(buf ^ 1);  // the other buffer was last read before the previous barrier
+      if (c0 + 2 * BC < kv_end) fetch(c0 + 2 * BC);   // requested before the barrier: its wait is part of the lead
       __syncthreads();
     }
 
