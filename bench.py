@@ -127,6 +127,16 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     y = torch.empty(B, d, dtype=bf, device=dev)
     scale = 1.0 / math.sqrt(dh)
 
+    # replanning cost of a whole step's worth of layers, planned concurrently on the host cores (the
+    # planner is pure host code and the binding releases the GIL): what a serving loop pays each time
+    # a sequence crosses a granule boundary, i.e. once per `granule` decode steps
+    from concurrent.futures import ThreadPoolExecutor
+    n_thr = min(16, os.cpu_count() or 1, L)
+    with ThreadPoolExecutor(n_thr) as ex:
+        t0 = time.perf_counter()
+        list(ex.map(lambda l: fdc.fdc_plan_decode(lay, l, [S] * B, pp), range(L)))
+        replan_ms = (time.perf_counter() - t0) * 1e3
+
     tabs = [p.export() for p in plans]
     dec_bytes = [decode_bytes(tabs[l], ranks[l], ranks[l], [S] * B, int(t["koff_r"][l, -1]),
                               int(t["voff_r"][l, -1]), B) for l in range(L)]
@@ -227,7 +237,10 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
                         "tile_kernel_GBps_per_layer": {"min": float(layer_gbps.min()), "max": float(layer_gbps.max())},
                         "GBps_call": avg_bytes / (attn_us_per_layer * 1e-6) / 1e9,
                         "planner_imbalance_max_over_mean": {"mean": float(np.mean(imb)), "max": float(np.max(imb))},
-                        "plan_host_ms_per_layer": t_plan * 1e3 / L, "n_workers": W,
+                        "plan_host_ms_per_layer": t_plan * 1e3 / L,
+                        "replan_all_layers_ms": replan_ms, "replan_threads": n_thr,
+                        "replan_amortised_fraction_of_step": replan_ms / pp.granule / ms_per_step,
+                        "n_workers": W,
                         "tiles_per_layer": float(np.mean([tb_["n_items"] for tb_ in tabs]))},
         "decode_other_calls_layer0": small,
         "step_algorithmic_bytes": step_bytes,
