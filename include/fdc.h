@@ -248,7 +248,8 @@ fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* 
 
 /* Decode attention on the latent cache, one query per sequence (Section 5, step 7; Section 5.3
  * decode scheduling): o'_h = softmax_t(scale * <q'_h, K'_h[t]>) . V'_h over t < seq_len[b].
- *   q_lat [batch, RK] f32, o_lat [batch, RV] f32, scale normally 1/sqrt(d_head).
+ *   q_lat [batch, RK] f32, o_lat [batch, RV] f32, scale > 0 and finite, normally 1/sqrt(d_head)
+ *   (FDC_INVALID_ARG otherwise; the same holds for fdc_latent_attn_prefill).
  *   workspace: prepared by fdc_plan_upload for this plan. Sequences with seq_len 0 give zeros.
  * Calls that share a workspace must not overlap in time. */
 fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,

@@ -416,6 +416,8 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: NULL argument");
   if (plan->kind != 0 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: not a decode plan of this layout");
+  if (!(scale > 0.f) || !(scale < 1e30f))
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: scale must be positive and finite (the running softmax orders scores by scale * s)");
   if (workspace_bytes < plan->workspace_bytes)
     FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_latent_attn_decode: workspace has %zu bytes, the plan needs %zu",
              workspace_bytes, plan->workspace_bytes);

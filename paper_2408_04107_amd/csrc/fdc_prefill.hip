@@ -348,6 +348,8 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: NULL argument");
   if (plan->kind != 1 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: not a prefill plan of this layout");
   if (lay->dtype != FDC_BF16) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_prefill: bf16 layouts only");
+  if (!(scale > 0.f) || !(scale < 1e30f))
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: scale must be positive and finite (the running softmax orders scores by scale * s)");
   if (workspace_bytes < plan->workspace_bytes)
     FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_latent_attn_prefill: workspace has %zu bytes, the plan needs %zu",
              workspace_bytes, plan->workspace_bytes);

@@ -194,3 +194,19 @@ def test_decode_argument_errors():
     with pytest.raises(fdc.FdcError) as e:
         fdc.fdc_latent_attn_decode(other, plan, q, cache.k, cache.v, 0.1, o, ws)
     assert e.value.status == -1
+
+
+def test_non_positive_scale_is_rejected():
+    say("scale <= 0 or non-finite is an error")
+    lay = fdc.Layout(1, 2, 256, 128, [[16, 64]], [[32, 16]], 1, 64, fdc.FDC_BF16)
+    cache = Cache(lay)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 4
+    plan = fdc.fdc_plan_decode(lay, 0, [64], pp)
+    ws = workspace_for(plan)
+    q = torch.zeros(1, cache.RK, device="cuda:0")
+    o = torch.zeros(1, cache.RV, device="cuda:0")
+    for bad in (0.0, -0.1, float("inf"), float("nan")):
+        with pytest.raises(fdc.FdcError) as e:
+            fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, bad, o, ws)
+        assert e.value.status == -1
