@@ -739,6 +739,135 @@ static void launch_skinny(const GemmArgs& a, hipStream_t st) {
   else go(gemm_skinny_kernel<TA, TC, 4>);
 }
 
+// ---- the same weight stream at M <= 16 (one MFMA row tile: the decode batch) ---------------------
+// Timing stamps inside the kernel above showed what bounds a launch this short (27 MB of weights is
+// ~0.1 MB per compute unit): each compute unit pulls its bytes through one vector-memory pipe, and the
+// activations (16 x K, read again by every workgroup, from L2) load that pipe as much as the weights.
+// So here (a) every load of a chunk, activations and weights, is in flight before the first wait,
+// (b) the activations are requested first and read like the weights (1 KiB contiguous per
+// instruction: half the requests of 64-byte fragment reads): they come from L2, land early, and
+// are transposed through the wave's LDS strip while the weight rows are still on their way from
+// HBM; fp32 activations are rounded to bf16 at that point, (c) the sixteen LDS fragment reads of
+// the weights are issued together instead of one wait per MFMA. WAVES waves split K.
+template <typename TA, typename TC, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny16_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t skinny_lds[];
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int ln = lane % 16, lg = lane / 16;
+  const int n0 = blockIdx.x * 16;
+  const uint16_t* B = static_cast<const uint16_t*>(g.B);
+  uint16_t* wl = skinny_lds + wave * 16 * kSkinnyRow;
+  const int k_per_wave = ((g.K + WAVES - 1) / WAVES + 63) / 64 * 64;
+  const int k_begin = wave * k_per_wave, k_end = min(g.K, k_begin + k_per_wave);
+  f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+  // unconditional loads: offsets of rows past N / M and of k past the wave's range are forced out of
+  // the buffer's range and return zeros
+  const int b_rows = min(16, g.N - n0);
+  constexpr int ES = (int)sizeof(TA);
+  const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(B + (int64_t)n0 * g.ldb), 0, (int)(((int64_t)(b_rows - 1) * g.ldb + g.K) * 2), 0x00020000);
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(g.A), 0, (int)(((int64_t)(g.M - 1) * g.lda + g.K) * ES), 0x00020000);
+  constexpr uint32_t kOut = 0x80000000u;
+  auto wave_sync = [] {  // LDS writes of this wave are visible to its own later reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  };
+  for (int kc = k_begin; kc < k_end; kc += kSkinnyChunkK) {
+    u32x4 rows[16], fa[16], fb[16];
+    [[maybe_unused]] u32x4 a_hi[ES == 4 ? 16 : 1];
+    const int k_lane = kc + lane * 8;  // the lane's eight consecutive k of every row
+    const uint32_t k_in = k_lane < k_end ? 0u : kOut;
+    // fp32 rows are two 16-byte loads; they are rounded to bf16 only after every load of the chunk
+    // has been issued (a conversion between the loads would wait for its operand and hold back the
+    // loads behind it)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t off = i < g.M ? k_in + (uint32_t)(((int64_t)i * g.lda + k_lane) * ES) : kOut;
+      fa[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)off, 0, 0);
+      if constexpr (ES == 4) a_hi[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)(off + 16), 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      rows[i] = __builtin_amdgcn_raw_buffer_load_b128(
+          b_rsrc, (int)(i < b_rows ? k_in + (uint32_t)(((int64_t)i * g.ldb + k_lane) * 2) : kOut), 0, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    // activations: strip rows -> MFMA fragments (lane (ln, lg) holds row ln, k = 32 u + 8 lg ..)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      u32x4 v = fa[i];
+      if constexpr (ES == 4)
+        v = u32x4{cvt_pk_bf16(__uint_as_float(fa[i][0]), __uint_as_float(fa[i][1])),
+                  cvt_pk_bf16(__uint_as_float(fa[i][2]), __uint_as_float(fa[i][3])),
+                  cvt_pk_bf16(__uint_as_float(a_hi[i][0]), __uint_as_float(a_hi[i][1])),
+                  cvt_pk_bf16(__uint_as_float(a_hi[i][2]), __uint_as_float(a_hi[i][3]))};
+      *reinterpret_cast<u32x4*>(&wl[i * kSkinnyRow + lane * 8]) = v;
+    }
+    wave_sync();
+#pragma unroll
+    for (int u = 0; u < 16; ++u) fa[u] = *reinterpret_cast<const u32x4*>(&wl[ln * kSkinnyRow + 32 * u + 8 * lg]);
+    wave_sync();
+    __builtin_amdgcn_sched_barrier(0);
+    // weights, the same way, as they land
+#pragma unroll
+    for (int i = 0; i < 16; ++i) *reinterpret_cast<u32x4*>(&wl[i * kSkinnyRow + lane * 8]) = rows[i];
+    wave_sync();
+#pragma unroll
+    for (int u = 0; u < 16; ++u) fb[u] = *reinterpret_cast<const u32x4*>(&wl[ln * kSkinnyRow + 32 * u + 8 * lg]);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      union { u32x4 u4; bf16x8 v; } a, b;
+      a.u4 = fa[u], b.u4 = fb[u];
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc, 0, 0, 0);
+    }
+    wave_sync();
+  }
+  // sum the k ranges through LDS in a fixed order; wave 0 writes the tile
+  __syncthreads();
+  f32x4* red = reinterpret_cast<f32x4*>(skinny_lds);
+  red[wave * 64 + lane] = acc;
+  __syncthreads();
+  if (wave == 0) {  // register e of lane l is row 4 * (l / 16) + e, column l % 16
+    f32x4 sum = red[lane];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) sum += red[w * 64 + lane];
+    const int n = n0 + ln;
+    if (n < g.N) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int m = 4 * lg + e;
+        if (m >= g.M) continue;
+        if (g.mode == kProject) {
+          int side;
+          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(sum[e]);
+        } else {
+          store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
+        }
+      }
+    }
+  }
+}
+
+template <typename TA, typename TC>
+static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
+  const dim3 grid((a.N + 15) / 16);
+  auto go = [&](auto kern, int waves) {
+    const size_t lds = (size_t)waves * 16 * kSkinnyRow * sizeof(uint16_t);
+    static bool raised = false;  // more than 64 KiB of dynamic LDS needs the attribute, once per instance
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(waves * 64), lds, st, a);
+  };
+  // measured at the 7B shapes (K = 4096 and K = 1100 .. 2000): eight waves pay off above 2048 k
+  if (a.K > 2048) go(gemm_skinny16_kernel<TA, TC, 8>, 8);
+  else go(gemm_skinny16_kernel<TA, TC, 4>, 4);
+}
+
 // ---- post-RoPE compression (Section 5.1: RoPE, then the rotation R truncated to r_h columns) ----
 // One workgroup = 64 token rows of one head. The pre-RoPE rows are rotated pair-wise in fp32 while
 // they are staged (pairs (2i, 2i+1), angles from the caller's cos / sin tables), rounded to bf16 and
@@ -836,6 +965,11 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     const dim3 grid((n_max + 15) / 16, groups);
     if (c_f32) hipLaunchKernelGGL(absorb_query_small_kernel<float>, grid, dim3(64), 0, st, a);
     else hipLaunchKernelGGL(absorb_query_small_kernel<uint16_t>, grid, dim3(64), 0, st, a);
+  } else if (a.M <= 16 && (a.mode == kPlain || a.mode == kProject)) {
+    if (a_f32 && c_f32) launch_skinny16<float, float>(a, st);
+    else if (a_f32) launch_skinny16<float, uint16_t>(a, st);
+    else if (c_f32) launch_skinny16<uint16_t, float>(a, st);
+    else launch_skinny16<uint16_t, uint16_t>(a, st);
   } else if (a.M <= 64 && (a.mode == kPlain || a.mode == kProject)) {
     if (a_f32 && c_f32) launch_skinny<float, float>(a, st);
     else if (a_f32) launch_skinny<float, uint16_t>(a, st);

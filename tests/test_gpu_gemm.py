@@ -41,6 +41,12 @@ CASES = [
     (4, 1000, 64, [64, 16, 48, 32], [16, 64, 64, 48], 64),
     (3, 264, 32, [16, 32, 16], [32, 16, 16], 33),
     (32, 4096, 128, [64] * 32, [64] * 32, 48),
+    # at most 16 rows: the single-row-tile weight stream. K = 4096 (eight waves), K beyond one pass of
+    # eight 512-wide chunks, a ragged last column tile of the output projection, and a wide V' (K = 4096 fp32 rows)
+    (32, 4096, 128, [64] * 32, [64] * 32, 16),
+    (4, 4616, 64, [64, 16, 48, 32], [16, 64, 64, 48], 9),
+    (4, 1000, 64, [64, 16, 48, 32], [16, 64, 64, 48], 7),
+    (32, 512, 128, [16] * 32, [128] * 32, 12),
 ]
 
 
