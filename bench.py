@@ -155,8 +155,8 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
 
     def step(si=None):
         for l in range(L):
-            fdc.fdc_project_latent_kv(lay, l, x, tb, tp, A_cat_t[l], kc[l], vc[l])
-            fdc.fdc_absorb_query(lay, l, q, Bk[l], q_lat, fdc.FDC_F32)
+            # K'/V' of the new tokens and the absorbed queries: one launch at decode batch
+            fdc.fdc_project_and_absorb_query(lay, l, x, tb, tp, A_cat_t[l], kc[l], vc[l], q, Bk[l], q_lat, fdc.FDC_F32)
             if si is not None:
                 i = 2 * (si * L + l)
                 fdc.fdc_profile_decode_events(ev.ev[i], ev.ev[i + 1])
@@ -192,7 +192,9 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     torch.cuda.synchronize()
     attn_us_per_layer = (time.perf_counter() - t0) * 1e6 / (reps * L)
 
-    # the other calls of a step on layer 0, each alone (weight streams at decode batch: HBM-bound)
+    # the other calls of a step on layer 0, each alone, 30 calls back to back (weight streams at decode
+    # batch). A call costs the host about 10 us through ctypes, so these figures are upper bounds of the
+    # kernels' durations; the kernel trace under profiles/ has the durations themselves.
     def timed_us(fn, n=30):
         fn()
         torch.cuda.synchronize()
@@ -209,6 +211,8 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     small["project_latent_kv"] = {"us": us, "weight_GBps": (RK0 + RV0) * d * 2 / us / 1e3}
     us = timed_us(lambda: fdc.fdc_absorb_query(lay, 0, q, Bk[0], q_lat, fdc.FDC_F32))
     small["absorb_query"] = {"us": us, "weight_GBps": RK0 * dh * 2 / us / 1e3}
+    us = timed_us(lambda: fdc.fdc_project_and_absorb_query(lay, 0, x, tb, tp, A_cat_t[0], kc[0], vc[0], q, Bk[0], q_lat, fdc.FDC_F32))
+    small["project_and_absorb_query"] = {"us": us, "weight_GBps": ((RK0 + RV0) * d + RK0 * dh) * 2 / us / 1e3}
     us = timed_us(lambda: fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt[0], o_lat, fdc.FDC_F32, B, y, fdc.FDC_BF16))
     small["absorb_output_apply"] = {"us": us, "weight_GBps": d * RV0 * 2 / us / 1e3}
 

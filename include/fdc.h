@@ -227,6 +227,15 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
 fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const void* Bk,
                             void* q_lat, fdc_dtype q_lat_dtype, void* stream);
 
+/* fdc_project_latent_kv and fdc_absorb_query of the same T tokens in one call (the two products that
+ * start a decode layer, Section 2; they are independent of each other). Arguments, layouts and
+ * results are those of the two calls, bit for bit. With a bf16 layout and 1 <= T <= 16 both run in
+ * one kernel launch; otherwise the two calls are made in turn on `stream`. */
+fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const void* x, int T,
+                                        const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
+                                        void* k_cache, void* v_cache, const void* q, const void* Bk, void* q_lat,
+                                        fdc_dtype q_lat_dtype, void* stream);
+
 /* Post-RoPE compression of Q and K (Section 5.1; steps 5 and 6 of the design overview): RoPE, then
  * the common rotation R of the head truncated to its first r_h columns, (Q_p R_p)(K_p R_p)^T ~= Q_p K_p^T.
  * Attention, planning and the V path are unchanged; K' of the cache is written by

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = [
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
-    "fdc_rope_absorb_query", "fdc_rope_compress_keys",
+    "fdc_rope_absorb_query", "fdc_rope_compress_keys", "fdc_project_and_absorb_query",
 ]
 
 
@@ -85,6 +85,7 @@ def lib() -> C.CDLL:
         l.fdc_plan_destroy.restype = None
         l.fdc_project_latent_kv.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp]
         l.fdc_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, C.c_int, vp]
+        l.fdc_project_and_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
         l.fdc_latent_attn_decode.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
@@ -263,6 +264,14 @@ def fdc_absorb_query(layout: Layout, layer: int, q, Bk, q_lat, q_lat_dtype: int,
     T = int(q.shape[0])
     _check(lib().fdc_absorb_query(layout.handle, layer, _dev(q), T, _dev(Bk), _dev(q_lat), q_lat_dtype,
                                   _stream(stream)))
+
+
+def fdc_project_and_absorb_query(layout: Layout, layer: int, x, tok_batch, tok_pos, A_cat, k_cache, v_cache,
+                                 q, Bk, q_lat, q_lat_dtype: int, stream=None) -> None:
+    T = int(x.shape[0])
+    _check(lib().fdc_project_and_absorb_query(layout.handle, layer, _dev(x), T, _dev(tok_batch), _dev(tok_pos),
+                                              _dev(A_cat), _dev(k_cache), _dev(v_cache), _dev(q), _dev(Bk),
+                                              _dev(q_lat), q_lat_dtype, _stream(stream)))
 
 
 def fdc_latent_attn_decode(layout: Layout, plan: Plan, q_lat, k_cache, v_cache, scale: float, o_lat,

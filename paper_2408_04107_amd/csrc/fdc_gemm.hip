@@ -301,11 +301,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // 16 latent columns) keeps the whole B operand of its tile in registers and walks the row tiles;
 // with a few dozen rows this is a launch of a few hundred independent waves and no LDS.
 template <typename TC>
-__global__ __launch_bounds__(64) void absorb_query_small_kernel(const GemmArgs g) {
-  const Group gr = group_of(g, blockIdx.y);
-  const int n0 = blockIdx.x * 16;
+__device__ __forceinline__ void absorb_query_small_body(const GemmArgs& g, const int col_tile, const int head,
+                                                        const int lane) {
+  const Group gr = group_of(g, head);
+  const int n0 = col_tile * 16;
   if (n0 >= gr.N) return;
-  const int lane = threadIdx.x, ln = lane % 16, lg = lane / 16;
+  const int ln = lane % 16, lg = lane / 16;
   const uint16_t* A = static_cast<const uint16_t*>(g.A) + gr.a_off;
   const uint16_t* B = static_cast<const uint16_t*>(g.B) + gr.b_off;
   union Fr { u32x4 u; bf16x8 v; };
@@ -332,6 +333,11 @@ __global__ __launch_bounds__(64) void absorb_query_small_kernel(const GemmArgs g
       if (m < g.M) store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n0 + ln, acc[e]);
     }
   }
+}
+
+template <typename TC>
+__global__ __launch_bounds__(64) void absorb_query_small_kernel(const GemmArgs g) {
+  absorb_query_small_body<TC>(g, blockIdx.x, blockIdx.y, threadIdx.x);
 }
 
 // ---- bf16 MFMA kernel for the large products (prefill: M = tokens of the batch) ----------------
@@ -750,11 +756,10 @@ static void launch_skinny(const GemmArgs& a, hipStream_t st) {
 // HBM; fp32 activations are rounded to bf16 at that point, (c) the sixteen LDS fragment reads of
 // the weights are issued together instead of one wait per MFMA. WAVES waves split K.
 template <typename TA, typename TC, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void gemm_skinny16_kernel(const GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t skinny_lds[];
+__device__ __forceinline__ void skinny16_body(const GemmArgs& g, const int col_tile, uint16_t* skinny_lds) {
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int n0 = blockIdx.x * 16;
+  const int n0 = col_tile * 16;
   const uint16_t* B = static_cast<const uint16_t*>(g.B);
   uint16_t* wl = skinny_lds + wave * 16 * kSkinnyRow;
   const int k_per_wave = ((g.K + WAVES - 1) / WAVES + 63) / 64 * 64;
@@ -848,6 +853,30 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_skinny16_kernel(const GemmArg
         }
       }
     }
+  }
+}
+
+template <typename TA, typename TC, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_skinny16_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t skinny_lds[];
+  skinny16_body<TA, TC, WAVES>(g, blockIdx.x, skinny_lds);
+}
+
+// The two calls that start a decode layer, K'/V' of the new tokens and the absorbed queries, do not
+// depend on each other, and at decode batch each is a launch of a few microseconds that leaves
+// compute units idle (the projection has N / 16 workgroups, fewer than compute units at the 7B
+// shape). One launch runs both: the first n_proj workgroups are the projection's, the wavefronts of
+// the rest each take one (query head, 16 latent columns) job of the query absorption.
+template <typename TC, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void decode_prologue_kernel(const GemmArgs proj, const GemmArgs absq,
+                                                                      const int n_proj, const int absq_col_tiles) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t skinny_lds[];
+  if ((int)blockIdx.x < n_proj) {
+    skinny16_body<uint16_t, uint16_t, WAVES>(proj, blockIdx.x, skinny_lds);
+  } else {
+    const int job = ((int)blockIdx.x - n_proj) * WAVES + (int)(threadIdx.x / 64);
+    const int head = job / absq_col_tiles;
+    if (head < absq.H * absq.G) absorb_query_small_body<TC>(absq, job % absq_col_tiles, head, threadIdx.x % 64);
   }
 }
 
@@ -1052,6 +1081,59 @@ fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int
   int n_max = 0;
   for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rk[(size_t)layer * lay->H + h]);
   return launch(lay, a, lay->H * lay->G, n_max, false, q_lat_dtype == FDC_F32, static_cast<hipStream_t>(stream));
+}
+
+fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const void* x, int T,
+                                        const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
+                                        void* k_cache, void* v_cache, const void* q, const void* Bk, void* q_lat,
+                                        fdc_dtype q_lat_dtype, void* stream) {
+  // one launch only where both halves take their few-row kernels; otherwise the two calls in turn
+  if (!lay || lay->dtype != FDC_BF16 || T < 1 || T > 16 || layer < 0 || layer >= lay->L || !x || !tok_batch ||
+      !tok_pos || !A_cat_t || !v_cache || !q || !Bk || !q_lat || !aligned16(x) || !aligned16(A_cat_t) ||
+      (k_cache && !aligned16(k_cache)) || !aligned16(v_cache) || !aligned16(q) || !aligned16(Bk) ||
+      !aligned16(q_lat) || (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) || lay->H > kMaxHeads) {
+    fdc_status s = fdc_project_latent_kv(lay, layer, x, T, tok_batch, tok_pos, A_cat_t, k_cache, v_cache, stream);
+    if (s != FDC_OK) return s;
+    return fdc_absorb_query(lay, layer, q, T, Bk, q_lat, q_lat_dtype, stream);
+  }
+  GemmArgs p{};
+  fill_tables(p, lay, layer);
+  p.A = x, p.B = A_cat_t, p.C = k_cache, p.C2 = v_cache;
+  p.lda = lay->d_model, p.ldb = lay->d_model, p.ldc = 0;
+  p.v_only = k_cache == nullptr;
+  p.M = T, p.N = p.v_only ? p.RV : p.RK + p.RV, p.K = lay->d_model;
+  p.mode = kProject;
+  p.tok_batch = tok_batch, p.tok_pos = tok_pos;
+  GemmArgs a{};
+  fill_tables(a, lay, layer);
+  a.A = q, a.B = Bk, a.C = q_lat;
+  a.lda = (int64_t)lay->H * lay->G * lay->d_head, a.ldb = lay->d_head, a.ldc = (int64_t)lay->G * a.RK;
+  a.M = T, a.N = 0, a.K = lay->d_head;
+  a.mode = kAbsorbQuery;
+  int n_max = 0;
+  for (int h = 0; h < lay->H; ++h) n_max = std::max(n_max, lay->rk[(size_t)layer * lay->H + h]);
+  const int col_tiles = (n_max + 15) / 16, jobs = col_tiles * lay->H * lay->G;
+  const int n_proj = (p.N + 15) / 16;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  auto go = [&](auto kern, int waves) {
+    const size_t lds = (size_t)waves * 16 * kSkinnyRow * sizeof(uint16_t);
+    static bool raised = false;  // more than 64 KiB of dynamic LDS needs the attribute, once per instance
+    if (!raised) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      raised = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(n_proj + (jobs + waves - 1) / waves), dim3(waves * 64), lds, st, p, a, n_proj, col_tiles);
+  };
+  const bool f32 = q_lat_dtype == FDC_F32;
+  if (p.K > 2048) {
+    if (f32) go(decode_prologue_kernel<float, 8>, 8);
+    else go(decode_prologue_kernel<uint16_t, 8>, 8);
+  } else {
+    if (f32) go(decode_prologue_kernel<float, 4>, 4);
+    else go(decode_prologue_kernel<uint16_t, 4>, 4);
+  }
+  FDC_HIP_CHECK(hipGetLastError());
+  return FDC_OK;
 }
 
 fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const void* Bv, const void* Wo_t, void* Mt,

@@ -109,6 +109,39 @@ def test_absorb_query(case, dtype, q_lat_dtype):
     say(f"  max_abs={ma:.2e} rel_l2={rl:.2e}")
 
 
+@pytest.mark.parametrize("q_per_kv", [1, 4])
+@pytest.mark.parametrize("q_lat_dtype", [fdc.FDC_F32, fdc.FDC_BF16])
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_project_and_absorb_query_equals_the_two_calls(case, q_lat_dtype, q_per_kv):
+    """The one-launch form (T <= 16) and its two-call fallback (T > 16) write exactly what
+    fdc_project_latent_kv and fdc_absorb_query write; those two are checked against the oracle above."""
+    H, d, d_h, rk, rv, T = CASES[case]
+    if H * q_per_kv > 128:
+        pytest.skip("more query heads than the library supports")
+    say(f"project_and_absorb_query case {case}: H={H}x{q_per_kv} d={d} T={T} q_lat {q_lat_dtype}")
+    B, S = 3, 200
+    lay = fdc.Layout(1, H, d, d_h, [rk], [rv], B, S, fdc.FDC_BF16, q_per_kv=q_per_kv)
+    two, one = Cache(lay), Cache(lay)
+    g = gen.make_rng(200 + case)
+    x = dev(gen.hidden_states(T, d, g), torch.bfloat16)
+    A_cat_t = dev(g.standard_normal((two.RK + two.RV, d)) / math.sqrt(d), torch.bfloat16)
+    q = dev(g.standard_normal((T, H * q_per_kv, d_h)), torch.bfloat16)
+    Bk = dev(g.standard_normal((two.RK, d_h)) / math.sqrt(d_h), torch.bfloat16)
+    slots = g.permutation(B * S)[:T]
+    tb, tp = dev(slots // S, torch.int32), dev(slots % S, torch.int32)
+    qd = torch_dtype(q_lat_dtype)
+    q_two = torch.full((T, q_per_kv * two.RK), float("nan"), dtype=qd, device="cuda:0")
+    q_one = torch.full((T, q_per_kv * two.RK), float("nan"), dtype=qd, device="cuda:0")
+    fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A_cat_t, two.k, two.v)
+    fdc.fdc_absorb_query(lay, 0, q, Bk, q_two, q_lat_dtype)
+    fdc.fdc_project_and_absorb_query(lay, 0, x, tb, tp, A_cat_t, one.k, one.v, q, Bk, q_one, q_lat_dtype)
+    torch.cuda.synchronize()
+    assert not torch.isnan(q_one.float()).any()
+    assert torch.equal(one.k, two.k) and torch.equal(one.v, two.v)
+    assert torch.equal(q_one, q_two)
+    assert one.k.float().abs().sum() > 0 and one.v.float().abs().sum() > 0
+
+
 @pytest.mark.parametrize("dtype,io", [(fdc.FDC_BF16, (fdc.FDC_F32, fdc.FDC_F32)), (fdc.FDC_BF16, (fdc.FDC_BF16, fdc.FDC_BF16)),
                                       (fdc.FDC_BF16, (fdc.FDC_F32, fdc.FDC_BF16)), (fdc.FDC_F32, (fdc.FDC_F32, fdc.FDC_F32))])
 @pytest.mark.parametrize("case", range(len(CASES)))
