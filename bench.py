@@ -245,7 +245,10 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
                         "replan_all_layers_ms": replan_ms, "replan_threads": n_thr,
                         "replan_amortised_fraction_of_step": replan_ms / pp.granule / ms_per_step,
                         "n_workers": W,
-                        "tiles_per_layer": float(np.mean([tb_["n_items"] for tb_ in tabs]))},
+                        "tiles_per_layer": float(np.mean([tb_["n_items"] for tb_ in tabs])),
+                        "by_layer": {"tile_kernel_GBps": [int(v) for v in layer_gbps],
+                                     "tiles": [int(tb_["n_items"]) for tb_ in tabs],
+                                     "max_tiles_of_a_unit": [int(np.diff(tb_["unit_item_ptr"]).max()) for tb_ in tabs]}},
         "decode_other_calls_layer0": small,
         "step_algorithmic_bytes": step_bytes,
     }

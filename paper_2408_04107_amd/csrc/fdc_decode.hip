@@ -355,6 +355,58 @@ __global__ __launch_bounds__(32 * G) void decode_merge_kernel(const DecUnit* __r
   }
 }
 
+// The same merge for units cut into a few tiles (every decode step at ordinary context lengths):
+// one wavefront per unit, a lane owns two output columns, and the states are read sixteen at a time
+// (all loads of a batch in flight together), so a unit costs two dependent memory round trips (its
+// record, then its states) instead of three. States are combined in slot order.
+constexpr int kMergeBatch = 16;
+constexpr int kMergeWaves = 4;
+
+__global__ __launch_bounds__(kMergeWaves * 64) void decode_merge_wave_kernel(const DecUnit* __restrict__ units,
+                                                                             const float* __restrict__ partials,
+                                                                             float* __restrict__ o_lat, int n_units) {
+  const int unit = blockIdx.x * kMergeWaves + (int)(threadIdx.x / 64);
+  if (unit >= n_units) return;
+  const int lane = threadIdx.x % 64;
+  const DecUnit u = units[unit];
+  const int n = u.tile_end - u.tile_begin;
+  if (n == 1) return;  // the tile kernel wrote the normalised output itself
+  const bool on = 2 * lane < u.rv;
+  if (n == 0) {
+    if (on) *reinterpret_cast<float2*>(o_lat + u.o_elem + 2 * lane) = make_float2(0.f, 0.f);
+    return;
+  }
+  const float* base = partials + (int64_t)u.tile_begin * kPartialStride;
+  float M = -INFINITY, L = 0.f, ax = 0.f, ay = 0.f;
+  for (int j0 = 0; j0 < n; j0 += kMergeBatch) {
+    float2 ml[kMergeBatch], v[kMergeBatch];
+#pragma unroll
+    for (int t = 0; t < kMergeBatch; ++t) {
+      const float* pp = base + (int64_t)min(j0 + t, n - 1) * kPartialStride;  // past the end: a valid slot, weight 0
+      ml[t] = *reinterpret_cast<const float2*>(pp);
+      v[t] = *reinterpret_cast<const float2*>(pp + 4 + (on ? 2 * lane : 0));
+    }
+    float bm = M;
+#pragma unroll
+    for (int t = 0; t < kMergeBatch; ++t) {
+      if (j0 + t >= n) ml[t].x = -INFINITY;
+      bm = fmaxf(bm, ml[t].x);
+    }
+    const float w0 = __builtin_amdgcn_exp2f(M - bm);  // first batch: 2^(-inf) = 0
+    L *= w0, ax *= w0, ay *= w0;
+#pragma unroll
+    for (int t = 0; t < kMergeBatch; ++t) {
+      const float w = __builtin_amdgcn_exp2f(ml[t].x - bm);
+      L = fmaf(ml[t].y, w, L), ax = fmaf(v[t].x, w, ax), ay = fmaf(v[t].y, w, ay);
+    }
+    M = bm;
+  }
+  if (on) {
+    const float inv = 1.f / L;
+    *reinterpret_cast<float2*>(o_lat + u.o_elem + 2 * lane) = make_float2(ax * inv, ay * inv);
+  }
+}
+
 }  // namespace fdc
 
 using namespace fdc;
@@ -460,8 +512,8 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
     hipLaunchKernelGGL(decode_merge_kernel<32>, dim3(plan->n_merge_units), dim3(1024), 0, st, units, partials,
                        static_cast<float*>(o_lat));
   else
-    hipLaunchKernelGGL(decode_merge_kernel<4>, dim3(plan->n_merge_units), dim3(128), 0, st, units, partials,
-                       static_cast<float*>(o_lat));
+    hipLaunchKernelGGL(decode_merge_wave_kernel, dim3((plan->n_merge_units + kMergeWaves - 1) / kMergeWaves),
+                       dim3(kMergeWaves * 64), 0, st, units, partials, static_cast<float*>(o_lat), plan->n_merge_units);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }
