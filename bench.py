@@ -330,7 +330,7 @@ def run_prefill_workload(fdc, gen, iters=10):
     Mt = torch.empty(d, RV, dtype=bf, device=dev)
     y = torch.empty(T, d, dtype=bf, device=dev)
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap, pp.softmax_cost = fdc.fdc_suggest_workers(1), 1, 384, 384, 150
+    pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap, pp.softmax_cost = fdc.fdc_suggest_workers(1), 1, 512, 512, 150
     t0 = time.perf_counter()
     plan = fdc.fdc_plan_prefill(lay, 0, [S] * B, [S] * B, pp)
     plan_ms = (time.perf_counter() - t0) * 1e3

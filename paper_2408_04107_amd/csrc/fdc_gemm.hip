@@ -8,12 +8,32 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
+#include <utility>
+#include <vector>
 
 #include "fdc_internal.h"
 
 namespace fdc {
 
 constexpr int kMaxHeads = 128;
+
+// A launch with more than 64 KiB of dynamic LDS needs the kernel's limit raised first, once per
+// kernel and device. Kernels of one signature share a function-pointer type, so the record is
+// keyed by the pointer's value, not by a per-template static.
+static hipError_t ensure_dynamic_lds(const void* kern, size_t bytes) {
+  static std::mutex mu;
+  static std::vector<std::pair<const void*, int>> done;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& d : done)
+    if (d.first == kern && d.second == dev) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done.emplace_back(kern, dev);
+  return e;
+}
 
 enum GemmMode { kPlain = 0, kProject = 1, kAbsorbQuery = 2, kFold = 3 };
 
@@ -730,13 +750,7 @@ static void launch_skinny(const GemmArgs& a, hipStream_t st) {
   const dim3 grid((a.N + 15) / 16), block(kSkinnyWaves * 64);
   const int mt = (a.M + 15) / 16;
   auto go = [&](auto kern) {
-    // more than 64 KiB of dynamic LDS needs the attribute, once per kernel instance
-    static bool raised = false;
-    if (!raised) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kSkinnyLdsBytes);
-      raised = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kSkinnyLdsBytes) != hipSuccess) return;
     hipLaunchKernelGGL(kern, grid, block, kSkinnyLdsBytes, st, a);
   };
   if (mt == 1) go(gemm_skinny_kernel<TA, TC, 1>);
@@ -885,11 +899,7 @@ static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
   const dim3 grid((a.N + 15) / 16);
   auto go = [&](auto kern, int waves) {
     const size_t lds = (size_t)waves * 16 * kSkinnyRow * sizeof(uint16_t);
-    static bool raised = false;  // more than 64 KiB of dynamic LDS needs the attribute, once per instance
-    if (!raised) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      raised = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds) != hipSuccess) return;
     hipLaunchKernelGGL(kern, grid, dim3(waves * 64), lds, st, a);
   };
   // measured at the 7B shapes (K = 4096 and K = 1100 .. 2000): eight waves pay off above 2048 k
@@ -1117,11 +1127,7 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
   hipStream_t st = static_cast<hipStream_t>(stream);
   auto go = [&](auto kern, int waves) {
     const size_t lds = (size_t)waves * 16 * kSkinnyRow * sizeof(uint16_t);
-    static bool raised = false;  // more than 64 KiB of dynamic LDS needs the attribute, once per instance
-    if (!raised) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      raised = true;
-    }
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds) != hipSuccess) return;
     hipLaunchKernelGGL(kern, dim3(n_proj + (jobs + waves - 1) / waves), dim3(waves * 64), lds, st, p, a, n_proj, col_tiles);
   };
   const bool f32 = q_lat_dtype == FDC_F32;

@@ -128,5 +128,5 @@ def test_prefill_config5_size_sampled_rows():
         return fixed + [int(x) for x in g.integers(0, S, 6)]
 
     ma, rl, n = run_prefill(r, r, [S] * wl.batch, [S] * wl.batch, W, cost_mode=1, device_fill=True,
-                            sample_rows=rows, seed=12, br_base=384, br_cap=384, softmax_cost=150)   # bench.py's launch configuration
+                            sample_rows=rows, seed=12, br_base=512, br_cap=512, softmax_cost=150)   # bench.py's launch configuration
     say(f"  tasks={n} max_abs={ma:.2e} rel_l2={rl:.2e}")

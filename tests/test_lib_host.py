@@ -113,7 +113,7 @@ def test_prefill_plan_bit_exact(mode):
     r = wl.ranks()[0].tolist()
     _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 256, mode)
     _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 512, mode, base=128, cap=128, sc=400)
-    _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 512, mode, base=384, cap=384, sc=150)  # bench.py's
+    _prefill_case(r, r, [wl.context] * wl.batch, [wl.context] * wl.batch, 256, mode, base=512, cap=512, sc=150)  # bench.py's
     g = gen.make_rng(78)
     for _ in range(10):
         H, B = int(g.integers(1, 6)), int(g.integers(1, 4))
