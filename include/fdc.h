@@ -161,7 +161,7 @@ fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const in
  * P must be a multiple of params->granule. The schedule is that of fdc_plan_decode for the same
  * seq_len; every piece is then cut at the page boundaries it contains (item_lo / item_hi are token
  * positions in the sequence). fdc_latent_attn_decode takes the plan unchanged; q_lat and o_lat are
- * indexed by sequence. Prefill attention needs the dense layout. */
+ * indexed by sequence. */
 fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
                                  const int32_t* block_table, int max_pages,
                                  const fdc_plan_params* params, fdc_plan** out);
@@ -170,6 +170,15 @@ fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, co
  * q_len[b] <= kv_len[b] <= max_seq. Query rows of all sequences are stacked b-major: T = sum q_len. */
 fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
                             const int32_t* kv_len, const fdc_plan_params* params, fdc_plan** out);
+
+/* Prefill plan over a PAGED cache: the layout describes the pages and block_table maps them to
+ * sequences exactly as for fdc_plan_decode_paged; kv_len[b] <= P * max_pages, and P must be a
+ * multiple of 128 (the kernel stages K'/V' 128 tokens at a time and a block never straddles pages).
+ * The schedule is that of fdc_plan_prefill for the same lengths (tasks are blocks of query rows;
+ * pages do not cut them). fdc_latent_attn_prefill takes the plan unchanged. */
+fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
+                                  const int32_t* kv_len, const int32_t* block_table, int max_pages,
+                                  const fdc_plan_params* params, fdc_plan** out);
 
 /* Host view of a plan's tables (pointers stay valid until fdc_plan_destroy). An item is a decode
  * tile (lo, hi = token range) or a prefill task (lo, hi = query-row range). */

@@ -21,7 +21,7 @@ FDC_FOLD, FDC_APPLY = 0, 1
 
 EXPORTED_SYMBOLS = [
     "fdc_last_error", "fdc_layout_create", "fdc_layout_create_gqa", "fdc_layout_tables", "fdc_layout_destroy",
-    "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_decode_paged", "fdc_plan_prefill",
+    "fdc_plan_params_default", "fdc_suggest_workers", "fdc_plan_decode", "fdc_plan_decode_paged", "fdc_plan_prefill", "fdc_plan_prefill_paged",
     "fdc_plan_export", "fdc_plan_workspace_bytes", "fdc_plan_upload", "fdc_plan_destroy",
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
@@ -77,6 +77,8 @@ def lib() -> C.CDLL:
         l.fdc_plan_decode_paged.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, C.c_int, C.POINTER(PlanParams),
                                             C.POINTER(vp)]
         l.fdc_plan_prefill.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, C.POINTER(PlanParams), C.POINTER(vp)]
+        l.fdc_plan_prefill_paged.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, i32p, C.c_int, C.POINTER(PlanParams),
+                                             C.POINTER(vp)]
         l.fdc_plan_export.argtypes = [vp, C.POINTER(PlanTables)]
         l.fdc_plan_workspace_bytes.argtypes = [vp]
         l.fdc_plan_workspace_bytes.restype = C.c_size_t
@@ -245,6 +247,19 @@ def fdc_plan_prefill(layout: Layout, layer: int, q_len: Sequence[int], kv_len: S
         raise ValueError("q_len and kv_len must have the same length")
     h = C.c_void_p()
     _check(lib().fdc_plan_prefill(layout.handle, layer, int(q.size), _p32(q), _p32(k), C.byref(params), C.byref(h)))
+    return Plan(h, layout)
+
+
+def fdc_plan_prefill_paged(layout: Layout, layer: int, q_len: Sequence[int], kv_len: Sequence[int], block_table,
+                           params: PlanParams) -> Plan:
+    """block_table: int [batch, max_pages]; the layout's batch rows are the pages, max_seq the page size."""
+    q, k = _i32(q_len), _i32(kv_len)
+    bt = np.ascontiguousarray(np.asarray(block_table, dtype=np.int32))
+    if q.size != k.size or bt.ndim != 2 or bt.shape[0] != q.size:
+        raise ValueError("q_len and kv_len must have the same length and block_table be [batch, max_pages]")
+    h = C.c_void_p()
+    _check(lib().fdc_plan_prefill_paged(layout.handle, layer, int(q.size), _p32(q), _p32(k), _p32(bt.reshape(-1)),
+                                        int(bt.shape[1]), C.byref(params), C.byref(h)))
     return Plan(h, layout)
 
 

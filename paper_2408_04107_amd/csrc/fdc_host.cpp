@@ -407,18 +407,45 @@ fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, co
   return plan_decode_impl("fdc_plan_decode_paged", lay, layer, batch, seq_len, block_table, max_pages, pr, out);
 }
 
-fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
-                            const int32_t* kv_len, const fdc_plan_params* pr, fdc_plan** out) {
-  fdc_status st = check_plan_args("fdc_plan_prefill", lay, layer, batch, q_len, pr, out);
-  if (st != FDC_OK) return st;
-  if (!kv_len) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: kv_len is NULL");
+}  // extern "C"
+
+// Prefill planning. block_table == nullptr: the dense layout. Otherwise the cache is paged as in
+// plan_decode_impl; the schedule does not depend on it (a task is a block of query rows), only the
+// addresses the kernel derives per staged block do.
+static fdc_status plan_prefill_impl(const char* fn, const fdc_layout* lay, int layer, int batch,
+                                    const int32_t* q_len, const int32_t* kv_len, const int32_t* block_table,
+                                    int max_pages, const fdc_plan_params* pr, fdc_plan** out) {
+  if (!out) FDC_FAIL(FDC_INVALID_ARG, "%s: out is NULL", fn);
+  *out = nullptr;
+  if (!lay || !q_len || !kv_len || !pr) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
+  if (layer < 0 || layer >= lay->L) FDC_FAIL(FDC_BAD_SHAPE, "%s: layer %d outside [0, %d)", fn, layer, lay->L);
+  const bool paged = block_table != nullptr;
+  if (batch <= 0 || (!paged && batch > lay->max_batch))
+    FDC_FAIL(FDC_BAD_SHAPE, "%s: batch %d outside [1, %d]", fn, batch, lay->max_batch);
+  if (pr->n_workers <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: n_workers must be positive", fn);
+  if (pr->softmax_cost <= 0) FDC_FAIL(FDC_INVALID_ARG, "%s: softmax_cost must be positive", fn);
   if (pr->br_base <= 0 || pr->br_cap < 16 || pr->br_cap % 16 != 0)
-    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: br_base must be positive and br_cap a positive multiple of 16");
-  if (pr->cost_mode != 0 && pr->cost_mode != 1) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: cost_mode %d", pr->cost_mode);
-  for (int b = 0; b < batch; ++b)
-    if (q_len[b] < 0 || kv_len[b] < q_len[b] || kv_len[b] > lay->max_seq)
-      FDC_FAIL(FDC_BAD_SHAPE, "fdc_plan_prefill: need 0 <= q_len[%d]=%d <= kv_len=%d <= %d", b, q_len[b], kv_len[b],
-               lay->max_seq);
+    FDC_FAIL(FDC_INVALID_ARG, "%s: br_base must be positive and br_cap a positive multiple of 16", fn);
+  if (pr->cost_mode != 0 && pr->cost_mode != 1) FDC_FAIL(FDC_INVALID_ARG, "%s: cost_mode %d", fn, pr->cost_mode);
+  const int64_t P = paged ? lay->max_seq : 0;
+  if (paged) {
+    if (max_pages <= 0) FDC_FAIL(FDC_BAD_SHAPE, "%s: max_pages must be positive", fn);
+    if (P % kPrefillBlockTokens != 0)
+      FDC_FAIL(FDC_INVALID_ARG, "%s: the page size %d must be a multiple of %d tokens", fn, (int)P, kPrefillBlockTokens);
+  }
+  const int64_t seq_cap = paged ? P * max_pages : lay->max_seq;
+  for (int b = 0; b < batch; ++b) {
+    if (q_len[b] < 0 || kv_len[b] < q_len[b] || kv_len[b] > seq_cap)
+      FDC_FAIL(FDC_BAD_SHAPE, "%s: need 0 <= q_len[%d]=%d <= kv_len=%d <= %lld", fn, b, q_len[b], kv_len[b],
+               (long long)seq_cap);
+    if (paged)
+      for (int64_t i = 0; i * P < kv_len[b]; ++i) {
+        const int32_t pg = block_table[(size_t)b * max_pages + i];
+        if (pg < 0 || pg >= lay->max_batch)
+          FDC_FAIL(FDC_BAD_SHAPE, "%s: block_table[%d][%lld] = %d outside [0, %d)", fn, b, (long long)i, pg,
+                   lay->max_batch);
+      }
+  }
 
   // With grouped queries the planner's heads are the QUERY heads: query head hq has the ranks and
   // the cache blocks of key/value head hq / g and its own columns in q_lat and o_lat.
@@ -430,7 +457,7 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
   for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost, d_max = std::max(d_max, d_sum[h]);
 
   fdc_plan* p = new (std::nothrow) fdc_plan();
-  if (!p) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill: out of host memory");
+  if (!p) FDC_FAIL(FDC_INVALID_ARG, "%s: out of host memory", fn);
   p->kind = 1, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
   p->G = g;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
@@ -522,8 +549,9 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
     PreTask& d = pt[i];
     std::memset(&d, 0, sizeof(d));
     const int hk = t.h / g, j = t.h % g;
-    d.k_elem = (int64_t)t.b * lay->max_seq * p->RK + koff[hk];
-    d.v_elem = (int64_t)t.b * lay->max_seq * p->RV + voff[hk];
+    d.k_elem = (paged ? 0 : (int64_t)t.b * lay->max_seq * p->RK) + koff[hk];
+    d.v_elem = (paged ? 0 : (int64_t)t.b * lay->max_seq * p->RV) + voff[hk];
+    d.page_tokens = (int32_t)P, d.page_first = paged ? t.b * max_pages : 0;
     d.q_elem = (row0[t.b] + t.q0) * g * p->RK + g * koff_r[hk] + j * rk[t.h];
     d.o_elem = (row0[t.b] + t.q0) * g * p->RV + g * voff_r[hk] + j * rv[t.h];
     d.rows = t.q1 - t.q0;
@@ -536,11 +564,29 @@ fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const i
   p->off_units = p->off_items;
   p->off_worker_ptr = append_aligned(p->image, p->worker_ptr.data(), p->worker_ptr.size());
   p->off_worker_items = append_aligned(p->image, p->worker_items.data(), p->worker_items.size());
+  if (paged) p->off_pages = append_aligned(p->image, block_table, (size_t)batch * max_pages);
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = 0;
   p->workspace_bytes = p->off_partials + 256;
   *out = p;
   return FDC_OK;
+}
+
+extern "C" {
+
+fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
+                            const int32_t* kv_len, const fdc_plan_params* pr, fdc_plan** out) {
+  return plan_prefill_impl("fdc_plan_prefill", lay, layer, batch, q_len, kv_len, nullptr, 0, pr, out);
+}
+
+fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
+                                  const int32_t* kv_len, const int32_t* block_table, int max_pages,
+                                  const fdc_plan_params* pr, fdc_plan** out) {
+  if (!block_table) {
+    if (out) *out = nullptr;
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill_paged: block_table is NULL");
+  }
+  return plan_prefill_impl("fdc_plan_prefill_paged", lay, layer, batch, q_len, kv_len, block_table, max_pages, pr, out);
 }
 
 fdc_status fdc_plan_export(const fdc_plan* p, fdc_plan_tables* o) {

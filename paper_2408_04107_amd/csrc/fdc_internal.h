@@ -66,6 +66,9 @@ struct DecUnit {
   int32_t rv;
 };
 
+// Tokens of a K'/V' block the prefill kernel stages at a time; a page holds a whole number of them.
+constexpr int kPrefillBlockTokens = 128;
+
 // Partial state of a tile: m, l, 2 pad floats, acc[rv <= 128].
 constexpr int kPartialStride = 132;
 
@@ -81,7 +84,10 @@ struct PreTask {
   int32_t rk_rv;     // rk | rv << 16
   int32_t ldq;       // RK (row stride of q_lat)
   int32_t ldo;       // RV
-  int32_t pad[2];
+  int32_t page_tokens;  // 0: k_elem / v_elem address the unit's rows [0, kv_len) directly. P > 0: the cache
+                        // is paged; tokens i*P .. of the sequence sit in page page_table[page_first + i], and
+                        // k_elem / v_elem are the head's offsets inside a page
+  int32_t page_first;   // index of the sequence's first entry in the plan's page table
 };
 static_assert(sizeof(PreTask) == 64, "PreTask layout");
 
@@ -133,6 +139,7 @@ struct fdc_plan {
   // device image: packed tables, copied verbatim by fdc_plan_upload
   std::vector<unsigned char> image;
   size_t off_items, off_units, off_worker_ptr, off_worker_items;  // byte offsets inside image
+  size_t off_pages = 0;        // prefill over a paged cache: int32 page table [batch * max_pages], inside image
   size_t off_partials, partial_bytes;                             // decode only, after the image
   size_t workspace_bytes;
 };

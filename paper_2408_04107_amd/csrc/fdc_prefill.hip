@@ -50,6 +50,7 @@ constexpr int QT = FDC_PREFILL_QT;       // 16-row MFMA tiles of queries per wav
 constexpr int BC = 64;                   // tokens per score tile set (one softmax update)
 constexpr int NH = FDC_PREFILL_HALVES;   // score tile sets per staged block
 constexpr int BCB = BC * NH;             // tokens per staged K'/V' block (one barrier)
+static_assert(BCB == kPrefillBlockTokens, "a page of a paged cache holds whole staged blocks");
 constexpr int kRowsPerWave = 16 * QT;
 constexpr int kRowsPerPass = FDC_PREFILL_ROWS;
 constexpr int kPreThreads = 64 * (kRowsPerPass / kRowsPerWave);
@@ -95,7 +96,8 @@ union Frag {
 __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* __restrict__ q_lat,
                                              const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
                                              float scale_log2, int causal, uint16_t* __restrict__ o_lat,
-                                             uint16_t* lds) {
+                                             const int32_t* __restrict__ page_table, int64_t page_stride_k,
+                                             int64_t page_stride_v, uint16_t* lds) {
   const int rk = t.rk_rv & 0xffff, rv = t.rk_rv >> 16;
   const int rk32 = (rk + 31) / 32, rv16 = rv / 16;
   const int RKP = rk32 * 32;  // rank of the K' rows in LDS, padded with zeros
@@ -178,10 +180,22 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     // register staging of the next block
     u32x4 kst[kSweeps], vst[kSweeps];
     auto fetch = [&](int c0) {  // rows past kv_len and lanes without a row read zeros through the range check
+      __amdgpu_buffer_rsrc_t kr = k_rsrc, vr = v_rsrc;
+      int rel = c0;
+      if (t.page_tokens > 0) {
+        // paged cache: the block lies inside one page (pages hold whole blocks); its rows are that
+        // page's rows [rel, ..) of this head, valid up to the end of the page or of the sequence
+        const int pi = c0 / t.page_tokens, start = pi * t.page_tokens;
+        const int64_t pg = page_table[t.page_first + pi];
+        const int rows = min(t.page_tokens, t.kv_len - start);
+        kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kbase + pg * page_stride_k), 0, rows * rk * 2, 0x00020000);
+        vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vbase + pg * page_stride_v), 0, rows * rv * 2, 0x00020000);
+        rel = c0 - start;
+      }
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(k_goff[i] + (uint32_t)(c0 * rk * 2)), 0, 0);
-        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(v_goff[i] + (uint32_t)(c0 * rv * 2)), 0, 0);
+        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, (int)(k_goff[i] + (uint32_t)(rel * rk * 2)), 0, 0);
+        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)(v_goff[i] + (uint32_t)(rel * rv * 2)), 0, 0);
       }
     };
     auto stage = [&](int buf) {
@@ -337,13 +351,14 @@ __global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(kPr
     const PreTask* __restrict__ tasks, const int32_t* __restrict__ worker_ptr,
     const int32_t* __restrict__ worker_items, const uint16_t* __restrict__ q_lat,
     const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, int causal,
-    uint16_t* __restrict__ o_lat) {
+    uint16_t* __restrict__ o_lat, const int32_t* __restrict__ page_table, int64_t page_stride_k,
+    int64_t page_stride_v) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStageElems];
   const int w = blockIdx.x;
   const int i0 = worker_ptr[w], i1 = worker_ptr[w + 1];
   for (int it = i0; it < i1; ++it) {
     const PreTask t = tasks[worker_items[it]];
-    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, lds);
+    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, page_table, page_stride_k, page_stride_v, lds);
   }
 }
 
@@ -381,7 +396,8 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
                      reinterpret_cast<const int32_t*>(ws + plan->off_worker_items),
                      static_cast<const uint16_t*>(q_lat), static_cast<const uint16_t*>(k_cache),
                      static_cast<const uint16_t*>(v_cache), scale * kLog2eP, causal,
-                     static_cast<uint16_t*>(o_lat));
+                     static_cast<uint16_t*>(o_lat), reinterpret_cast<const int32_t*>(ws + plan->off_pages),
+                     (int64_t)lay->max_seq * plan->RK, (int64_t)lay->max_seq * plan->RV);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

@@ -186,6 +186,43 @@ def test_paged_decode_plan_bit_exact():
         fdc.fdc_plan_decode_paged(lay, 0, [100], [[0, 1]], pp)
 
 
+def test_paged_prefill_plan_bit_exact():
+    """Pages do not cut query blocks: the paged prefill plan is the oracle's plan for the same lengths."""
+    rk, rv = [16, 64, 32, 128], [32, 64, 16, 128]
+    g = gen.make_rng(6)
+    for P, W, mode in [(128, 37, "causal"), (256, 9, "paper"), (512, 300, "causal")]:
+        kv = [0, 5, 700, 1300, 256, 129]
+        q = [0, 5, 300, 1300, 1, 129]
+        max_pages = max(1, max(-(-x // P) for x in kv))
+        n_pages = sum(-(-x // P) for x in kv) + 3
+        perm = g.permutation(n_pages)
+        bt = np.full((len(kv), max_pages), -7, dtype=np.int32)       # entries past a sequence's end are never read
+        k = 0
+        for b, S in enumerate(kv):
+            for i in range(-(-S // P)):
+                bt[b, i] = perm[k]
+                k += 1
+        lay = fdc.Layout(1, len(rk), 256, 128, [rk], [rv], n_pages, P, fdc.FDC_BF16)
+        pp = fdc.fdc_plan_params_default()
+        pp.n_workers, pp.cost_mode, pp.br_base, pp.br_cap = W, {"paper": 0, "causal": 1}[mode], 64, 256
+        got = fdc.fdc_plan_prefill_paged(lay, 0, q, kv, bt, pp).export()
+        ref = op.plan_prefill(q, kv, rk, rv, W, br_base=64, br_cap=256, cost_mode=mode)
+        for a, b_ in PRE_PAIRS:
+            assert got[a].dtype == ref[b_].dtype and np.array_equal(got[a], ref[b_]), (a, P, W, mode)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 4
+    lay = fdc.Layout(1, 4, 256, 128, [rk], [rv], 4, 128, fdc.FDC_BF16)
+    with pytest.raises(fdc.FdcError):          # page id outside the layout
+        fdc.fdc_plan_prefill_paged(lay, 0, [10], [100], [[4, 0]], pp)
+    with pytest.raises(fdc.FdcError):          # sequence longer than its block table
+        fdc.fdc_plan_prefill_paged(lay, 0, [10], [257], [[0, 1]], pp)
+    with pytest.raises(fdc.FdcError):          # more queries than keys
+        fdc.fdc_plan_prefill_paged(lay, 0, [101], [100], [[0, 1]], pp)
+    lay64 = fdc.Layout(1, 4, 256, 128, [rk], [rv], 4, 64, fdc.FDC_BF16)
+    with pytest.raises(fdc.FdcError):          # a 64-token page would split the kernel's 128-token blocks
+        fdc.fdc_plan_prefill_paged(lay64, 0, [10], [100], [[0, 1]], pp)
+
+
 def test_select_ranks_bit_exact_with_oracle():
     """Eq. (1): the library's rank choice equals the oracle's on planted, random and tie-prone spectra."""
     from oracle import rank_select as ors
