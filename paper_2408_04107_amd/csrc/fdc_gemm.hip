@@ -622,7 +622,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 constexpr int kSkinnyWaves = 8;
 
 constexpr int kSkinnyChunkK = 512;             // k covered by one wave-wide 16-byte-per-lane load of a row
-constexpr int kSkinnyRow = kSkinnyChunkK + 8;  // padded LDS row (elements)
+// Padded LDS row (elements): 66 chunks of 16 bytes. The MFMA fragment read (lane (ln, lg): row ln,
+// chunk lg) is free of bank conflicts when the row stride is 2 (mod 16) chunks, because the LDS
+// serves eight lanes of lane row lg and eight of lane row lg + 1 in one pass (measured); the stride
+// of 1 (mod 16) that suits lane-row passes gave a two-way conflict on every read.
+constexpr int kSkinnyRow = kSkinnyChunkK + 16;
 
 template <typename TA, typename TC, int MT>
 __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const GemmArgs g) {
@@ -743,7 +747,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const Ge
   }
 }
 
-constexpr size_t kSkinnyLdsBytes = (size_t)kSkinnyWaves * 16 * kSkinnyRow * sizeof(uint16_t);  // 133120
+constexpr size_t kSkinnyLdsBytes = (size_t)kSkinnyWaves * 16 * kSkinnyRow * sizeof(uint16_t);  // 135168
 
 template <typename TA, typename TC>
 static void launch_skinny(const GemmArgs& a, hipStream_t st) {
@@ -913,6 +917,8 @@ static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
 // multiplied with the head's R_t rows (r_h x d_head, K = d_head <= 128, so the whole product is one
 // LDS stage and 4 k-steps of v_mfma_f32_16x16x32_bf16). Queries go to q_lat, keys into the K' cache.
 constexpr int kRopeRows = 64;
+// 17 chunks per row: the fragment reads take a two-way bank conflict (see kSkinnyRow), but with 18
+// chunks only two workgroups instead of three fit a compute unit and the kernel was 30 % slower.
 constexpr int kRopeLdsRow = 128 + 8;
 
 template <typename TC, bool KEYS>
