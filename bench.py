@@ -456,6 +456,51 @@ def run_gqa_decode_workload(fdc, gen, iters=20):
             "call_us": call_us, "call_GBps": cache_bytes / call_us / 1e3}
 
 
+def run_fp8_decode_workload(fdc, gen, wl, iters=12):
+    """Decode attention of layer 0 of the decode workload with the cache stored as E4M3 codes
+    (FDC_FP8 layout): the same tokens and ranks at half the cache bytes."""
+    import torch
+    dev = "cuda:0"
+    ranks = wl.ranks()[:1]
+    H, B, S, dh = wl.n_heads, wl.batch, wl.context, wl.d_head
+    lay = fdc.Layout(1, H, wl.d_model, dh, ranks, ranks, B, S, fdc.FDC_FP8)
+    t = lay.tables()
+    RK = int(t["koff_r"][0, -1])
+    gt = torch.Generator(device=dev).manual_seed(9)
+    n = int(t["k_bytes"][0])
+    copies = 3   # rotate cache copies so that no launch finds its bytes in the last-level cache
+    # random finite codes: any byte but the two NaN patterns
+    mk = lambda: torch.randint(0, 0x7F, (n,), generator=gt, device=dev, dtype=torch.uint8) | \
+        (torch.randint(0, 2, (n,), generator=gt, device=dev, dtype=torch.uint8) << 7)
+    kcs, vcs = [mk() for _ in range(copies)], [mk() for _ in range(copies)]
+    q_lat = torch.randn(B, RK, generator=gt, device=dev) * 0.01
+    o_lat = torch.empty(B, RK, device=dev)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(3), wl.min_split
+    plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
+    ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan.workspace_bytes()]
+    fdc.fdc_plan_upload(plan, ws)
+    fn = lambda i: fdc.fdc_latent_attn_decode(lay, plan, q_lat, kcs[i % copies], vcs[i % copies], 1.0 / math.sqrt(dh), o_lat, ws)
+    for i in range(copies):
+        fn(i)
+    torch.cuda.synchronize()
+    ev = HipEvents(2 * iters)
+    for i in range(iters):
+        fdc.fdc_profile_decode_events(ev.ev[2 * i], ev.ev[2 * i + 1])
+        fn(i)
+    torch.cuda.synchronize()
+    tile = float(np.mean([ev.ms(2 * i, 2 * i + 1) for i in range(iters)])) * 1e3
+    ev.destroy()
+    cache_bytes = float(B * S * 2 * int(np.sum(ranks[0])))    # one byte per cached element
+    return {"workload": "layer 0 of %s with an E4M3 cache (one byte per element)" % wl.name,
+            "n_workers": pp.n_workers, "tiles": int(plan.export()["n_items"]),
+            "tile_kernel_us": tile, "tile_kernel_GBps": cache_bytes / tile / 1e3,
+            "frac_of_hbm_peak": cache_bytes / tile / 1e3 / HBM_PEAK_GBPS,
+            "cached_tokens_per_us": B * S / tile}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -471,6 +516,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-gqa", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
@@ -518,6 +564,9 @@ def main():
         line["prefill"] = run_prefill_workload(fdc, gen)
     if not args.no_gqa:
         line["gqa_decode"] = run_gqa_decode_workload(fdc, gen)
+    if not args.no_fp8:
+        torch.cuda.empty_cache()
+        line["fp8_decode"] = run_fp8_decode_workload(fdc, gen, wl)
     print(json.dumps(line))
 
 

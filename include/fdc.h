@@ -24,7 +24,16 @@
  *    (FDC_BAD_ALIGNMENT).
  *  - dtype of a layout: FDC_BF16 = caches, activations and weights are bf16,
  *    sums are fp32; FDC_F32 = everything fp32 (small validation shapes; the
- *    prefill kernel does not support it).
+ *    prefill kernel does not support it); FDC_FP8 = the K'/V' caches hold OCP
+ *    E4M3 codes (one byte per element: round to nearest even, values beyond
+ *    +-448 saturate), everything else is as in a bf16 layout. No scales are
+ *    stored: per-head scales fold into the factors (A divided, B_k and
+ *    B_v.W_o multiplied by them), so attention works on the decoded code
+ *    values (the paper combines its compression with cache quantisation in
+ *    Section 6.2 and fixes no format: a reading). Supported with FDC_FP8:
+ *    the projections, fdc_project_and_absorb_query, the decode planners and
+ *    fdc_latent_attn_decode for multi-head layouts; prefill attention,
+ *    grouped queries and the post-RoPE key path are FDC_UNSUPPORTED_DTYPE.
  *  - fdc_layout and fdc_plan are host objects, immutable after creation,
  *    destroyed by the matching call.
  */
@@ -49,7 +58,7 @@ typedef enum {
   FDC_UNSUPPORTED_DTYPE = -7
 } fdc_status;
 
-typedef enum { FDC_BF16 = 0, FDC_F32 = 1 } fdc_dtype;
+typedef enum { FDC_BF16 = 0, FDC_F32 = 1, FDC_FP8 = 2 } fdc_dtype;
 
 typedef struct fdc_layout fdc_layout;
 typedef struct fdc_plan fdc_plan;
@@ -142,7 +151,8 @@ typedef struct {
 void fdc_plan_params_default(fdc_plan_params* p);
 
 /* Number of workers that are resident at once on the current HIP device for the decode
- * (kind 0), prefill (kind 1) or grouped-query decode (kind 2, layouts with q_per_kv > 1) kernel.
+ * (kind 0), prefill (kind 1), grouped-query decode (kind 2, layouts with q_per_kv > 1) or E4M3-cache
+ * decode (kind 3, FDC_FP8 layouts) kernel.
  * Needs a GPU (FDC_HIP_ERROR otherwise). */
 fdc_status fdc_suggest_workers(int kind, int32_t* n_workers);
 

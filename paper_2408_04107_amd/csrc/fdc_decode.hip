@@ -27,7 +27,7 @@ namespace fdc {
 #endif
 constexpr int kTokLanes = 64 * FDC_DECODE_LOADS;  // a block holds FDC_DECODE_LOADS wave-wide loads of the wider operand
 constexpr int kWavesPerBlock = 4;
-constexpr int kLdsFloatsPerWave = kTokLanes / 2 > 256 ? kTokLanes / 2 : 256;
+constexpr int kLdsFloatsPerWave = kTokLanes > 256 ? kTokLanes : 256;  // a block of one-lane rows (E4M3, rank 16) has kTokLanes tokens
 
 // Tokens per block: FDC_DECODE_LOADS loads of the wider operand, at least one load of the narrower.
 constexpr int block_tokens(int lk, int lv) {
@@ -88,6 +88,18 @@ struct Elem<uint16_t> {  // bf16 bits
     f[2] = __uint_as_float(r[1] << 16), f[3] = __uint_as_float(r[1] & 0xffff0000u);
     f[4] = __uint_as_float(r[2] << 16), f[5] = __uint_as_float(r[2] & 0xffff0000u);
     f[6] = __uint_as_float(r[3] << 16), f[7] = __uint_as_float(r[3] & 0xffff0000u);
+  }
+};
+template <>
+struct Elem<uint8_t> {  // OCP E4M3 codes: sixteen elements per 16-byte load, decoded in pairs (v_cvt_pk_f32_fp8)
+  static constexpr int EL = 16;
+  __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8(r[w], false);  // bytes 0, 1 of the word
+      const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8(r[w], true);   // bytes 2, 3
+      f[4 * w + 0] = lo[0], f[4 * w + 1] = lo[1], f[4 * w + 2] = hi[0], f[4 * w + 3] = hi[1];
+    }
   }
 };
 template <>
@@ -263,8 +275,8 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
 // log2 of the padded lanes-per-row: rank r needs r * sizeof(T) / 16 lanes.
 template <typename T>
 __device__ __forceinline__ int lane_class(int r) {
-  const int lanes = r / Elem<T>::EL;  // 2..16 (bf16), 4..32 (f32)
-  return 32 - __builtin_clz(lanes - 1);  // ceil(log2(lanes)) for lanes >= 2
+  const int lanes = r / Elem<T>::EL;  // 1..8 (E4M3), 2..16 (bf16), 4..32 (f32)
+  return lanes <= 1 ? 0 : 32 - __builtin_clz(lanes - 1);  // ceil(log2(lanes))
 }
 
 template <typename T>
@@ -282,14 +294,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
   const int count = hd->count, begin = hd->begin;
   if (count == 0) return;
   DecTile td = hd->first;
-  constexpr int BASE = Elem<T>::EL == 8 ? 1 : 2;  // smallest lane class of this element type
+  constexpr int BASE = Elem<T>::EL == 16 ? 0 : (Elem<T>::EL == 8 ? 1 : 2);  // smallest lane class (log2 lanes per row) of this element type
   for (int i = 0;;) {
     const int ck = lane_class<T>(td.rk_rv & 0xffff) - BASE, cvv = lane_class<T>(td.rk_rv >> 16) - BASE;
 #define FDC_CASE(a, b)                                                                                      \
   case (a)*4 + (b):                                                                                         \
-    decode_tile<T, (2 << (a)) * (BASE == 2 ? 2 : 1), (2 << (b)) * (BASE == 2 ? 2 : 1)>(td, q_lat, kc, vc,   \
-                                                                                      scale_log2, o_lat,   \
-                                                                                      partials, lds, lane); \
+    decode_tile<T, (1 << ((a) + BASE)), (1 << ((b) + BASE))>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, \
+                                                             lane);                                                \
     break;
     switch (ck * 4 + cvv) {
       FDC_CASE(0, 0) FDC_CASE(0, 1) FDC_CASE(0, 2) FDC_CASE(0, 3)
@@ -434,6 +445,11 @@ fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
     FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<uint16_t>,
                                                                kWavesPerBlock * 64, 0));
     *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
+  } else if (kind == 3) {
+    int nb = 0;
+    FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<uint8_t>,
+                                                               kWavesPerBlock * 64, 0));
+    *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
   } else if (kind == 2) {
     int waves = 0;
     fdc_status st = decode_gqa_workers_per_cu(&waves);
@@ -500,6 +516,10 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
       hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
                          static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+    else if (lay->dtype == FDC_FP8)
+      hipLaunchKernelGGL(decode_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles,
+                         static_cast<const float*>(q_lat), static_cast<const uint8_t*>(k_cache),
+                         static_cast<const uint8_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
     else
       hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),

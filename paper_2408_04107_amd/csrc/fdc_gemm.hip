@@ -52,6 +52,7 @@ struct GemmArgs {
   const int32_t* tok_batch;
   const int32_t* tok_pos;
   int v_only;             // project: B holds only the V' rows, every column goes to the V' cache
+  int cache_fp8;          // project: the caches hold E4M3 codes (one byte per element) instead of bf16
   const float* rope_cos;  // post-RoPE path: [n_pos, d_head / 2]
   const float* rope_sin;
   int n_pos;
@@ -96,6 +97,17 @@ template <>
 __device__ __forceinline__ void store_out<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void store_out<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+
+// One cache element: bf16, or the E4M3 code of the value saturated to +-448 (v_cvt_pk_fp8_f32 rounds
+// to nearest even and would turn larger values into NaN).
+__device__ __forceinline__ void store_cache(const GemmArgs& g, void* cache, int64_t e, float v) {
+  if (g.cache_fp8) {
+    const float c = fminf(fmaxf(v, -448.f), 448.f);
+    static_cast<uint8_t*>(cache)[e] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(c, 0.f, 0u, false) & 0xffu);
+  } else {
+    static_cast<uint16_t*>(cache)[e] = f32_to_bf16(v);
+  }
+}
 
 // Cache element for output column n of the concatenated [K heads | V heads] projection.
 // Returns the buffer (0 = K', 1 = V') and the element offset for token (b, pos).
@@ -299,7 +311,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       rank = (int)(one - col_off);
       seq_stride = (int64_t)g.max_seq * (side ? g.RV : g.RK);
     }
-    uint16_t* cache = static_cast<uint16_t*>(side ? g.C2 : g.C);
+    void* cache = side ? g.C2 : g.C;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -307,7 +319,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int m = m0 + wm + i * 32 + (e / 4) * 8 + (lane / 32) * 4 + e % 4;
         if (m >= g.M) continue;
         if (g.mode == kProject) {
-          cache[(int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank] = f32_to_bf16(acc[i][j][e]);
+          store_cache(g, cache, (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank, acc[i][j][e]);
         } else {
           store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc[i][j][e]);
         }
@@ -738,7 +750,7 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const Ge
         if (g.mode == kProject) {
           int side;
           const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
-          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(sum[e]);
+          store_cache(g, side ? g.C2 : g.C, dst, sum[e]);
         } else {
           store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
         }
@@ -865,7 +877,7 @@ __device__ __forceinline__ void skinny16_body(const GemmArgs& g, const int col_t
         if (g.mode == kProject) {
           int side;
           const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
-          static_cast<uint16_t*>(side ? g.C2 : g.C)[dst] = f32_to_bf16(sum[e]);
+          store_cache(g, side ? g.C2 : g.C, dst, sum[e]);
         } else {
           store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
         }
@@ -1021,7 +1033,7 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     else if (c_f32) launch_skinny<uint16_t, float>(a, st);
     else launch_skinny<uint16_t, uint16_t>(a, st);
   } else if (!a_f32 && groups == 1 && (a.mode == kPlain || a.mode == kProject) && a.K % 8 == 0 && a.lda % 8 == 0 &&
-             a.ldb % 8 == 0) {
+             a.ldb % 8 == 0 && !(a.mode == kProject && a.cache_fp8)) {  // its scatter epilogue packs bf16 pairs
     GemmArgs b = a;
     b.nt = (a.N + DN - 1) / DN;
     const int tiles = b.nt * ((a.M + DM - 1) / DM);
@@ -1071,6 +1083,7 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
   a.A = x, a.B = A_cat_t, a.C = k_cache, a.C2 = v_cache;
   a.lda = lay->d_model, a.ldb = lay->d_model, a.ldc = 0;
   a.v_only = k_cache == nullptr;
+  a.cache_fp8 = lay->dtype == FDC_FP8;
   a.M = T, a.N = a.v_only ? a.RV : a.RK + a.RV, a.K = lay->d_model;
   a.mode = kProject;
   a.tok_batch = tok_batch, a.tok_pos = tok_pos;
@@ -1104,7 +1117,7 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
                                         void* k_cache, void* v_cache, const void* q, const void* Bk, void* q_lat,
                                         fdc_dtype q_lat_dtype, void* stream) {
   // one launch only where both halves take their few-row kernels; otherwise the two calls in turn
-  if (!lay || lay->dtype != FDC_BF16 || T < 1 || T > 16 || layer < 0 || layer >= lay->L || !x || !tok_batch ||
+  if (!lay || lay->dtype == FDC_F32 || T < 1 || T > 16 || layer < 0 || layer >= lay->L || !x || !tok_batch ||
       !tok_pos || !A_cat_t || !v_cache || !q || !Bk || !q_lat || !aligned16(x) || !aligned16(A_cat_t) ||
       (k_cache && !aligned16(k_cache)) || !aligned16(v_cache) || !aligned16(q) || !aligned16(Bk) ||
       !aligned16(q_lat) || (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) || lay->H > kMaxHeads) {
@@ -1117,6 +1130,7 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
   p.A = x, p.B = A_cat_t, p.C = k_cache, p.C2 = v_cache;
   p.lda = lay->d_model, p.ldb = lay->d_model, p.ldc = 0;
   p.v_only = k_cache == nullptr;
+  p.cache_fp8 = lay->dtype == FDC_FP8;
   p.M = T, p.N = p.v_only ? p.RV : p.RK + p.RV, p.K = lay->d_model;
   p.mode = kProject;
   p.tok_batch = tok_batch, p.tok_pos = tok_pos;

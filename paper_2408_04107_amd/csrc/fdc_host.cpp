@@ -74,7 +74,8 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
   if (d_head < 16 || d_head > 128 || d_head % 16 != 0)
     FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_head %d must be a multiple of 16 in [16, 128]", d_head);
   if (d_model % 8 != 0) FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_model %d must be a multiple of 8", d_model);
-  if (dtype != FDC_BF16 && dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_layout_create: dtype %d", (int)dtype);
+  if (dtype != FDC_BF16 && dtype != FDC_F32 && dtype != FDC_FP8)
+    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_layout_create: dtype %d", (int)dtype);
   const size_t n = (size_t)n_layers * n_heads;
   for (size_t i = 0; i < n; ++i) {
     for (int32_t r : {rk[i], rv[i]})
@@ -86,7 +87,7 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
   if (!lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create: out of host memory");
   lay->L = n_layers, lay->H = n_heads, lay->d_model = d_model, lay->d_head = d_head;
   lay->max_batch = max_batch, lay->max_seq = max_seq, lay->dtype = dtype;
-  lay->elem_size = dtype == FDC_BF16 ? 2 : 4;
+  lay->elem_size = dtype == FDC_BF16 ? 2 : (dtype == FDC_FP8 ? 1 : 4);
   lay->rk.assign(rk, rk + n);
   lay->rv.assign(rv, rv + n);
   lay->koff.resize(n), lay->voff.resize(n);

@@ -1,0 +1,232 @@
+"""GPU parity of the E4M3 latent cache (FDC_FP8 layouts) through the C ABI.
+
+Projection: the codes the library stores are compared with the oracle's codes of the same products
+(the code decision is taken on the fp32 value on both sides; the library's fp32 sum is MFMA-ordered,
+so a value that sits on a rounding boundary may land on the neighbouring code: such elements must be
+rare and exactly one code apart). Decode attention: the oracle works on the decoded values of the
+very bytes the kernel reads, so the usual tolerance applies.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2408_04107_amd as fdc
+from oracle import attention as oa
+from oracle import fp8
+from tests.gpu_util import assert_close, workspace_for
+from workloads import generators as gen
+
+pytestmark = pytest.mark.gpu
+BF = torch.bfloat16
+
+
+def say(msg):
+    print(f"[fp8-parity] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+def magnitude_index(codes):
+    """Position of a code on the ordered grid of values (sign-magnitude -> signed integer)."""
+    c = np.asarray(codes).astype(np.int64)
+    return np.where(c & 0x80, -(c & 0x7F), c & 0x7F)
+
+
+@pytest.mark.parametrize("T", [1, 16, 40, 300])
+def test_projection_stores_the_oracles_codes(T):
+    rk, rv = [16, 48, 128, 64], [64, 16, 128, 32]
+    H, d, B, S = len(rk), 512, 3, 200
+    say(f"project T={T}")
+    lay = fdc.Layout(1, H, d, 128, [rk], [rv], B, S, fdc.FDC_FP8)
+    t = lay.tables()
+    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    assert int(t["k_bytes"][0]) == B * S * RK and int(t["v_bytes"][0]) == B * S * RV    # one byte per element
+    kc = torch.zeros(B * S * RK, dtype=torch.uint8, device="cuda:0")
+    vc = torch.zeros(B * S * RV, dtype=torch.uint8, device="cuda:0")
+    g = gen.make_rng(900 + T)
+    x = torch.from_numpy(gen.round_to_bf16(gen.hidden_states(T, d, g))).to(BF).cuda()
+    # weights scaled so that the rows spread over the whole E4M3 range, some beyond 448 (saturation)
+    A = torch.from_numpy(gen.round_to_bf16(g.standard_normal((RK + RV, d)) * (150.0 / math.sqrt(d)))).to(BF).cuda()
+    slots = g.permutation(B * S)[:T]
+    tb = torch.tensor(slots // S, dtype=torch.int32, device="cuda:0")
+    tp = torch.tensor(slots % S, dtype=torch.int32, device="cuda:0")
+    fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A, kc, vc)
+    torch.cuda.synchronize()
+    x64, A64 = x.to(torch.float64).cpu().numpy(), A.to(torch.float64).cpu().numpy()
+    kb, vb = kc.cpu().numpy(), vc.cpu().numpy()
+    n_total = n_off = 0
+    sat = 0
+    for side, buf, ranks, R, row0 in (("k", kb, rk, RK, 0), ("v", vb, rv, RV, RK)):
+        off = np.concatenate([[0], np.cumsum(ranks)])
+        for h in range(H):
+            want = fp8.quantise_latent(x64 @ A64[row0 + off[h]:row0 + off[h + 1]].T)       # [T, r] codes
+            got = np.stack([buf[(b * S) * R + S * off[h] + p * ranks[h]:(b * S) * R + S * off[h] + (p + 1) * ranks[h]]
+                            for b, p in zip(slots // S, slots % S)])
+            diff = np.abs(magnitude_index(got) - magnitude_index(want))
+            assert diff.max() <= 1, (side, h, int(diff.max()))
+            n_total += diff.size
+            n_off += int((diff == 1).sum())
+            sat += int(((want & 0x7F) == 0x7E).sum())
+    assert n_off <= max(2, n_total // 500), (n_off, n_total)
+    assert sat > 0                      # the saturating branch was exercised
+    written = np.zeros(B * S, bool)
+    written[slots] = True
+    view = kb.reshape(B, -1)
+    assert kb.any() and not view[~written.reshape(B, S).any(axis=1)].any()      # untouched sequences stay zero
+    say(f"  {n_total} codes, {n_off} one code apart, {sat} saturated")
+
+
+@pytest.mark.parametrize("W,granule,min_split", [(1, 64, 1), (37, 64, 1), (700, 32, 2)])
+def test_decode_attention_on_e4m3_codes(W, granule, min_split):
+    rk = [16, 32, 48, 64, 80, 96, 112, 128]
+    rv = [128, 16, 112, 32, 96, 48, 64, 80]
+    H, d_h = len(rk), 128
+    seq = [0, 1, 63, 257, 1500, 700]
+    B, S = len(seq), max(seq)
+    say(f"decode W={W} granule={granule} min_split={min_split}")
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], B, S, fdc.FDC_FP8)
+    t = lay.tables()
+    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    g = gen.make_rng(17 * W + granule)
+    # codes of latent rows with the decaying spectrum of the workloads, scaled into the format's range
+    kcodes = np.zeros(B * S * RK, dtype=np.uint8)
+    vcodes = np.zeros(B * S * RV, dtype=np.uint8)
+    Ks, Vs = {}, {}
+    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    for b, n in enumerate(seq):
+        for h in range(H):
+            kq = fp8.quantise_latent(gen.direct_latent(n, rk[h], 32.0, g) * 6.0)
+            vq = fp8.quantise_latent(gen.direct_latent(n, rv[h], 32.0, g) * 100.0)
+            Ks[b, h], Vs[b, h] = fp8.e4m3_decode(kq), fp8.e4m3_decode(vq)
+            k0, v0 = b * S * RK + S * ko[h], b * S * RV + S * vo[h]
+            kcodes[k0:k0 + n * rk[h]] = kq.ravel()
+            vcodes[v0:v0 + n * rv[h]] = vq.ravel()
+    kc, vc = torch.from_numpy(kcodes).cuda(), torch.from_numpy(vcodes).cuda()
+    q_lat = torch.from_numpy((g.standard_normal((B, RK)) * 0.5).astype(np.float32)).cuda()
+    o_lat = torch.full((B, RV), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.granule, pp.min_split = W, granule, min_split
+    plan = fdc.fdc_plan_decode(lay, 0, seq, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    for _ in range(2):      # twice on the same workspace
+        fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    out = o_lat.cpu().numpy().astype(np.float64)
+    q64 = q_lat.cpu().numpy().astype(np.float64)
+    got_all, ref_all = [], []
+    for b, n in enumerate(seq):
+        for h in range(H):
+            got = out[b, vo[h]:vo[h + 1]]
+            if n == 0:
+                assert not got.any()
+                continue
+            ref = oa.latent_attn_decode(q64[b, ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale)
+            # values reach +-448: the absolute bound scales with the largest value a head can output
+            assert_close(got / 100.0, ref / 100.0, f"b={b} h={h} n={n}")
+            got_all.append(got), ref_all.append(ref)
+    ma, rl = assert_close(np.concatenate(got_all) / 100.0, np.concatenate(ref_all) / 100.0, "all")
+    say(f"  tiles={plan.export()['n_items']} max_abs/100={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_calls_without_an_e4m3_path_refuse_the_layout():
+    lay = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 4
+    plan = fdc.fdc_plan_prefill(lay, 0, [10, 0], [100, 0], pp)
+    ws = workspace_for(plan)
+    q = torch.zeros(10, 48, dtype=BF, device="cuda:0")
+    o = torch.zeros(10, 32, dtype=BF, device="cuda:0")
+    kc = torch.zeros(2 * 128 * 48, dtype=torch.uint8, device="cuda:0")
+    vc = torch.zeros(2 * 128 * 32, dtype=torch.uint8, device="cuda:0")
+    with pytest.raises(fdc.FdcError):
+        fdc.fdc_latent_attn_prefill(lay, plan, q, kc, vc, 0.1, True, o, ws)
+    layg = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8, q_per_kv=2)
+    pland = fdc.fdc_plan_decode(layg, 0, [5, 7], pp)
+    wsd = workspace_for(pland)
+    ql = torch.zeros(2, 96, dtype=torch.float32, device="cuda:0")
+    ol = torch.zeros(2, 64, dtype=torch.float32, device="cuda:0")
+    with pytest.raises(fdc.FdcError):
+        fdc.fdc_latent_attn_decode(layg, pland, ql, kc, vc, 0.1, ol, wsd)
+
+
+def test_one_launch_prologue_and_bf16_side_calls_on_an_e4m3_layout():
+    """fdc_project_and_absorb_query writes the same codes and queries as the two calls; query absorption
+    and output projection of an FDC_FP8 layout are those of the bf16 layout (only the cache differs)."""
+    rk, rv = [16, 48, 128, 64], [64, 16, 128, 32]
+    H, d, d_h, B, S, T = len(rk), 512, 128, 2, 64, 12
+    lay8 = fdc.Layout(1, H, d, d_h, [rk], [rv], B, S, fdc.FDC_FP8)
+    lay16 = fdc.Layout(1, H, d, d_h, [rk], [rv], B, S, fdc.FDC_BF16)
+    RK, RV = sum(rk), sum(rv)
+    g = gen.make_rng(77)
+    x = torch.from_numpy(gen.round_to_bf16(gen.hidden_states(T, d, g))).to(BF).cuda()
+    A = torch.from_numpy(gen.round_to_bf16(g.standard_normal((RK + RV, d)) * (40.0 / math.sqrt(d)))).to(BF).cuda()
+    q = torch.from_numpy(gen.round_to_bf16(g.standard_normal((T, H, d_h)))).to(BF).cuda()
+    Bk = torch.from_numpy(gen.round_to_bf16(g.standard_normal((RK, d_h)) / math.sqrt(d_h))).to(BF).cuda()
+    slots = g.permutation(B * S)[:T]
+    tb = torch.tensor(slots // S, dtype=torch.int32, device="cuda:0")
+    tp = torch.tensor(slots % S, dtype=torch.int32, device="cuda:0")
+    k2, v2 = torch.zeros(B * S * RK, dtype=torch.uint8, device="cuda:0"), torch.zeros(B * S * RV, dtype=torch.uint8, device="cuda:0")
+    k1, v1 = torch.zeros_like(k2), torch.zeros_like(v2)
+    q2 = torch.full((T, RK), float("nan"), dtype=torch.float32, device="cuda:0")
+    q1, q16 = torch.full_like(q2, float("nan")), torch.full_like(q2, float("nan"))
+    fdc.fdc_project_latent_kv(lay8, 0, x, tb, tp, A, k2, v2)
+    fdc.fdc_absorb_query(lay8, 0, q, Bk, q2, fdc.FDC_F32)
+    fdc.fdc_project_and_absorb_query(lay8, 0, x, tb, tp, A, k1, v1, q, Bk, q1, fdc.FDC_F32)
+    fdc.fdc_absorb_query(lay16, 0, q, Bk, q16, fdc.FDC_F32)
+    Mt = torch.from_numpy(gen.round_to_bf16(g.standard_normal((d, RV)) / math.sqrt(RV))).to(BF).cuda()
+    o = torch.from_numpy(g.standard_normal((T, RV)).astype(np.float32)).cuda()
+    y8 = torch.empty(T, d, dtype=BF, device="cuda:0")
+    y16 = torch.empty(T, d, dtype=BF, device="cuda:0")
+    fdc.fdc_absorb_output(lay8, 0, fdc.FDC_APPLY, None, None, Mt, o, fdc.FDC_F32, T, y8, fdc.FDC_BF16)
+    fdc.fdc_absorb_output(lay16, 0, fdc.FDC_APPLY, None, None, Mt, o, fdc.FDC_F32, T, y16, fdc.FDC_BF16)
+    torch.cuda.synchronize()
+    assert k1.any() and torch.equal(k1, k2) and torch.equal(v1, v2)
+    assert torch.equal(q1, q2) and torch.equal(q1, q16) and not torch.isnan(q1).any()
+    assert torch.equal(y8, y16)
+
+
+def test_paged_decode_on_e4m3_codes():
+    from tests.test_gpu_paged import build_block_table
+    from oracle import layout as ol
+    rk, rv = [16, 64, 128], [32, 128, 16]
+    H, d_h, P = len(rk), 128, 128
+    seq = [5, 300, 0, 129]
+    g = gen.make_rng(123)
+    bt, n_pages = build_block_table(seq, P, g)
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], n_pages, P, fdc.FDC_FP8)
+    RK, RV = sum(rk), sum(rv)
+    kcodes, vcodes = np.zeros(n_pages * P * RK, np.uint8), np.zeros(n_pages * P * RV, np.uint8)
+    Ks, Vs = {}, {}
+    for b, n in enumerate(seq):
+        for h in range(H):
+            kq = fp8.quantise_latent(gen.direct_latent(n, rk[h], 32.0, g) * 6.0)
+            vq = fp8.quantise_latent(gen.direct_latent(n, rv[h], 32.0, g) * 50.0)
+            Ks[b, h], Vs[b, h] = fp8.e4m3_decode(kq), fp8.e4m3_decode(vq)
+            for tkn in range(n):
+                k0 = ol.paged_element_index(rk, P, bt[b], h, tkn, 0)
+                v0 = ol.paged_element_index(rv, P, bt[b], h, tkn, 0)
+                kcodes[k0:k0 + rk[h]], vcodes[v0:v0 + rv[h]] = kq[tkn], vq[tkn]
+    kc, vc = torch.from_numpy(kcodes).cuda(), torch.from_numpy(vcodes).cuda()
+    B = len(seq)
+    q_lat = torch.from_numpy((g.standard_normal((B, RK)) * 0.5).astype(np.float32)).cuda()
+    o_lat = torch.full((B, RV), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 19
+    plan = fdc.fdc_plan_decode_paged(lay, 0, seq, bt, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    out, q64 = o_lat.cpu().numpy().astype(np.float64), q_lat.cpu().numpy().astype(np.float64)
+    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    for b, n in enumerate(seq):
+        for h in range(H):
+            got = out[b, vo[h]:vo[h + 1]]
+            if n == 0:
+                assert not got.any()
+                continue
+            ref = oa.latent_attn_decode(q64[b, ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale)
+            assert_close(got / 50.0, ref / 50.0, f"paged b={b} h={h}")

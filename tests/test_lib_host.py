@@ -223,6 +223,17 @@ def test_paged_prefill_plan_bit_exact():
         fdc.fdc_plan_prefill_paged(lay64, 0, [10], [100], [[0, 1]], pp)
 
 
+def test_e4m3_layout_has_the_bf16_layouts_offsets_at_one_byte_per_element():
+    rk, rv = [[16, 64, 32, 128]], [[32, 64, 16, 128]]
+    t8 = fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, fdc.FDC_FP8).tables()
+    t16 = fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, fdc.FDC_BF16).tables()
+    for key in ("koff", "voff", "koff_r", "voff_r"):
+        assert np.array_equal(t8[key], t16[key]), key
+    assert np.array_equal(2 * t8["k_bytes"], t16["k_bytes"]) and np.array_equal(2 * t8["v_bytes"], t16["v_bytes"])
+    with pytest.raises(fdc.FdcError):
+        fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, 3)     # no such dtype
+
+
 def test_select_ranks_bit_exact_with_oracle():
     """Eq. (1): the library's rank choice equals the oracle's on planted, random and tie-prone spectra."""
     from oracle import rank_select as ors
