@@ -284,6 +284,19 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
                                   const void* k_cache, const void* v_cache, float scale, void* o_lat,
                                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same call for a decode loop that appends a token per step without planning every step
+ * (Section 5.3 schedules per step; the schedule of a plan only depends on the lengths in units of
+ * the granule). Plan once with every length rounded up to a multiple of params->granule, then call
+ * this with the actual lengths:
+ *   seq_len  device int32 [batch], planned[b] - granule < seq_len[b] <= planned[b] (and 0 where
+ *            planned[b] is 0); read by the kernel, not checked on the host
+ * The tile that ends a sequence covers only the tokens below seq_len[b]; everything else is the
+ * planned call. Out-of-range entries never make a kernel read past a planned tile, but the result
+ * for that sequence is then meaningless. */
+fdc_status fdc_latent_attn_decode_at(const fdc_layout* lay, const fdc_plan* plan, const int32_t* seq_len,
+                                     const void* q_lat, const void* k_cache, const void* v_cache, float scale,
+                                     void* o_lat, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aid: when both arguments are non-NULL hipEvent_t handles, the next
  * fdc_latent_attn_decode call made by this thread records `start` immediately before and `stop`
  * immediately after its tile kernel (the kernel that streams the cache; the split-K merge runs

@@ -283,7 +283,8 @@ template <typename T>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
     const DecWorker* __restrict__ workers, const DecTile* __restrict__ wtiles, const float* __restrict__ q_lat,
     const T* __restrict__ kc, const T* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
-    float* __restrict__ partials, int n_workers) {
+    float* __restrict__ partials, int n_workers, const int32_t* __restrict__ planned_len,
+    const int32_t* __restrict__ seq_len) {
   __shared__ float lds_all[kWavesPerBlock][kLdsFloatsPerWave];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int lane = threadIdx.x % 64;
@@ -296,6 +297,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
   DecTile td = hd->first;
   constexpr int BASE = Elem<T>::EL == 16 ? 0 : (Elem<T>::EL == 8 ? 1 : 2);  // smallest lane class (log2 lanes per row) of this element type
   for (int i = 0;;) {
+    td.len = dec_tile_len(td, planned_len, seq_len);
     const int ck = lane_class<T>(td.rk_rv & 0xffff) - BASE, cvv = lane_class<T>(td.rk_rv >> 16) - BASE;
 #define FDC_CASE(a, b)                                                                                      \
   case (a)*4 + (b):                                                                                         \
@@ -478,9 +480,11 @@ fdc_status fdc_plan_upload(const fdc_plan* plan, void* workspace, size_t workspa
   return FDC_OK;
 }
 
-fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat, const void* k_cache,
-                                  const void* v_cache, float scale, void* o_lat, void* workspace,
-                                  size_t workspace_bytes, void* stream) {
+}  // extern "C"
+
+static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const int32_t* lens, const void* q_lat,
+                              const void* k_cache, const void* v_cache, float scale, void* o_lat, void* workspace,
+                              size_t workspace_bytes, void* stream) {
   if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: NULL argument");
   if (plan->kind != 0 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: not a decode plan of this layout");
@@ -498,6 +502,7 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
   const DecUnit* units = reinterpret_cast<const DecUnit*>(ws + plan->off_units);
   const DecWorker* heads = reinterpret_cast<const DecWorker*>(ws + plan->off_worker_ptr);
   float* partials = reinterpret_cast<float*>(ws + plan->off_partials);
+  const int32_t* planned = reinterpret_cast<const int32_t*>(ws + plan->off_lens);
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
   const float scale_log2 = scale * kLog2e;
@@ -510,20 +515,20 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
     if (plan->G > 1) {
       fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat),
                                         static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
-                                        scale, static_cast<float*>(o_lat), partials, W, st);
+                                        scale, static_cast<float*>(o_lat), partials, W, planned, lens, st);
       if (gs != FDC_OK) return gs;
     } else if (lay->dtype == FDC_BF16)
       hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
-                         static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+                         static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
     else if (lay->dtype == FDC_FP8)
       hipLaunchKernelGGL(decode_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const uint8_t*>(k_cache),
-                         static_cast<const uint8_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+                         static_cast<const uint8_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
     else
       hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, heads, wtiles,
                          static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),
-                         static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W);
+                         static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
     FDC_HIP_CHECK(hipGetLastError());
     if (ev1) FDC_HIP_CHECK(hipEventRecord(ev1, st));
   }
@@ -536,6 +541,21 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
                        dim3(kMergeWaves * 64), 0, st, units, partials, static_cast<float*>(o_lat), plan->n_merge_units);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
+}
+
+extern "C" {
+
+fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat, const void* k_cache,
+                                  const void* v_cache, float scale, void* o_lat, void* workspace,
+                                  size_t workspace_bytes, void* stream) {
+  return decode_impl(lay, plan, nullptr, q_lat, k_cache, v_cache, scale, o_lat, workspace, workspace_bytes, stream);
+}
+
+fdc_status fdc_latent_attn_decode_at(const fdc_layout* lay, const fdc_plan* plan, const int32_t* seq_len,
+                                     const void* q_lat, const void* k_cache, const void* v_cache, float scale,
+                                     void* o_lat, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!seq_len) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_at: seq_len is NULL");
+  return decode_impl(lay, plan, seq_len, q_lat, k_cache, v_cache, scale, o_lat, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -265,7 +265,8 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
 __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
     const DecWorker* __restrict__ workers, const DecTile* __restrict__ wtiles, const float* __restrict__ q_lat,
     const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
-    float* __restrict__ partials, int n_workers) {
+    float* __restrict__ partials, int n_workers, const int32_t* __restrict__ planned_len,
+    const int32_t* __restrict__ seq_len) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_all[kGqaWaves][kGqaLdsElems];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int lane = threadIdx.x % 64;
@@ -277,6 +278,7 @@ __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
   if (count == 0) return;
   DecTile td = hd->first;
   for (int i = 0;;) {
+    td.len = dec_tile_len(td, planned_len, seq_len);
     const int rmax = max(td.rk_rv & 0xffff, td.rk_rv >> 16);
     switch ((rmax + 31) / 32) {
       case 1: gqa_tile<1>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
@@ -299,10 +301,10 @@ fdc_status decode_gqa_workers_per_cu(int* waves) {
 
 fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const uint16_t* kc,
                              const uint16_t* vc, float scale, float* o_lat, float* partials, int n_workers,
-                             hipStream_t st) {
+                             const int32_t* planned_len, const int32_t* seq_len, hipStream_t st) {
   const dim3 grid((n_workers + kGqaWaves - 1) / kGqaWaves), block(kGqaWaves * 64);
   hipLaunchKernelGGL(decode_gqa_tiles_kernel, grid, block, 0, st, heads, wtiles, q_lat, kc, vc, scale * kGqaLog2e,
-                     o_lat, partials, n_workers);
+                     o_lat, partials, n_workers, planned_len, seq_len);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

@@ -352,6 +352,7 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
     t.g = g;
     t.slot_stride = n_u;
     t.slot = n_u == 1 ? -1 : g * p->unit_item_ptr[u] + ((int32_t)tid - p->unit_item_ptr[u]);
+    t.b_end = b | (p->item_hi[tid] == seq_len[b] ? (int32_t)0x80000000 : 0);
   }
   p->n_merge_units = p->n_units * p->G;
   std::vector<DecUnit> units(p->n_merge_units);
@@ -375,6 +376,8 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
   p->off_units = region(units.size() * sizeof(DecUnit));
   p->off_worker_ptr = region((size_t)W * sizeof(DecWorker));
   p->off_worker_items = p->off_worker_ptr;
+  p->off_lens = region((size_t)batch * sizeof(int32_t));
+  std::memcpy(p->image.data() + p->off_lens, seq_len, (size_t)batch * sizeof(int32_t));
   DecTile* wtiles = reinterpret_cast<DecTile*>(p->image.data() + p->off_items);
   for (size_t i = 0; i < n; ++i) wtiles[i] = tiles[p->worker_items[i]];
   if (!units.empty()) std::memcpy(p->image.data() + p->off_units, units.data(), units.size() * sizeof(DecUnit));

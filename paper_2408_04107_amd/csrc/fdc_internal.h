@@ -44,8 +44,21 @@ struct DecTile {
                     // reads q' at q_elem + j * rk, writes o' at o_elem + j * rv and uses partial slot
                     // slot + j * slot_stride
   int32_t slot_stride;  // tiles of the unit
-  int32_t pad[1];
+  int32_t b_end;        // the sequence (bits 0..30); bit 31 set when the tile ends at the sequence's planned
+                        // length, i.e. it is the tile that shrinks when the call is given shorter actual lengths
 };
+
+// Length of a tile when the call passes the actual sequence lengths (device int32 [batch], each in the
+// last granule of the planned length): tiles that end the sequence give up planned - actual tokens.
+// Never longer than planned and never empty, whatever the array holds.
+#ifdef __HIPCC__
+__device__ inline int32_t dec_tile_len(const DecTile& t, const int32_t* planned_len, const int32_t* seq_len) {
+  if (seq_len == nullptr || t.b_end >= 0) return t.len;
+  const int32_t b = t.b_end & 0x7fffffff;
+  const int32_t cut = planned_len[b] - seq_len[b];
+  return cut <= 0 ? t.len : (t.len - cut < 1 ? 1 : t.len - cut);
+}
+#endif
 static_assert(sizeof(DecTile) == 48, "DecTile layout");
 
 // What a decode worker (one wavefront) reads first: how many tiles it has, where the rest of them
@@ -106,7 +119,7 @@ fdc_status decode_gqa_workers_per_cu(int* waves);
 namespace fdc {
 fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const uint16_t* kc,
                              const uint16_t* vc, float scale, float* o_lat, float* partials, int n_workers,
-                             hipStream_t st);
+                             const int32_t* planned_len, const int32_t* seq_len, hipStream_t st);
 }
 #endif
 
@@ -139,6 +152,7 @@ struct fdc_plan {
   // device image: packed tables, copied verbatim by fdc_plan_upload
   std::vector<unsigned char> image;
   size_t off_items, off_units, off_worker_ptr, off_worker_items;  // byte offsets inside image
+  size_t off_lens = 0;         // decode: int32 planned sequence lengths [batch], inside image
   size_t off_pages = 0;        // prefill over a paged cache: int32 page table [batch * max_pages], inside image
   size_t off_partials, partial_bytes;                             // decode only, after the image
   size_t workspace_bytes;

@@ -210,3 +210,69 @@ def test_non_positive_scale_is_rejected():
         with pytest.raises(fdc.FdcError) as e:
             fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, bad, o, ws)
         assert e.value.status == -1
+
+
+@pytest.mark.parametrize("g", [1, 4])
+@pytest.mark.parametrize("W,granule,min_split", [(9, 64, 1), (300, 32, 2), (4096, 64, 1)])
+def test_decode_at_actual_lengths_on_a_plan_for_rounded_up_lengths(W, granule, min_split, g):
+    """A decode loop plans once per granule: the plan is made for the lengths rounded up to a multiple of
+    the granule and fdc_latent_attn_decode_at runs it for every actual length in that last granule. The
+    rows between the actual and the planned length hold a poison value that must not reach the output."""
+    from oracle import gqa as og
+    rk, rv = [16, 48, 128, 64], [64, 16, 128, 32]
+    H, d_h = len(rk), 128
+    planned = [granule * n for n in (1, 5, 12, 3, 0)]
+    B, S_max = len(planned), max(planned)
+    say(f"decode_at g={g} W={W} granule={granule} planned={planned}")
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], B, S_max, fdc.FDC_BF16, q_per_kv=g)
+    cache = Cache(lay)
+    rng = gen.make_rng(31 * W + g)
+    for b in range(B):
+        for h in range(H):
+            if planned[b]:
+                cache.fill_unit("k", b, h, gen.direct_latent(planned[b], rk[h], 32.0, rng))
+                cache.fill_unit("v", b, h, gen.direct_latent(planned[b], rv[h], 32.0, rng))
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.granule, pp.min_split = W, granule, min_split
+    plan = fdc.fdc_plan_decode(lay, 0, planned, pp)
+    ws = workspace_for(plan)
+    q_lat = torch.from_numpy((rng.standard_normal((B, g * cache.RK)) * 2.0).astype(np.float32)).cuda()
+    scale = 1.0 / math.sqrt(d_h)
+    qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
+    q_used = q_lat.cpu().numpy().astype(np.float64) if g == 1 else q_lat.to(torch.bfloat16).to(torch.float64).cpu().numpy()
+    keep = {(b, h, s): cache.unit(s, b, h).clone() for b in range(B) for h in range(H) for s in "kv"}
+    for back in (0, 1, granule // 2, granule - 1):
+        actual = [max(p - back, 0) if p else 0 for p in planned]
+        for b in range(B):                      # poison what lies past the actual length
+            for h in range(H):
+                for s in "kv":
+                    u = cache.unit(s, b, h)
+                    u.copy_(keep[b, h, s])
+                    u[actual[b]:planned[b]] = 3.0e4
+        o_lat = torch.full((B, g * cache.RV), float("nan"), dtype=torch.float32, device="cuda:0")
+        lens = torch.tensor(actual, dtype=torch.int32, device="cuda:0")
+        fdc.fdc_latent_attn_decode_at(lay, plan, lens, q_lat, cache.k, cache.v, scale, o_lat, ws)
+        torch.cuda.synchronize()
+        out = o_lat.cpu().numpy().astype(np.float64)
+        for b in range(B):
+            for hq in range(H * g):
+                h = hq // g
+                got = out[b, oo[hq]:oo[hq + 1]]
+                if actual[b] == 0:
+                    assert not got.any()
+                    continue
+                ref = oa.latent_attn_decode(q_used[b, qo[hq]:qo[hq + 1]], cache.unit_f64("k", b, h, actual[b]),
+                                            cache.unit_f64("v", b, h, actual[b]), scale)
+                assert_close(got, ref, f"back={back} b={b} hq={hq}")
+    # the planned call itself is unchanged by the new tables
+    for b in range(B):
+        for h in range(H):
+            for s in "kv":
+                cache.unit(s, b, h).copy_(keep[b, h, s])
+    o1 = torch.empty(B, g * cache.RV, dtype=torch.float32, device="cuda:0")
+    o2 = torch.empty_like(o1)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o1, ws)
+    fdc.fdc_latent_attn_decode_at(lay, plan, torch.tensor(planned, dtype=torch.int32, device="cuda:0"), q_lat, cache.k,
+                                  cache.v, scale, o2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
