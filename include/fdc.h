@@ -30,10 +30,8 @@
  *    stored: per-head scales fold into the factors (A divided, B_k and
  *    B_v.W_o multiplied by them), so attention works on the decoded code
  *    values (the paper combines its compression with cache quantisation in
- *    Section 6.2 and fixes no format: a reading). Supported with FDC_FP8:
- *    the projections, fdc_project_and_absorb_query, the decode planners and
- *    fdc_latent_attn_decode for multi-head layouts; prefill attention,
- *    grouped queries and the post-RoPE key path are FDC_UNSUPPORTED_DTYPE.
+ *    Section 6.2 and fixes no format: a reading). Every call takes FDC_FP8
+ *    layouts except grouped-query decode attention (FDC_UNSUPPORTED_DTYPE).
  *  - fdc_layout and fdc_plan are host objects, immutable after creation,
  *    destroyed by the matching call.
  */

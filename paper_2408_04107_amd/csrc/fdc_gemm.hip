@@ -993,7 +993,7 @@ __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
       if constexpr (KEYS) {
         const int64_t dst = (int64_t)g.tok_batch[t] * g.max_seq * g.RK + (int64_t)g.max_seq * g.koff_r[h] +
                             (int64_t)g.tok_pos[t] * r + n;
-        static_cast<uint16_t*>(g.C)[dst] = f32_to_bf16(acc[e]);
+        store_cache(g, g.C, dst, acc[e]);
       } else {
         store_out(static_cast<TC*>(g.C) + (int64_t)t * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n, acc[e]);
       }
@@ -1204,7 +1204,7 @@ static fdc_status rope_common(const char* fn, const fdc_layout* lay, int layer, 
                               const void* R_t, void* out, GemmArgs* a) {
   fdc_status s = check_common(fn, lay, layer, T);
   if (s != FDC_OK) return s;
-  if (lay->dtype != FDC_BF16) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "%s: bf16 layouts only", fn);
+  if (lay->dtype == FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "%s: bf16 and E4M3 layouts only", fn);
   if (!x || !tok_pos || !cos_t || !sin_t || !R_t || !out) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
   if (n_pos <= 0) FDC_FAIL(FDC_BAD_SHAPE, "%s: n_pos must be positive", fn);
   if (!aligned16(x) || !aligned16(cos_t) || !aligned16(sin_t) || !aligned16(R_t) || !aligned16(out))
@@ -1244,6 +1244,7 @@ fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* 
   if (s != FDC_OK) return s;
   if (!tok_batch) FDC_FAIL(FDC_INVALID_ARG, "fdc_rope_compress_keys: tok_batch is NULL");
   a.tok_batch = tok_batch;
+  a.cache_fp8 = lay->dtype == FDC_FP8;
   const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H);
   hipLaunchKernelGGL((rope_compress_kernel<uint16_t, true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
   FDC_HIP_CHECK(hipGetLastError());

@@ -100,8 +100,11 @@ union Frag {
 // One instantiation serves every rank: the k-steps of the score product and the column tiles of
 // the output are fully unrolled loops with wave-uniform guards, so register arrays keep
 // compile-time indices and narrow heads skip the unused steps.
+// TC is the cache element: uint16_t (bf16) or uint8_t (E4M3 codes, widened to bf16, which holds them
+// exactly, on their way from the staging registers to LDS; everything after that is the same).
+template <typename TC>
 __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* __restrict__ q_lat,
-                                             const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+                                             const TC* __restrict__ kc, const TC* __restrict__ vc,
                                              float scale_log2, int causal, uint16_t* __restrict__ o_lat,
                                              const int32_t* __restrict__ page_table, int64_t page_stride_k,
                                              int64_t page_stride_v, uint16_t* lds) {
@@ -110,8 +113,10 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   const int RKP = rk32 * 32;  // rank of the K' rows in LDS, padded with zeros
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
-  const uint16_t* kbase = kc + t.k_elem;
-  const uint16_t* vbase = vc + t.v_elem;
+  const TC* kbase = kc + t.k_elem;
+  const TC* vbase = vc + t.v_elem;
+  constexpr int ES = (int)sizeof(TC);   // bytes per cached element
+  constexpr int EPC = 16 / ES;          // elements per 16-byte chunk of the cache
 
   // zero the rank padding of both K' tiles once: staging never writes those columns
   if (RKP != rk) {
@@ -121,21 +126,21 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     }
   }
 
-  // staging map: a token row of rank r is r / 8 chunks of 16 bytes; thread tid takes chunk
+  // staging map: a token row of rank r is r / EPC chunks of 16 bytes (r / 8 for bf16); thread tid takes chunk
   // tid % (r/8) of row tid / (r/8), so every lane of a sweep carries data whatever the rank (one
   // division per task). A sweep covers kPreThreads / (r/8) >= 32 rows: one sweep per block for
   // ranks <= 64, two above. K' and V' have their own maps (rk != rv).
   constexpr int kSweeps = 2;
-  const int lpk = rk / 8, lpv = rv / 8;
+  const int lpk = rk / EPC, lpv = rv / EPC;
   const int k_rps = kPreThreads / lpk, v_rps = kPreThreads / lpv;
   const int k_row = tid / lpk, k_cc = tid - k_row * lpk;
   const int v_row = tid / lpv, v_cc = tid - v_row * lpv;
   const int k_sweeps = (BCB + k_rps - 1) / k_rps, v_sweeps = (BCB + v_rps - 1) / v_rps;
   // the unit's K' and V' rows [0, kv_len) as raw buffers (at most 131072 * 256 bytes each)
   const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kbase), 0, t.kv_len * rk * 2, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(kbase), 0, t.kv_len * rk * ES, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vbase), 0, t.kv_len * rv * 2, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(vbase), 0, t.kv_len * rv * ES, 0x00020000);
   // per sweep: byte offset of the lane's chunk in block 0 (out of range when the lane has no row)
   // and its LDS element offset
   uint32_t k_goff[kSweeps], v_goff[kSweeps];
@@ -146,10 +151,10 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     const int kr = k_row + i * k_rps, vr = v_row + i * v_rps;
     k_on[i] = k_row < k_rps && kr < BCB;
     v_on[i] = v_row < v_rps && vr < BCB;
-    k_goff[i] = k_on[i] ? (uint32_t)(kr * rk * 2 + k_cc * 16) : 0x80000000u;
-    v_goff[i] = v_on[i] ? (uint32_t)(vr * rv * 2 + v_cc * 16) : 0x80000000u;
-    k_loff[i] = kr * KROW + k_cc * 8;
-    v_loff[i] = vr * VROW + v_cc * 8;
+    k_goff[i] = k_on[i] ? (uint32_t)(kr * rk * ES + k_cc * 16) : 0x80000000u;
+    v_goff[i] = v_on[i] ? (uint32_t)(vr * rv * ES + v_cc * 16) : 0x80000000u;
+    k_loff[i] = kr * KROW + k_cc * EPC;
+    v_loff[i] = vr * VROW + v_cc * EPC;
   }
 
   for (int r0 = 0; r0 < t.rows; r0 += kRowsPerPass) {
@@ -195,14 +200,31 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         const int pi = c0 / t.page_tokens, start = pi * t.page_tokens;
         const int64_t pg = page_table[t.page_first + pi];
         const int rows = min(t.page_tokens, t.kv_len - start);
-        kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kbase + pg * page_stride_k), 0, rows * rk * 2, 0x00020000);
-        vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vbase + pg * page_stride_v), 0, rows * rv * 2, 0x00020000);
+        kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(kbase + pg * page_stride_k), 0, rows * rk * ES, 0x00020000);
+        vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(vbase + pg * page_stride_v), 0, rows * rv * ES, 0x00020000);
         rel = c0 - start;
       }
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, (int)(k_goff[i] + (uint32_t)(rel * rk * 2)), 0, 0);
-        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)(v_goff[i] + (uint32_t)(rel * rv * 2)), 0, 0);
+        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, (int)(k_goff[i] + (uint32_t)(rel * rk * ES)), 0, 0);
+        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)(v_goff[i] + (uint32_t)(rel * rv * ES)), 0, 0);
+      }
+    };
+    auto put = [&](uint16_t* dst, const u32x4& chunk) {   // one 16-byte chunk of the cache -> bf16 in LDS
+      if constexpr (ES == 2) {
+        *reinterpret_cast<u32x4*>(dst) = chunk;
+      } else {
+        u32x4 lo, hi;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(chunk[w], false);  // bytes 0, 1 of the word
+          const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(chunk[w], true);   // bytes 2, 3
+          const uint32_t p0 = pack_bf16(a[0], a[1]), p1 = pack_bf16(b[0], b[1]);
+          if (w < 2) lo[2 * w] = p0, lo[2 * w + 1] = p1;
+          else hi[2 * (w - 2)] = p0, hi[2 * (w - 2) + 1] = p1;
+        }
+        *reinterpret_cast<u32x4*>(dst) = lo;
+        *reinterpret_cast<u32x4*>(dst + 8) = hi;
       }
     };
     auto stage = [&](int buf) {
@@ -210,8 +232,8 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
       uint16_t* lv = lk + BCB * KROW;
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        if (i < k_sweeps && k_on[i]) *reinterpret_cast<u32x4*>(&lk[k_loff[i]]) = kst[i];
-        if (i < v_sweeps && v_on[i]) *reinterpret_cast<u32x4*>(&lv[v_loff[i]]) = vst[i];
+        if (i < k_sweeps && k_on[i]) put(&lk[k_loff[i]], kst[i]);
+        if (i < v_sweeps && v_on[i]) put(&lv[v_loff[i]], vst[i]);
       }
     };
 
@@ -354,10 +376,11 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   }
 }
 
+template <typename TC>
 __global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(kPreWavesPerSimd, kPreWavesPerSimd))) void prefill_kernel(
     const PreTask* __restrict__ tasks, const int32_t* __restrict__ worker_ptr,
     const int32_t* __restrict__ worker_items, const uint16_t* __restrict__ q_lat,
-    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, int causal,
+    const TC* __restrict__ kc, const TC* __restrict__ vc, float scale_log2, int causal,
     uint16_t* __restrict__ o_lat, const int32_t* __restrict__ page_table, int64_t page_stride_k,
     int64_t page_stride_v) {
   __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStageElems];
@@ -365,12 +388,12 @@ __global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(kPr
   const int i0 = worker_ptr[w], i1 = worker_ptr[w + 1];
   for (int it = i0; it < i1; ++it) {
     const PreTask t = tasks[worker_items[it]];
-    prefill_task(t, q_lat, kc, vc, scale_log2, causal, o_lat, page_table, page_stride_k, page_stride_v, lds);
+    prefill_task<TC>(t, q_lat, kc, vc, scale_log2, causal, o_lat, page_table, page_stride_k, page_stride_v, lds);
   }
 }
 
 fdc_status prefill_blocks_per_cu(int* nb) {
-  FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(nb, prefill_kernel, kPreThreads, 0));
+  FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(nb, prefill_kernel<uint16_t>, kPreThreads, 0));
   return FDC_OK;
 }
 
@@ -386,7 +409,7 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
   if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: NULL argument");
   if (plan->kind != 1 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: not a prefill plan of this layout");
-  if (lay->dtype != FDC_BF16) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_prefill: bf16 layouts only");
+  if (lay->dtype == FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_prefill: bf16 and E4M3 layouts only");
   if (!(scale > 0.f) || !(scale < 1e30f))
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_prefill: scale must be positive and finite (the running softmax orders scores by scale * s)");
   if (workspace_bytes < plan->workspace_bytes)
@@ -397,14 +420,19 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
     FDC_FAIL(FDC_BAD_ALIGNMENT, "fdc_latent_attn_prefill: pointers must be 16-byte aligned (workspace 256)");
   if (plan->item_b.empty()) return FDC_OK;
   unsigned char* ws = static_cast<unsigned char*>(workspace);
-  hipLaunchKernelGGL(prefill_kernel, dim3(plan->n_workers), dim3(kPreThreads), 0, static_cast<hipStream_t>(stream),
-                     reinterpret_cast<const PreTask*>(ws + plan->off_items),
-                     reinterpret_cast<const int32_t*>(ws + plan->off_worker_ptr),
-                     reinterpret_cast<const int32_t*>(ws + plan->off_worker_items),
-                     static_cast<const uint16_t*>(q_lat), static_cast<const uint16_t*>(k_cache),
-                     static_cast<const uint16_t*>(v_cache), scale * kLog2eP, causal,
-                     static_cast<uint16_t*>(o_lat), reinterpret_cast<const int32_t*>(ws + plan->off_pages),
-                     (int64_t)lay->max_seq * plan->RK, (int64_t)lay->max_seq * plan->RV);
+  auto go = [&](auto kern, auto* kp, auto* vp) {
+    hipLaunchKernelGGL(kern, dim3(plan->n_workers), dim3(kPreThreads), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const PreTask*>(ws + plan->off_items),
+                       reinterpret_cast<const int32_t*>(ws + plan->off_worker_ptr),
+                       reinterpret_cast<const int32_t*>(ws + plan->off_worker_items),
+                       static_cast<const uint16_t*>(q_lat), kp, vp, scale * kLog2eP, causal,
+                       static_cast<uint16_t*>(o_lat), reinterpret_cast<const int32_t*>(ws + plan->off_pages),
+                       (int64_t)lay->max_seq * plan->RK, (int64_t)lay->max_seq * plan->RV);
+  };
+  if (lay->dtype == FDC_FP8)
+    go(prefill_kernel<uint8_t>, static_cast<const uint8_t*>(k_cache), static_cast<const uint8_t*>(v_cache));
+  else
+    go(prefill_kernel<uint16_t>, static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache));
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

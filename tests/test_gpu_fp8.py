@@ -4,7 +4,7 @@ Projection: the codes the library stores are compared with the oracle's codes of
 (the code decision is taken on the fp32 value on both sides; the library's fp32 sum is MFMA-ordered,
 so a value that sits on a rounding boundary may land on the neighbouring code: such elements must be
 rare and exactly one code apart). Decode attention: the oracle works on the decoded values of the
-very bytes the kernel reads, so the usual tolerance applies.
+very bytes the kernel reads, so the usual tolerance applies; the same for prefill attention.
 """
 import math
 import sys
@@ -131,25 +131,125 @@ def test_decode_attention_on_e4m3_codes(W, granule, min_split):
     say(f"  tiles={plan.export()['n_items']} max_abs/100={ma:.2e} rel_l2={rl:.2e}")
 
 
-def test_calls_without_an_e4m3_path_refuse_the_layout():
-    lay = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8)
+def test_grouped_query_decode_refuses_an_e4m3_layout():
+    layg = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8, q_per_kv=2)
     pp = fdc.fdc_plan_params_default()
     pp.n_workers = 4
-    plan = fdc.fdc_plan_prefill(lay, 0, [10, 0], [100, 0], pp)
-    ws = workspace_for(plan)
-    q = torch.zeros(10, 48, dtype=BF, device="cuda:0")
-    o = torch.zeros(10, 32, dtype=BF, device="cuda:0")
-    kc = torch.zeros(2 * 128 * 48, dtype=torch.uint8, device="cuda:0")
-    vc = torch.zeros(2 * 128 * 32, dtype=torch.uint8, device="cuda:0")
-    with pytest.raises(fdc.FdcError):
-        fdc.fdc_latent_attn_prefill(lay, plan, q, kc, vc, 0.1, True, o, ws)
-    layg = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8, q_per_kv=2)
     pland = fdc.fdc_plan_decode(layg, 0, [5, 7], pp)
     wsd = workspace_for(pland)
+    kc = torch.zeros(2 * 128 * 48, dtype=torch.uint8, device="cuda:0")
+    vc = torch.zeros(2 * 128 * 32, dtype=torch.uint8, device="cuda:0")
     ql = torch.zeros(2, 96, dtype=torch.float32, device="cuda:0")
     ol = torch.zeros(2, 64, dtype=torch.float32, device="cuda:0")
     with pytest.raises(fdc.FdcError):
         fdc.fdc_latent_attn_decode(layg, pland, ql, kc, vc, 0.1, ol, wsd)
+
+
+@pytest.mark.parametrize("g", [1, 2])
+@pytest.mark.parametrize("W,br,paged", [(5, 64, False), (40, 256, False), (9, 512, True)])
+def test_prefill_attention_on_e4m3_codes(W, br, paged, g):
+    """Causal prefill over E4M3 codes (dense and paged, chunked prompts, grouped queries): the kernel
+    widens the codes to bf16 while staging, which is exact, so the bf16 tolerance applies."""
+    from tests.test_gpu_paged import build_block_table
+    from oracle import gqa as og
+    from oracle import layout as ol
+    rk, rv = [16, 48, 128, 64], [64, 16, 128, 32]
+    H, d_h, P = len(rk), 128, 256
+    kv = [1, 129, 700, 1300, 333]
+    ql = [1, 129, 300, 1300, 0]
+    say(f"prefill W={W} br={br} paged={paged} g={g}")
+    rng = gen.make_rng(5 * W + br + g)
+    RK, RV = sum(rk), sum(rv)
+    if paged:
+        bt, n_rows = build_block_table(kv, P, rng)
+        lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], n_rows, P, fdc.FDC_FP8, q_per_kv=g)
+        row_len = P
+    else:
+        n_rows, row_len = len(kv), max(kv)
+        lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], n_rows, row_len, fdc.FDC_FP8, q_per_kv=g)
+    kcodes, vcodes = np.zeros(n_rows * row_len * RK, np.uint8), np.zeros(n_rows * row_len * RV, np.uint8)
+    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    Ks, Vs = {}, {}
+    for b, n in enumerate(kv):
+        for h in range(H):
+            kq = fp8.quantise_latent(gen.direct_latent(n, rk[h], 32.0, rng) * 6.0)
+            vq = fp8.quantise_latent(gen.direct_latent(n, rv[h], 32.0, rng) * 100.0)
+            Ks[b, h], Vs[b, h] = fp8.e4m3_decode(kq), fp8.e4m3_decode(vq)
+            for tkn in range(n):
+                if paged:
+                    k0 = ol.paged_element_index(rk, P, bt[b], h, tkn, 0)
+                    v0 = ol.paged_element_index(rv, P, bt[b], h, tkn, 0)
+                else:
+                    k0 = b * row_len * RK + row_len * ko[h] + tkn * rk[h]
+                    v0 = b * row_len * RV + row_len * vo[h] + tkn * rv[h]
+                kcodes[k0:k0 + rk[h]], vcodes[v0:v0 + rv[h]] = kq[tkn], vq[tkn]
+    kc, vc = torch.from_numpy(kcodes).cuda(), torch.from_numpy(vcodes).cuda()
+    T = int(np.sum(ql))
+    q_lat = torch.from_numpy(gen.round_to_bf16(rng.standard_normal((T, g * RK)) * 0.3)).to(BF).cuda()
+    o_lat = torch.full((T, g * RV), float("nan"), dtype=BF, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.br_base, pp.br_cap, pp.cost_mode = W, br, br, 1
+    plan = fdc.fdc_plan_prefill_paged(lay, 0, ql, kv, bt, pp) if paged else fdc.fdc_plan_prefill(lay, 0, ql, kv, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_prefill(lay, plan, q_lat, kc, vc, scale, True, o_lat, ws)
+    torch.cuda.synchronize()
+    out, q64 = o_lat.to(torch.float64).cpu().numpy(), q_lat.to(torch.float64).cpu().numpy()
+    assert np.all(np.isfinite(out))
+    qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
+    row0 = np.concatenate([[0], np.cumsum(ql)])
+    got_all, ref_all = [], []
+    for b in range(len(kv)):
+        if ql[b] == 0:
+            continue
+        for hq in range(H * g):
+            h = hq // g
+            ref = oa.latent_attn_prefill(q64[row0[b]:row0[b + 1], qo[hq]:qo[hq + 1]], Ks[b, h], Vs[b, h], scale, True)
+            got = out[row0[b]:row0[b + 1], oo[hq]:oo[hq + 1]]
+            assert_close(got / 100.0, ref / 100.0, f"b={b} hq={hq}")
+            got_all.append(got.ravel()), ref_all.append(ref.ravel())
+    ma, rl = assert_close(np.concatenate(got_all) / 100.0, np.concatenate(ref_all) / 100.0, "all")
+    say(f"  tasks={plan.export()['n_items']} max_abs/100={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_post_rope_keys_are_stored_as_e4m3_codes():
+    """fdc_rope_compress_keys on an FDC_FP8 layout. The kernel rounds the rotated keys to bf16 before its
+    MFMA product, the oracle does not, so values near a rounding boundary (and, in absolute terms, values near zero where the codes are fine)
+    can take another code: every decoded element must lie within half a code spacing plus the bf16-operand
+    error of the oracle's value, and most codes must be the oracle's."""
+    from oracle import rope as orp
+    H, d_h, rk, T, n_pos = 4, 64, [16, 64, 32, 48], 130, 256
+    g = gen.make_rng(41)
+    B, S = 2, 200
+    lay = fdc.Layout(1, H, 128, d_h, [rk], [rk], B, S, fdc.FDC_FP8)
+    RK = sum(rk)
+    kc = torch.zeros(B * S * RK, dtype=torch.uint8, device="cuda:0")
+    R_t = np.concatenate([np.linalg.qr(g.standard_normal((d_h, d_h)))[0][:, :r].T for r in rk], axis=0)   # [RK, d_h]
+    cos, sin = orp.rope_tables(n_pos, d_h)
+    k = torch.from_numpy(gen.round_to_bf16(g.standard_normal((T, H, d_h)) * 20.0)).to(BF).cuda()
+    R_d = torch.from_numpy(gen.round_to_bf16(R_t)).to(BF).cuda()
+    slots = g.permutation(B * S)[:T]
+    tb, tp = (slots // S).astype(np.int32), (slots % S).astype(np.int32)
+    fdc.fdc_rope_compress_keys(lay, 0, k, torch.from_numpy(tb).cuda(), torch.from_numpy(tp).cuda(),
+                               torch.from_numpy(cos.astype(np.float32)).cuda(), torch.from_numpy(sin.astype(np.float32)).cuda(),
+                               R_d, kc)
+    torch.cuda.synchronize()
+    cos32, sin32 = cos.astype(np.float32).astype(np.float64), sin.astype(np.float32).astype(np.float64)
+    off = np.concatenate([[0], np.cumsum(rk)])
+    R64, k64, kb = R_d.to(torch.float64).cpu().numpy(), k.to(torch.float64).cpu().numpy(), kc.cpu().numpy()
+    n_total = n_same = 0
+    for h in range(H):
+        want_rows = orp.rope(k64[:, h, :], tp, cos32, sin32) @ R64[off[h]:off[h + 1]].T
+        want = fp8.quantise_latent(want_rows)
+        got = np.stack([kb[b * S * RK + S * off[h] + p * rk[h]: b * S * RK + S * off[h] + (p + 1) * rk[h]] for b, p in zip(tb, tp)])
+        # half a code spacing (at most 1/16 of the value) plus the error of the bf16 operands (values reach 60,
+        # 64 terms: a few hundredths), which near zero spans several of the fine codes there
+        err = np.abs(fp8.e4m3_decode(got) - want_rows)
+        assert np.all(err <= np.abs(want_rows) / 16 + 0.15), (h, float(err.max()))
+        n_total += got.size
+        n_same += int((got == want).sum())
+    assert kb.any() and n_same >= 0.85 * n_total, (n_same, n_total)
+    say(f"  rope keys: {n_total} codes, {n_same} equal to the oracle's")
 
 
 def test_one_launch_prologue_and_bf16_side_calls_on_an_e4m3_layout():
