@@ -31,7 +31,7 @@
  *    B_v.W_o multiplied by them), so attention works on the decoded code
  *    values (the paper combines its compression with cache quantisation in
  *    Section 6.2 and fixes no format: a reading). Every call takes FDC_FP8
- *    layouts except grouped-query decode attention (FDC_UNSUPPORTED_DTYPE).
+ *    layouts.
  *  - fdc_layout and fdc_plan are host objects, immutable after creation,
  *    destroyed by the matching call.
  */

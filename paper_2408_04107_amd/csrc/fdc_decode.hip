@@ -508,14 +508,13 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   const float scale_log2 = scale * kLog2e;
   hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
-  if (plan->G > 1 && lay->dtype != FDC_BF16)
-    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 layout");
+  if (plan->G > 1 && lay->dtype == FDC_F32)
+    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
   if (!plan->item_b.empty()) {
     if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
     if (plan->G > 1) {
-      fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat),
-                                        static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache),
-                                        scale, static_cast<float*>(o_lat), partials, W, planned, lens, st);
+      fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat), k_cache, v_cache,
+                                        lay->dtype == FDC_FP8, scale, static_cast<float*>(o_lat), partials, W, planned, lens, st);
       if (gs != FDC_OK) return gs;
     } else if (lay->dtype == FDC_BF16)
       hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,

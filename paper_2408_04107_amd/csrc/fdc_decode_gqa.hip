@@ -54,6 +54,18 @@ __device__ __forceinline__ uint32_t gq_pack(float lo, float hi) {  // v_cvt_pk_b
   r.v = __builtin_convertvector(gq_f32x2{lo, hi}, gq_bf16x2);
   return r.u;
 }
+// Sixteen E4M3 codes (16 bytes) -> sixteen bf16 in the same order (v_cvt_pk_f32_fp8, then v_cvt_pk_bf16_f32;
+// bf16 holds every code value exactly).
+__device__ __forceinline__ void gq_widen16(const gq_u32x4& c, gq_u32x4& lo, gq_u32x4& hi) {
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(c[w], false);  // bytes 0, 1 of the word
+    const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(c[w], true);   // bytes 2, 3
+    const uint32_t p0 = gq_pack(a[0], a[1]), p1 = gq_pack(b[0], b[1]);
+    if (w < 2) lo[2 * w] = p0, lo[2 * w + 1] = p1;
+    else hi[2 * (w - 2)] = p0, hi[2 * (w - 2) + 1] = p1;
+  }
+}
 // reductions over the four lanes l, l ^ 16, l ^ 32, l ^ 48 that share a query
 __device__ __forceinline__ float gq_row_max(float v) {
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
@@ -75,27 +87,35 @@ __device__ __forceinline__ void gq_lds_order() {
 
 // M = ceil(max(rk, rv) / 32) in 1..4. Loop bounds are compile-time in M; the actual ranks only
 // guard (wave-uniformly) the steps a narrower side does not need.
-template <int M>
+// TC is the cache element: uint16_t (bf16) or uint8_t (E4M3 codes). Codes are widened to bf16 (exact)
+// in registers: a 16-byte load then holds sixteen k of its row, i.e. the operands of TWO MFMA steps, so
+// the k index is permuted (step 2 b + h takes elements 64 b + 16 lg + 8 h .. + 8 of lane row lg); Q' is
+// laid out the same way, and a product does not depend on the order of its terms' index.
+template <int M, typename TC>
 __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restrict__ q_lat,
-                                         const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc,
+                                         const TC* __restrict__ kc, const TC* __restrict__ vc,
                                          float scale_log2, float* __restrict__ o_lat, float* __restrict__ partials,
                                          uint16_t* lds, int lane) {
   constexpr int NB = M == 1 ? 4 : (M == 2 ? 2 : 1);  // 32-token sub-blocks per step
   constexpr int BT = 32 * NB;
-  constexpr int NVL = NB * 2 * M;                    // most 1 KiB loads a step of V' can need
+  constexpr int ES = (int)sizeof(TC);                // bytes per cached element
+  constexpr int MB = (M + 1) / 2;                    // E4M3: 64-element blocks of a K' row (two MFMA steps each)
+  constexpr int KS = ES == 2 ? M : 2 * MB;           // MFMA k-steps of the score product
+  constexpr int KL = ES == 2 ? M : MB;               // 16-byte K' loads per 16-token half
+  constexpr int NVL = ES == 2 ? NB * 2 * M : NB * M; // most 1 KiB loads a step of V' can need
   static_assert(BT * 32 * M <= kGqaLdsElems, "V' staging region");
   const int rk = td.rk_rv & 0xffff, rv = td.rk_rv >> 16;
   const int rk32 = (rk + 31) / 32, rv16 = rv / 16;
   const int ln = lane % 16, lg = lane / 16;
   const int g = td.g, len = td.len;
-  const uint32_t rk2 = (uint32_t)rk * 2, rv2 = (uint32_t)rv * 2;
+  const uint32_t rk2 = (uint32_t)rk * ES, rv2 = (uint32_t)rv * ES;   // bytes per cached row
   constexpr uint32_t kOob = 0x80000000u;
 
   // Q' operand: lane (ln, lg) holds k = 32 ks + 8 lg .. + 8 of query ln (zero rows past the group)
-  GqFrag qf[M];
+  GqFrag qf[KS];
 #pragma unroll
-  for (int ks = 0; ks < M; ++ks) {
-    const int col = 32 * ks + 8 * lg;
+  for (int ks = 0; ks < KS; ++ks) {
+    const int col = ES == 2 ? 32 * ks + 8 * lg : 64 * (ks / 2) + 16 * lg + 8 * (ks % 2);
     if (ln < g && col < rk) {
       const float* qp = q_lat + td.q_elem + ln * rk + col;
       const float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
@@ -106,17 +126,20 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
   }
 
   const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(kc + td.k_elem), 0, (int)(len * rk2), 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(kc + td.k_elem), 0, (int)(len * rk2), 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vc + td.v_elem), 0, (int)(len * rv2), 0x00020000);
-  // K' fragment (nb, j, ks): row tok0 + 32 nb + 16 j + ln, bytes 64 ks + 16 lg of the row
-  uint32_t kcol[M];
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(vc + td.v_elem), 0, (int)(len * rv2), 0x00020000);
+  // K' load (nb, j, kl): row tok0 + 32 nb + 16 j + ln, bytes 64 kl + 16 lg of the row (bf16: the fragment
+  // of step kl; E4M3: the sixteen codes of steps 2 kl and 2 kl + 1)
+  uint32_t kcol[KL];
 #pragma unroll
-  for (int ks = 0; ks < M; ++ks) kcol[ks] = (32 * ks + 8 * lg < rk) ? (uint32_t)(64 * ks + 16 * lg) : kOob;
+  for (int kl = 0; kl < KL; ++kl) kcol[kl] = (64 * kl + 16 * lg < (int)rk2) ? (uint32_t)(64 * kl + 16 * lg) : kOob;
   const uint32_t vlane = (uint32_t)lane * 16;
-  const int n_vl = NB * rv16;  // 1 KiB loads of a step's V' span: 32 NB tokens x rv x 2 bytes
+  // 1 KiB loads of a step's V' span: 32 NB tokens x rv elements (a last half load of an E4M3 span also
+  // brings rows of the next step; they land inside the staging region and are never read)
+  const int n_vl = ES == 2 ? NB * rv16 : (NB * rv16 + 1) / 2;
 
-  gq_u32x4 kreg[NB][2][M], vreg[NVL];
+  gq_u32x4 kreg[NB][2][KL], vreg[NVL];
   auto fetch_k = [&](int tok0) {
     const uint32_t row = (uint32_t)(tok0 + ln) * rk2;
 #pragma unroll
@@ -124,9 +147,9 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int ks = 0; ks < M; ++ks)
-          kreg[nb][j][ks] = __builtin_amdgcn_raw_buffer_load_b128(
-              k_rsrc, (int)(kcol[ks] + row + (uint32_t)(32 * nb + 16 * j) * rk2), 0, kGqaStream);
+        for (int kl = 0; kl < KL; ++kl)
+          kreg[nb][j][kl] = __builtin_amdgcn_raw_buffer_load_b128(
+              k_rsrc, (int)(kcol[kl] + row + (uint32_t)(32 * nb + 16 * j) * rk2), 0, kGqaStream);
   };
   auto fetch_v = [&](int tok0) {
     const uint32_t base = (uint32_t)tok0 * rv2 + vlane;
@@ -151,13 +174,27 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         GqFrag kf;
-        kf.u = kreg[nb][j][0];
-        st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0].v, gq_f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        if constexpr (ES == 2) {
+          kf.u = kreg[nb][j][0];
+          st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0].v, gq_f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
-        for (int ks = 1; ks < M; ++ks) {
-          if (ks >= rk32) break;
-          kf.u = kreg[nb][j][ks];
-          st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[ks].v, st[nb][j], 0, 0, 0);
+          for (int ks = 1; ks < M; ++ks) {
+            if (ks >= rk32) break;
+            kf.u = kreg[nb][j][ks];
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[ks].v, st[nb][j], 0, 0, 0);
+          }
+        } else {
+          st[nb][j] = gq_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kl = 0; kl < KL; ++kl) {
+            if (64 * kl >= rk) break;
+            gq_u32x4 lo, hi;
+            gq_widen16(kreg[nb][j][kl], lo, hi);
+            kf.u = lo;
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[2 * kl].v, st[nb][j], 0, 0, 0);
+            kf.u = hi;
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[2 * kl + 1].v, st[nb][j], 0, 0, 0);
+          }
         }
       }
     __builtin_amdgcn_sched_barrier(0);
@@ -213,7 +250,16 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
     gq_lds_order();   // the previous step's transposing reads come first
 #pragma unroll
     for (int i = 0; i < NVL; ++i)
-      if (i < n_vl) *reinterpret_cast<gq_u32x4*>(&lds[(i * 64 + lane) * 8]) = vreg[i];
+      if (i < n_vl) {
+        if constexpr (ES == 2) {
+          *reinterpret_cast<gq_u32x4*>(&lds[(i * 64 + lane) * 8]) = vreg[i];
+        } else {   // sixteen codes -> sixteen bf16, same row-major order
+          gq_u32x4 lo, hi;
+          gq_widen16(vreg[i], lo, hi);
+          *reinterpret_cast<gq_u32x4*>(&lds[(i * 64 + lane) * 16]) = lo;
+          *reinterpret_cast<gq_u32x4*>(&lds[(i * 64 + lane) * 16 + 8]) = hi;
+        }
+      }
     __builtin_amdgcn_sched_barrier(0);
     fetch_v(tok0 + BT);   // the V' registers are free again
     __builtin_amdgcn_sched_barrier(0);
@@ -262,9 +308,10 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
   }
 }
 
+template <typename TC>
 __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
     const DecWorker* __restrict__ workers, const DecTile* __restrict__ wtiles, const float* __restrict__ q_lat,
-    const uint16_t* __restrict__ kc, const uint16_t* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
+    const TC* __restrict__ kc, const TC* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
     float* __restrict__ partials, int n_workers, const int32_t* __restrict__ planned_len,
     const int32_t* __restrict__ seq_len) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_all[kGqaWaves][kGqaLdsElems];
@@ -281,10 +328,10 @@ __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
     td.len = dec_tile_len(td, planned_len, seq_len);
     const int rmax = max(td.rk_rv & 0xffff, td.rk_rv >> 16);
     switch ((rmax + 31) / 32) {
-      case 1: gqa_tile<1>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
-      case 2: gqa_tile<2>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
-      case 3: gqa_tile<3>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
-      case 4: gqa_tile<4>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
+      case 1: gqa_tile<1, TC>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
+      case 2: gqa_tile<2, TC>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
+      case 3: gqa_tile<3, TC>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
+      case 4: gqa_tile<4, TC>(td, q_lat, kc, vc, scale_log2, o_lat, partials, lds, lane); break;
       default: break;
     }
     if (++i >= count) break;
@@ -294,17 +341,23 @@ __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
 
 fdc_status decode_gqa_workers_per_cu(int* waves) {
   int nb = 0;
-  FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_gqa_tiles_kernel, kGqaWaves * 64, 0));
+  FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_gqa_tiles_kernel<uint16_t>, kGqaWaves * 64, 0));
   *waves = std::max(nb, 1) * kGqaWaves;
   return FDC_OK;
 }
 
-fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const uint16_t* kc,
-                             const uint16_t* vc, float scale, float* o_lat, float* partials, int n_workers,
+fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const void* kc,
+                             const void* vc, bool e4m3, float scale, float* o_lat, float* partials, int n_workers,
                              const int32_t* planned_len, const int32_t* seq_len, hipStream_t st) {
   const dim3 grid((n_workers + kGqaWaves - 1) / kGqaWaves), block(kGqaWaves * 64);
-  hipLaunchKernelGGL(decode_gqa_tiles_kernel, grid, block, 0, st, heads, wtiles, q_lat, kc, vc, scale * kGqaLog2e,
-                     o_lat, partials, n_workers, planned_len, seq_len);
+  if (e4m3)
+    hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles, q_lat,
+                       static_cast<const uint8_t*>(kc), static_cast<const uint8_t*>(vc), scale * kGqaLog2e, o_lat,
+                       partials, n_workers, planned_len, seq_len);
+  else
+    hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles, q_lat,
+                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), scale * kGqaLog2e, o_lat,
+                       partials, n_workers, planned_len, seq_len);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

@@ -117,8 +117,8 @@ fdc_status decode_gqa_workers_per_cu(int* waves);
 #ifdef __HIPCC__
 #include <hip/hip_runtime.h>
 namespace fdc {
-fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const uint16_t* kc,
-                             const uint16_t* vc, float scale, float* o_lat, float* partials, int n_workers,
+fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const void* kc,
+                             const void* vc, bool e4m3, float scale, float* o_lat, float* partials, int n_workers,
                              const int32_t* planned_len, const int32_t* seq_len, hipStream_t st);
 }
 #endif

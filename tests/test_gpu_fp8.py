@@ -78,18 +78,21 @@ def test_projection_stores_the_oracles_codes(T):
     say(f"  {n_total} codes, {n_off} one code apart, {sat} saturated")
 
 
+@pytest.mark.parametrize("g", [1, 4, 16])
 @pytest.mark.parametrize("W,granule,min_split", [(1, 64, 1), (37, 64, 1), (700, 32, 2)])
-def test_decode_attention_on_e4m3_codes(W, granule, min_split):
+def test_decode_attention_on_e4m3_codes(W, granule, min_split, g):
+    """Multi-head (g = 1) and grouped-query decode over E4M3 codes, every rank class on both sides."""
+    from oracle import gqa as og
     rk = [16, 32, 48, 64, 80, 96, 112, 128]
     rv = [128, 16, 112, 32, 96, 48, 64, 80]
     H, d_h = len(rk), 128
     seq = [0, 1, 63, 257, 1500, 700]
     B, S = len(seq), max(seq)
-    say(f"decode W={W} granule={granule} min_split={min_split}")
-    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], B, S, fdc.FDC_FP8)
+    say(f"decode g={g} W={W} granule={granule} min_split={min_split}")
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], B, S, fdc.FDC_FP8, q_per_kv=g)
     t = lay.tables()
     RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
-    g = gen.make_rng(17 * W + granule)
+    rng = gen.make_rng(17 * W + granule + g)
     # codes of latent rows with the decaying spectrum of the workloads, scaled into the format's range
     kcodes = np.zeros(B * S * RK, dtype=np.uint8)
     vcodes = np.zeros(B * S * RV, dtype=np.uint8)
@@ -97,15 +100,15 @@ def test_decode_attention_on_e4m3_codes(W, granule, min_split):
     ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
     for b, n in enumerate(seq):
         for h in range(H):
-            kq = fp8.quantise_latent(gen.direct_latent(n, rk[h], 32.0, g) * 6.0)
-            vq = fp8.quantise_latent(gen.direct_latent(n, rv[h], 32.0, g) * 100.0)
+            kq = fp8.quantise_latent(gen.direct_latent(n, rk[h], 32.0, rng) * 6.0)
+            vq = fp8.quantise_latent(gen.direct_latent(n, rv[h], 32.0, rng) * 100.0)
             Ks[b, h], Vs[b, h] = fp8.e4m3_decode(kq), fp8.e4m3_decode(vq)
             k0, v0 = b * S * RK + S * ko[h], b * S * RV + S * vo[h]
             kcodes[k0:k0 + n * rk[h]] = kq.ravel()
             vcodes[v0:v0 + n * rv[h]] = vq.ravel()
     kc, vc = torch.from_numpy(kcodes).cuda(), torch.from_numpy(vcodes).cuda()
-    q_lat = torch.from_numpy((g.standard_normal((B, RK)) * 0.5).astype(np.float32)).cuda()
-    o_lat = torch.full((B, RV), float("nan"), dtype=torch.float32, device="cuda:0")
+    q_lat = torch.from_numpy((rng.standard_normal((B, g * RK)) * 0.5).astype(np.float32)).cuda()
+    o_lat = torch.full((B, g * RV), float("nan"), dtype=torch.float32, device="cuda:0")
     pp = fdc.fdc_plan_params_default()
     pp.n_workers, pp.granule, pp.min_split = W, granule, min_split
     plan = fdc.fdc_plan_decode(lay, 0, seq, pp)
@@ -115,34 +118,23 @@ def test_decode_attention_on_e4m3_codes(W, granule, min_split):
         fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
     torch.cuda.synchronize()
     out = o_lat.cpu().numpy().astype(np.float64)
-    q64 = q_lat.cpu().numpy().astype(np.float64)
+    # the grouped kernel feeds q' to the matrix core as bf16
+    q64 = (q_lat if g == 1 else q_lat.to(BF)).to(torch.float64).cpu().numpy()
+    qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     got_all, ref_all = [], []
     for b, n in enumerate(seq):
-        for h in range(H):
-            got = out[b, vo[h]:vo[h + 1]]
+        for hq in range(H * g):
+            h = hq // g
+            got = out[b, oo[hq]:oo[hq + 1]]
             if n == 0:
                 assert not got.any()
                 continue
-            ref = oa.latent_attn_decode(q64[b, ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale)
+            ref = oa.latent_attn_decode(q64[b, qo[hq]:qo[hq + 1]], Ks[b, h], Vs[b, h], scale)
             # values reach +-448: the absolute bound scales with the largest value a head can output
-            assert_close(got / 100.0, ref / 100.0, f"b={b} h={h} n={n}")
+            assert_close(got / 100.0, ref / 100.0, f"b={b} hq={hq} n={n}")
             got_all.append(got), ref_all.append(ref)
     ma, rl = assert_close(np.concatenate(got_all) / 100.0, np.concatenate(ref_all) / 100.0, "all")
     say(f"  tiles={plan.export()['n_items']} max_abs/100={ma:.2e} rel_l2={rl:.2e}")
-
-
-def test_grouped_query_decode_refuses_an_e4m3_layout():
-    layg = fdc.Layout(1, 2, 64, 32, [[16, 32]], [[16, 16]], 2, 128, fdc.FDC_FP8, q_per_kv=2)
-    pp = fdc.fdc_plan_params_default()
-    pp.n_workers = 4
-    pland = fdc.fdc_plan_decode(layg, 0, [5, 7], pp)
-    wsd = workspace_for(pland)
-    kc = torch.zeros(2 * 128 * 48, dtype=torch.uint8, device="cuda:0")
-    vc = torch.zeros(2 * 128 * 32, dtype=torch.uint8, device="cuda:0")
-    ql = torch.zeros(2, 96, dtype=torch.float32, device="cuda:0")
-    ol = torch.zeros(2, 64, dtype=torch.float32, device="cuda:0")
-    with pytest.raises(fdc.FdcError):
-        fdc.fdc_latent_attn_decode(layg, pland, ql, kc, vc, 0.1, ol, wsd)
 
 
 @pytest.mark.parametrize("g", [1, 2])
