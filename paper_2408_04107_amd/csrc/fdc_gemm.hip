@@ -589,6 +589,37 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     uint16_t* cbase = static_cast<uint16_t*>((g.mode == kProject && side) ? g.C2 : g.C);
     const bool wide = g.mode == kProject || g.ldc % 8 == 0;
+    if (g.mode == kProject && g.cache_fp8) {
+      // E4M3 cache: the same transposition with one byte per element. Four accumulators become four
+      // codes (saturated, rounded from the fp32 value) in one LDS word; a lane then scatters the eight
+      // codes of its chunk with one 8-byte store.
+      uint8_t* ep8 = reinterpret_cast<uint8_t*>(ep);
+      uint8_t* cb8 = reinterpret_cast<uint8_t*>(cbase);
+      auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+              const int i = 2 * h + ii;
+              uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[i][j][gq * 4 + 0]), sat(acc[i][j][gq * 4 + 1]), 0u, false);
+              w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[i][j][gq * 4 + 2]), sat(acc[i][j][gq * 4 + 3]), w, true);
+              *reinterpret_cast<uint32_t*>(&ep8[(ii * 32 + lane % 32) * EROW + j * 32 + gq * 8 + (lane / 32) * 4]) = w;
+            }
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+          const int row = it * 8 + lane / 8;
+          const int m = m0 + wm + h * 64 + row;
+          const uint2 v = *reinterpret_cast<const uint2*>(&ep8[row * EROW + c * 8]);
+          if (m >= M || n >= N) continue;
+          *reinterpret_cast<uint2*>(cb8 + (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank) = v;
+        }
+      }
+      return;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
@@ -1033,7 +1064,7 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     else if (c_f32) launch_skinny<uint16_t, float>(a, st);
     else launch_skinny<uint16_t, uint16_t>(a, st);
   } else if (!a_f32 && groups == 1 && (a.mode == kPlain || a.mode == kProject) && a.K % 8 == 0 && a.lda % 8 == 0 &&
-             a.ldb % 8 == 0 && !(a.mode == kProject && a.cache_fp8)) {  // its scatter epilogue packs bf16 pairs
+             a.ldb % 8 == 0) {
     GemmArgs b = a;
     b.nt = (a.N + DN - 1) / DN;
     const int tiles = b.nt * ((a.M + DM - 1) / DM);
