@@ -322,3 +322,43 @@ def test_paged_decode_on_e4m3_codes():
                 continue
             ref = oa.latent_attn_decode(q64[b, ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale)
             assert_close(got / 50.0, ref / 50.0, f"paged b={b} h={h}")
+
+
+def test_decode_on_e4m3_codes_at_config3_size_sampled_units():
+    """Layer 0 of the adaptive-rank decode config (batch 16, context 8192, 32 heads) with an E4M3 cache, in the
+    launch configuration bench.py times (fdc_suggest_workers(3)): random finite codes on the device, the
+    oracle on ~60 sampled (sequence, head) units including the narrowest and the widest head."""
+    wl = gen.CONFIGS["c3_adaptive_decode"]
+    r = wl.ranks()[0].tolist()
+    H, B, S, d_h = wl.n_heads, wl.batch, wl.context, wl.d_head
+    W = fdc.fdc_suggest_workers(3)
+    say(f"config 3 layer 0, E4M3: B={B} S={S} W={W}")
+    lay = fdc.Layout(1, H, wl.d_model, d_h, [r], [r], B, S, fdc.FDC_FP8)
+    R = sum(r)
+    tg = torch.Generator(device="cuda:0").manual_seed(3)
+    mk = lambda: torch.randint(0, 0x7F, (B * S * R,), generator=tg, device="cuda:0", dtype=torch.uint8) | \
+        (torch.randint(0, 2, (B * S * R,), generator=tg, device="cuda:0", dtype=torch.uint8) << 7)
+    kc, vc = mk(), mk()
+    rng = gen.make_rng(8)
+    # codes are uniform over the grid, so values reach 448: small queries keep the scores in a softmax's range
+    q_lat = torch.from_numpy((rng.standard_normal((B, R)) * 0.01).astype(np.float32)).cuda()
+    o_lat = torch.full((B, R), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = W
+    plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(o_lat).any()
+    units = {(int(b), int(h)) for b, h in zip(rng.integers(0, B, 60), rng.integers(0, H, 60))}
+    units |= {(0, int(np.argmax(r))), (B - 1, int(np.argmin(r)))}
+    off = np.concatenate([[0], np.cumsum(r)])
+    out, q64 = o_lat.cpu().numpy().astype(np.float64), q_lat.cpu().numpy().astype(np.float64)
+    for b, h in sorted(units):
+        k0 = b * S * R + S * off[h]
+        K = fp8.e4m3_decode(kc[k0:k0 + S * r[h]].cpu().numpy()).reshape(S, r[h])
+        V = fp8.e4m3_decode(vc[k0:k0 + S * r[h]].cpu().numpy()).reshape(S, r[h])
+        ref = oa.latent_attn_decode(q64[b, off[h]:off[h + 1]], K, V, scale)
+        assert_close(out[b, off[h]:off[h + 1]] / 100.0, ref / 100.0, f"b={b} h={h} r={r[h]}")
+    say(f"  tiles={plan.export()['n_items']} units checked={len(units)}")
