@@ -560,13 +560,21 @@ def main():
         line["cpu_baseline"] = cpu_baseline(state)
     del state
     torch.cuda.empty_cache()
+    # side measurements of the other rows: a failure in one of them is reported in its place and does
+    # not take the headline line with it
+    def side(name, fn):
+        try:
+            torch.cuda.empty_cache()
+            line[name] = fn()
+        except Exception as exc:   # noqa: BLE001
+            line[name] = {"error": f"{type(exc).__name__}: {exc}"}
+            print(f"bench.py: {name} failed: {exc}", file=sys.stderr)
     if not args.no_prefill:
-        line["prefill"] = run_prefill_workload(fdc, gen)
+        side("prefill", lambda: run_prefill_workload(fdc, gen))
     if not args.no_gqa:
-        line["gqa_decode"] = run_gqa_decode_workload(fdc, gen)
+        side("gqa_decode", lambda: run_gqa_decode_workload(fdc, gen))
     if not args.no_fp8:
-        torch.cuda.empty_cache()
-        line["fp8_decode"] = run_fp8_decode_workload(fdc, gen, wl)
+        side("fp8_decode", lambda: run_fp8_decode_workload(fdc, gen, wl))
     print(json.dumps(line))
 
 
