@@ -372,6 +372,80 @@ __global__ __launch_bounds__(64) void absorb_query_small_kernel(const GemmArgs g
   absorb_query_small_body<TC>(g, blockIdx.x, blockIdx.y, threadIdx.x);
 }
 
+// ---- per-head products with many rows (prefill query absorption, the fold of B_v into W_o) -------
+// K = d_head <= 128 and N = rank <= 128: 1 flop per 2 bytes, a stream over A (read once) and C
+// (written once). A workgroup takes 256 rows of one head: the head's B rows (at most 128 x 128) go
+// to LDS once, each of the four waves loads the A fragments of its four 16-row tiles straight from
+// global memory in MFMA layout (a row's 2 K bytes are contiguous, so the four k-steps of a tile use
+// whole lines) and walks the head's column tiles with a B fragment in registers shared by its four
+// row tiles. The product is taken transposed (B rows first), which leaves a lane with four
+// consecutive columns of one output row: one 8- or 16-byte store.
+constexpr int kRowsBRow = 128 + 16;   // LDS row of the B tile: 18 chunks, conflict-free fragment reads
+constexpr int kRowsPerWg = 256;
+
+template <typename TC>
+__global__ __launch_bounds__(256) void grouped_rows_kernel(const GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRowsBRow];
+  const Group gr = group_of(g, blockIdx.y);
+  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64, ln = lane % 16, lg = lane / 16;
+  const uint16_t* A = static_cast<const uint16_t*>(g.A) + gr.a_off;
+  const uint16_t* B = static_cast<const uint16_t*>(g.B) + gr.b_off;
+  const int ksteps = (g.K + 31) / 32;
+  // the head's B rows: N rows of K elements, K / 8 chunks of 16 bytes each; columns K .. 128 are never read
+  {
+    const int cpr = g.K / 8;
+    for (int i = tid; i < gr.N * cpr; i += 256) {
+      const int r = i / cpr, c = i - r * cpr;
+      *reinterpret_cast<u32x4*>(&lds_b[r * kRowsBRow + c * 8]) = *reinterpret_cast<const u32x4*>(B + (int64_t)r * g.ldb + c * 8);
+    }
+  }
+  // A fragments of the wave's four row tiles: lane (ln, lg) holds k = 32 ks + 8 lg .. + 8 of row ln
+  const int row0 = blockIdx.x * kRowsPerWg + wave * 64;
+  const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<uint16_t*>(A), 0, (int)(((int64_t)(g.M - 1) * g.lda + g.K) * 2), 0x00020000);
+  union Fr { u32x4 u; bf16x8 v; };
+  Fr af[4][4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int row = row0 + 16 * t + ln, col = 32 * ks + 8 * lg;
+      af[t][ks].u = __builtin_amdgcn_raw_buffer_load_b128(
+          a_rsrc, (int)((row < g.M && col < g.K) ? (uint32_t)(((int64_t)row * g.lda + col) * 2) : 0x80000000u), 0, 2);
+    }
+  __syncthreads();
+  TC* C = static_cast<TC*>(g.C) + gr.c_off;
+  for (int n0 = 0; n0 < gr.N; n0 += 16) {
+    f32x4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks >= ksteps) break;
+      Fr b;
+      const int col = 32 * ks + 8 * lg;
+      b.u = col < g.K ? *reinterpret_cast<const u32x4*>(&lds_b[(n0 + ln) * kRowsBRow + col]) : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b.v, af[t][ks].v, acc[t], 0, 0, 0);
+    }
+    // register e of lane l: column n0 + 4 * (l / 16) + e of row l % 16
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int row = row0 + 16 * t + ln;
+      if (row >= g.M) continue;
+      TC* dst = C + (int64_t)row * g.ldc + n0 + 4 * lg;
+      if constexpr (sizeof(TC) == 4) {
+        *reinterpret_cast<f32x4*>(dst) = acc[t];
+      } else {
+        uint2 w;
+        w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
+        w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
+        *reinterpret_cast<uint2*>(dst) = w;
+      }
+    }
+  }
+}
+
 // ---- bf16 MFMA kernel for the large products (prefill: M = tokens of the batch) ----------------
 // Workgroup tile 256 x 256, k stage 64, eight waves in a 2 x 4 grid, each wave 128 x 64 as 4 x 2
 // v_mfma_f32_32x32x16_bf16 tiles. Both operands go from global memory straight into LDS
@@ -1053,6 +1127,11 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     const dim3 grid((n_max + 15) / 16, groups);
     if (c_f32) hipLaunchKernelGGL(absorb_query_small_kernel<float>, grid, dim3(64), 0, st, a);
     else hipLaunchKernelGGL(absorb_query_small_kernel<uint16_t>, grid, dim3(64), 0, st, a);
+  } else if ((a.mode == kAbsorbQuery || a.mode == kFold) && !a_f32 && a.K <= 128 && a.K % 8 == 0 && n_max <= 128 &&
+             a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldc % 4 == 0) {
+    const dim3 grid((a.M + kRowsPerWg - 1) / kRowsPerWg, groups);
+    if (c_f32) hipLaunchKernelGGL(grouped_rows_kernel<float>, grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(grouped_rows_kernel<uint16_t>, grid, dim3(256), 0, st, a);
   } else if (a.M <= 16 && (a.mode == kPlain || a.mode == kProject)) {
     if (a_f32 && c_f32) launch_skinny16<float, float>(a, st);
     else if (a_f32) launch_skinny16<float, uint16_t>(a, st);
