@@ -1029,22 +1029,21 @@ static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
 }
 
 // ---- post-RoPE compression (Section 5.1: RoPE, then the rotation R truncated to r_h columns) ----
-// One workgroup = 64 token rows of one head. The pre-RoPE rows are rotated pair-wise in fp32 while
-// they are staged (pairs (2i, 2i+1), angles from the caller's cos / sin tables), rounded to bf16 and
-// multiplied with the head's R_t rows (r_h x d_head, K = d_head <= 128, so the whole product is one
-// LDS stage and 4 k-steps of v_mfma_f32_16x16x32_bf16). Queries go to q_lat, keys into the K' cache.
-constexpr int kRopeRows = 64;
-// 17 chunks per row: the fragment reads take a two-way bank conflict (see kSkinnyRow), but with 18
-// chunks only two workgroups instead of three fit a compute unit and the kernel was 30 % slower.
-constexpr int kRopeLdsRow = 128 + 8;
+// One workgroup = 256 token rows of one head, laid out like grouped_rows_kernel: the head's R_t rows
+// (r_h x d_head, K = d_head <= 128) go to LDS once, every wave loads the rows of its four 16-row tiles
+// straight into MFMA fragments, and a lane's eight consecutive k are four RoPE pairs (2i, 2i+1), so
+// the rotation is done in the lane's registers in fp32 (angles from the caller's cos / sin tables at
+// the row's position) and the result rounded to bf16 is the operand. The product is taken transposed:
+// a lane ends up with four consecutive latent columns of one token, stored at once. Queries go to
+// q_lat, keys into the K' cache (bf16 or E4M3 codes).
+constexpr int kRopeRows = 256;
 
 template <typename TC, bool KEYS>
 __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_a[kRopeRows * kRopeLdsRow];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRopeLdsRow];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRowsBRow];
   // blockIdx.y is the head of the input rows: a key/value head for keys, a query head for queries
   // (which then uses the rotation of key/value head hx / G and its own columns of q_lat)
-  const int hx = blockIdx.y, t0 = blockIdx.x * kRopeRows;
+  const int hx = blockIdx.y;
   const int h = KEYS ? hx : hx / g.G, jq = KEYS ? 0 : hx % g.G;
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
@@ -1052,55 +1051,84 @@ __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
   const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)hx * g.d_head;  // row stride lda = heads * d_head
   const uint16_t* Rt = static_cast<const uint16_t*>(g.B) + (int64_t)g.koff_r[h] * g.d_head;
   const int half = g.d_head / 2;
-  // stage A with RoPE: 64 rows x 16 chunks of 8 elements
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + 256 * i, row = c / 16, kc = c % 16;
-    u32x4 out = {0, 0, 0, 0};
-    if (t0 + row < g.M && kc * 8 < g.d_head) {
-      const u32x4 raw = *reinterpret_cast<const u32x4*>(X + (int64_t)(t0 + row) * g.lda + kc * 8);
-      const int pos = min(max(g.tok_pos[t0 + row], 0), g.n_pos - 1);
-      const float4 cs = *reinterpret_cast<const float4*>(g.rope_cos + (int64_t)pos * half + kc * 4);
-      const float4 sn = *reinterpret_cast<const float4*>(g.rope_sin + (int64_t)pos * half + kc * 4);
-      const float cc[4] = {cs.x, cs.y, cs.z, cs.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float xe = __uint_as_float(raw[j] << 16), xo = __uint_as_float(raw[j] & 0xffff0000u);
-        out[j] = cvt_pk_bf16(xe * cc[j] - xo * ss[j], xe * ss[j] + xo * cc[j]);
-      }
+  {
+    const int cpr = g.d_head / 8;
+    for (int i = tid; i < r * cpr; i += 256) {
+      const int row = i / cpr, c = i - row * cpr;
+      *reinterpret_cast<u32x4*>(&lds_b[row * kRowsBRow + c * 8]) = *reinterpret_cast<const u32x4*>(Rt + (int64_t)row * g.d_head + c * 8);
     }
-    *reinterpret_cast<u32x4*>(&lds_a[row * kRopeLdsRow + kc * 8]) = out;
   }
-  // stage B: the head's kept directions, 128 rows x 16 chunks (rows >= r and columns >= d_head are zero)
+  const int row0 = blockIdx.x * kRopeRows + wave * 64;
+  union Fr { u32x4 u; bf16x8 v; };
+  Fr af[4][4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int c = tid + 256 * i, row = c / 16, kc = c % 16;
-    const u32x4 v = (row < r && kc * 8 < g.d_head) ? *reinterpret_cast<const u32x4*>(Rt + (int64_t)row * g.d_head + kc * 8)
-                                                   : u32x4{0, 0, 0, 0};
-    *reinterpret_cast<u32x4*>(&lds_b[row * kRopeLdsRow + kc * 8]) = v;
+  for (int t = 0; t < 4; ++t) {
+    const int row = row0 + 16 * t + ln;
+    const bool row_on = row < g.M;
+    const int pos = row_on ? min(max(g.tok_pos[row], 0), g.n_pos - 1) : 0;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int col = 32 * ks + 8 * lg;
+      u32x4 out = {0, 0, 0, 0};
+      if (row_on && col < g.d_head) {
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(X + (int64_t)row * g.lda + col);
+        const float4 cs = *reinterpret_cast<const float4*>(g.rope_cos + (int64_t)pos * half + col / 2);
+        const float4 sn = *reinterpret_cast<const float4*>(g.rope_sin + (int64_t)pos * half + col / 2);
+        const float cc[4] = {cs.x, cs.y, cs.z, cs.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float xe = __uint_as_float(raw[j] << 16), xo = __uint_as_float(raw[j] & 0xffff0000u);
+          out[j] = cvt_pk_bf16(xe * cc[j] - xo * ss[j], xe * ss[j] + xo * cc[j]);
+        }
+      }
+      af[t][ks].u = out;
+    }
   }
   __syncthreads();
   const int ksteps = (g.d_head + 31) / 32;
-  for (int nt = 0; nt < r / 16; ++nt) {
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < ksteps; ++ks) {
-      union { u32x4 u; bf16x8 v; } a, b;
-      a.u = *reinterpret_cast<const u32x4*>(&lds_a[(16 * wave + ln) * kRopeLdsRow + 32 * ks + 8 * lg]);
-      b.u = *reinterpret_cast<const u32x4*>(&lds_b[(16 * nt + ln) * kRopeLdsRow + 32 * ks + 8 * lg]);
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, acc, 0, 0, 0);
-    }
-    // register e of lane l is row 4 * (l / 16) + e, column l % 16
-    const int n = 16 * nt + ln;
+  for (int n0 = 0; n0 < r; n0 += 16) {
+    f32x4 acc[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int t = t0 + 16 * wave + 4 * lg + e;
-      if (t >= g.M) continue;
+    for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      if (ks >= ksteps) break;
+      Fr bq;
+      const int col = 32 * ks + 8 * lg;
+      bq.u = col < g.d_head ? *reinterpret_cast<const u32x4*>(&lds_b[(n0 + ln) * kRowsBRow + col]) : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq.v, af[t][ks].v, acc[t], 0, 0, 0);
+    }
+    // register e of lane l: latent column n0 + 4 * (l / 16) + e of token row l % 16
+    const int n = n0 + 4 * lg;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int tok = row0 + 16 * t + ln;
+      if (tok >= g.M) continue;
       if constexpr (KEYS) {
-        const int64_t dst = (int64_t)g.tok_batch[t] * g.max_seq * g.RK + (int64_t)g.max_seq * g.koff_r[h] +
-                            (int64_t)g.tok_pos[t] * r + n;
-        store_cache(g, g.C, dst, acc[e]);
+        const int64_t dst = (int64_t)g.tok_batch[tok] * g.max_seq * g.RK + (int64_t)g.max_seq * g.koff_r[h] +
+                            (int64_t)g.tok_pos[tok] * r + n;
+        if (g.cache_fp8) {
+          auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
+          uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][0]), sat(acc[t][1]), 0u, false);
+          w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][2]), sat(acc[t][3]), w, true);
+          *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(g.C) + dst) = w;
+        } else {
+          uint2 w;
+          w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
+          w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.C) + dst) = w;
+        }
       } else {
-        store_out(static_cast<TC*>(g.C) + (int64_t)t * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n, acc[e]);
+        TC* dst = static_cast<TC*>(g.C) + (int64_t)tok * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n;
+        if constexpr (sizeof(TC) == 4) {
+          *reinterpret_cast<f32x4*>(dst) = acc[t];
+        } else {
+          uint2 w;
+          w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
+          w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
+          *reinterpret_cast<uint2*>(dst) = w;
+        }
       }
     }
   }
