@@ -295,3 +295,26 @@ def test_config5_size_projection_and_apply_sampled_rows():
     ma, rl = assert_close(f64(y[rows_t]), y_ref, "config 5 y rows")
     say(f"  apply max_abs={ma:.2e} rel_l2={rl:.2e}")
     assert torch.isfinite(y.float()).all().item()
+
+
+def test_project_and_absorb_query_with_values_only():
+    """k_cache = NULL (post-RoPE path: only V' comes from the projection): same V' rows and queries as the two calls."""
+    H, d, d_h, rk, rv, T = 4, 1000, 64, [64, 16, 48, 32], [16, 64, 64, 48], 11
+    B, S = 2, 50
+    lay = fdc.Layout(1, H, d, d_h, [rk], [rv], B, S, fdc.FDC_BF16)
+    two, one = Cache(lay), Cache(lay)
+    g = gen.make_rng(321)
+    x = dev(gen.hidden_states(T, d, g), torch.bfloat16)
+    A_v_t = dev(g.standard_normal((two.RV, d)) / math.sqrt(d), torch.bfloat16)
+    q = dev(g.standard_normal((T, H, d_h)), torch.bfloat16)
+    Bk = dev(g.standard_normal((two.RK, d_h)) / math.sqrt(d_h), torch.bfloat16)
+    slots = g.permutation(B * S)[:T]
+    tb, tp = dev(slots // S, torch.int32), dev(slots % S, torch.int32)
+    q_two = torch.full((T, two.RK), float("nan"), dtype=torch.float32, device="cuda:0")
+    q_one = torch.full_like(q_two, float("nan"))
+    fdc.fdc_project_latent_kv(lay, 0, x, tb, tp, A_v_t, None, two.v)
+    fdc.fdc_absorb_query(lay, 0, q, Bk, q_two, fdc.FDC_F32)
+    fdc.fdc_project_and_absorb_query(lay, 0, x, tb, tp, A_v_t, None, one.v, q, Bk, q_one, fdc.FDC_F32)
+    torch.cuda.synchronize()
+    assert torch.equal(one.v, two.v) and one.v.float().abs().sum() > 0
+    assert not one.k.any() and torch.equal(q_one, q_two)
