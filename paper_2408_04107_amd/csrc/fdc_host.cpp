@@ -258,13 +258,23 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
   struct Piece { int32_t b, h, t0, t1, w; };
   std::vector<Piece> pieces;
   const int64_t mean = ceil_div(total, W);
-  LoadHeap heap = empty_workers(W);
+  // Least-loaded worker, ties to the lowest id. Every piece has a positive cost, so a worker that has
+  // been given one never ties with an untouched one: until all W have been touched the answer is the
+  // next untouched worker, and only the touched ones need the heap (same order, a third of the work).
+  LoadHeap heap;
+  int32_t next_fresh = 0;
+  pieces.reserve(chunks.size() + (size_t)W);
   for (int32_t ci : order) {
     const Chunk& c = chunks[ci];
     int64_t t0 = c.t0;
     while (t0 < c.t1) {
-      Load top = heap.top();
-      heap.pop();
+      Load top;
+      if (next_fresh < W) {
+        top = {0, next_fresh++};
+      } else {
+        top = heap.top();
+        heap.pop();
+      }
       int64_t take = c.t1 - t0;
       if (pr->split) {
         const int64_t room = mean - top.first, step = G * d_sum[c.h];
