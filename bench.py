@@ -501,6 +501,49 @@ def run_fp8_decode_workload(fdc, gen, wl, iters=12):
             "cached_tokens_per_us": B * S / tile}
 
 
+def run_device_planner(fdc, gen, wl, iters=5):
+    """Re-planning every layer of the decode workload on the GPU (one workgroup per layer, one launch)
+    beside the host planner on one core: what a re-plan costs once per `granule` decode steps."""
+    import torch
+    dev = "cuda:0"
+    ranks = wl.ranks()
+    L, H, B, S = wl.n_layers, wl.n_heads, wl.batch, wl.context
+    lay = fdc.Layout(L, H, wl.d_model, wl.d_head, ranks, ranks, B, S, fdc.FDC_BF16)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(0), wl.min_split
+    plans, wss = [], []
+    for l in range(L):
+        plan = fdc.fdc_plan_decode_device(lay, l, B, 0, pp)
+        ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + plan.workspace_bytes()]
+        fdc.fdc_plan_upload(plan, ws)
+        plans.append(plan), wss.append(ws)
+    seq = torch.full((B,), S, dtype=torch.int32, device=dev)
+    per_launch = 32
+    groups = [(plans[i:i + per_launch], wss[i:i + per_launch]) for i in range(0, L, per_launch)]
+    run = lambda: [fdc.fdc_plan_decode_run(p, w, seq) for p, w in groups]
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    dev_ms = e0.elapsed_time(e1) / iters
+    fdc.fdc_plan_download(plans[0], wss[0])
+    t0 = time.perf_counter()
+    host = [fdc.fdc_plan_decode(lay, l, [S] * B, pp) for l in range(L)]
+    host_ms = (time.perf_counter() - t0) * 1e3
+    same = all(np.array_equal(plans[0].export()[k], host[0].export()[k])
+               for k in ("item_b", "item_h", "item_lo", "item_hi", "worker_ptr", "worker_items", "unit_item_ptr"))
+    return {"workload": "%s: all %d layers re-planned" % (wl.name, L), "n_workers": pp.n_workers,
+            "device_ms_all_layers": dev_ms, "host_one_core_ms_all_layers": host_ms,
+            "tiles_layer0": int(plans[0].export()["n_items"]), "layer0_tables_equal_host": bool(same),
+            "workspace_MB_per_layer": plans[0].workspace_bytes() / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -517,6 +560,7 @@ def main():
     ap.add_argument("--no-prefill", action="store_true")
     ap.add_argument("--no-gqa", action="store_true")
     ap.add_argument("--no-fp8", action="store_true")
+    ap.add_argument("--no-device-planner", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
@@ -575,6 +619,8 @@ def main():
         side("gqa_decode", lambda: run_gqa_decode_workload(fdc, gen))
     if not args.no_fp8:
         side("fp8_decode", lambda: run_fp8_decode_workload(fdc, gen, wl))
+    if not args.no_device_planner:
+        side("device_planner", lambda: run_device_planner(fdc, gen, wl))
     print(json.dumps(line))
 
 

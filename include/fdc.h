@@ -188,6 +188,39 @@ fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, c
                                   const int32_t* kv_len, const int32_t* block_table, int max_pages,
                                   const fdc_plan_params* params, fdc_plan** out);
 
+/* The decode planner as a GPU kernel (Section 6.1, implementation: the scheduling computations of
+ * the decode kernel, sorting included, run on the device). For callers whose sequence lengths live
+ * in device memory and who do not want a host round trip per re-plan (serving loops, captured
+ * graphs). The schedule and every table are those fdc_plan_decode / fdc_plan_decode_paged would
+ * produce for the same lengths, bit for bit.
+ *
+ * fdc_plan_decode_device (host only, no GPU work) sizes a plan for ANY lengths up to the layout's
+ * capacity: max_pages = 0 for the dense cache (seq_len[b] <= max_seq), max_pages > 0 for the paged
+ * cache of fdc_plan_decode_paged (seq_len[b] <= P * max_pages). Its workspace is larger than that
+ * of a host plan for one set of lengths (regions are sized by an upper bound on the tile count).
+ * Limits of the kernel (FDC_BAD_SHAPE beyond them; fdc_plan_decode has none): n_workers <= 8192,
+ * batch <= 2048, batch * n_heads * min_split <= 8192, worker loads below 2^29.
+ * Use: fdc_plan_upload once (constants), then fdc_plan_decode_run whenever the lengths change, then
+ * fdc_latent_attn_decode / _decode_at with (plan, workspace) as for a host plan.
+ *
+ * fdc_plan_decode_run launches one workgroup per plan (1 <= n_plans <= 32: e.g. the layers of a
+ * model, all for the same batch and cache shape), asynchronously on `stream`:
+ *   plans, workspaces  host arrays [n_plans]; workspaces[i] is the 256-byte aligned device workspace
+ *                      plans[i] was uploaded to (distinct per plan)
+ *   seq_len            device int32 [batch]; values outside [0, capacity] are planned clamped
+ *   block_table        device int32 [batch * max_pages] (paged plans; NULL otherwise); entries outside
+ *                      the layout's pages are replaced by page 0
+ * Both faults are recorded in the workspace and reported by fdc_plan_download; no kernel ever reads
+ * outside the cache because of them.
+ *
+ * fdc_plan_download (optional; synchronises `stream`) copies the tables back so that
+ * fdc_plan_export works on the plan, and returns FDC_BAD_SHAPE if the kernel recorded a fault. */
+fdc_status fdc_plan_decode_device(const fdc_layout* lay, int layer, int batch, int max_pages,
+                                  const fdc_plan_params* params, fdc_plan** out);
+fdc_status fdc_plan_decode_run(fdc_plan* const* plans, void* const* workspaces, int n_plans,
+                               const int32_t* seq_len, const int32_t* block_table, void* stream);
+fdc_status fdc_plan_download(fdc_plan* plan, const void* workspace, void* stream);
+
 /* Host view of a plan's tables (pointers stay valid until fdc_plan_destroy). An item is a decode
  * tile (lo, hi = token range) or a prefill task (lo, hi = query-row range). */
 typedef struct {

@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = [
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
     "fdc_rope_absorb_query", "fdc_rope_compress_keys", "fdc_project_and_absorb_query", "fdc_latent_attn_decode_at",
+    "fdc_plan_decode_device", "fdc_plan_decode_run", "fdc_plan_download",
 ]
 
 
@@ -79,6 +80,9 @@ def lib() -> C.CDLL:
         l.fdc_plan_prefill.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, C.POINTER(PlanParams), C.POINTER(vp)]
         l.fdc_plan_prefill_paged.argtypes = [vp, C.c_int, C.c_int, i32p, i32p, i32p, C.c_int, C.POINTER(PlanParams),
                                              C.POINTER(vp)]
+        l.fdc_plan_decode_device.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.POINTER(PlanParams), C.POINTER(vp)]
+        l.fdc_plan_decode_run.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, vp, vp, vp]
+        l.fdc_plan_download.argtypes = [vp, vp, vp]
         l.fdc_plan_export.argtypes = [vp, C.POINTER(PlanTables)]
         l.fdc_plan_workspace_bytes.argtypes = [vp]
         l.fdc_plan_workspace_bytes.restype = C.c_size_t
@@ -262,6 +266,28 @@ def fdc_plan_prefill_paged(layout: Layout, layer: int, q_len: Sequence[int], kv_
     _check(lib().fdc_plan_prefill_paged(layout.handle, layer, int(q.size), _p32(q), _p32(k), _p32(bt.reshape(-1)),
                                         int(bt.shape[1]), C.byref(params), C.byref(h)))
     return Plan(h, layout)
+
+
+def fdc_plan_decode_device(layout: Layout, layer: int, batch: int, max_pages: int, params: PlanParams) -> Plan:
+    """A decode plan whose tables the GPU computes (fdc_plan_decode_run). max_pages 0: dense cache."""
+    h = C.c_void_p()
+    _check(lib().fdc_plan_decode_device(layout.handle, layer, int(batch), int(max_pages), C.byref(params), C.byref(h)))
+    return Plan(h, layout)
+
+
+def fdc_plan_decode_run(plans: Sequence[Plan], workspaces, seq_len, block_table=None, stream=None) -> None:
+    """seq_len (and block_table for paged plans): int32 device tensors; one workspace per plan."""
+    n = len(plans)
+    if n != len(workspaces):
+        raise ValueError("one workspace per plan")
+    hs = (C.c_void_p * n)(*[p.handle for p in plans])
+    ws = (C.c_void_p * n)(*[_dev(w) for w in workspaces])
+    _check(lib().fdc_plan_decode_run(hs, ws, n, _dev(seq_len), _dev(block_table) if block_table is not None else None,
+                                     _stream(stream)))
+
+
+def fdc_plan_download(plan: Plan, workspace, stream=None) -> None:
+    _check(lib().fdc_plan_download(plan.handle, _dev(workspace), _stream(stream)))
 
 
 def fdc_plan_upload(plan: Plan, workspace, stream=None) -> None:

@@ -14,7 +14,8 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(PKG_DIR, "libfdc.so")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["fdc_host.cpp", "fdc_decode.hip", "fdc_decode_gqa.hip", "fdc_gemm.hip", "fdc_prefill.hip"]
+SOURCES = ["fdc_host.cpp", "fdc_decode.hip", "fdc_decode_gqa.hip", "fdc_gemm.hip", "fdc_prefill.hip",
+           "fdc_plan_device.hip"]
 
 COMMON_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
@@ -45,7 +46,7 @@ def build(verbose: bool = True) -> str:
     """Compiles every source and links paper_2408_04107_amd/libfdc.so. Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
-    with ThreadPoolExecutor(max_workers=min(5, len(srcs))) as ex:
+    with ThreadPoolExecutor(max_workers=min(6, len(srcs))) as ex:
         objs = list(ex.map(_compile, srcs))
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)

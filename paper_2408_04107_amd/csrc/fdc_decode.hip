@@ -510,7 +510,7 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   g_prof_start = g_prof_stop = nullptr;
   if (plan->G > 1 && lay->dtype == FDC_F32)
     FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
-  if (!plan->item_b.empty()) {
+  if (plan->on_device || !plan->item_b.empty()) {   // a device plan's tile count is not known here: empty workers return at once
     if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
     if (plan->G > 1) {
       fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat), k_cache, v_cache,

@@ -605,6 +605,8 @@ fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, c
 
 fdc_status fdc_plan_export(const fdc_plan* p, fdc_plan_tables* o) {
   if (!p || !o) FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_export: NULL argument");
+  if (p->on_device && !p->downloaded)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_export: the plan's tables are on the device; call fdc_plan_download first");
   o->kind = p->kind;
   o->n_items = (int32_t)p->item_b.size();
   o->n_workers = p->n_workers;

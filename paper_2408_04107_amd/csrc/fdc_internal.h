@@ -156,4 +156,11 @@ struct fdc_plan {
   size_t off_pages = 0;        // prefill over a paged cache: int32 page table [batch * max_pages], inside image
   size_t off_partials, partial_bytes;                             // decode only, after the image
   size_t workspace_bytes;
+  // Decode plans made on the device (fdc_plan_decode_device): the tables above stay empty until
+  // fdc_plan_download; `image` holds only the constants of the planner kernel, and the regions of the
+  // workspace are sized for n_max pieces, an upper bound known without the sequence lengths.
+  bool on_device = false, downloaded = false;
+  int64_t n_max = 0;
+  std::vector<int64_t> d_sum;   // per head, for item_cost after a download
+  size_t off_header = 0, off_export = 0, lds_bytes = 0;
 };

@@ -287,3 +287,37 @@ def test_error_codes_without_gpu():
     assert plan.workspace_bytes() % 4 == 0 and plan.workspace_bytes() > 0
     d = fdc.fdc_plan_params_default()
     assert (d.granule, d.min_split, d.split, d.br_base, d.br_cap, d.cost_mode, d.softmax_cost) == (64, 1, 1, 64, 256, 0, 1)
+
+
+def test_device_plan_creation_is_host_only_and_bounds_the_host_plan():
+    """fdc_plan_decode_device does no GPU work: it sizes the workspace for any lengths up to the
+    layout's capacity, so it must cover the host plan of the worst case; shapes beyond the planner
+    kernel's limits are refused with a pointer to the host planner."""
+    rk, rv = gen.adaptive_ranks(1, 32, 0)[0], gen.adaptive_ranks(1, 32, 1)[0]
+    lay = _layout([rk], [rv], 16, 8192)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 4096
+    dev = fdc.fdc_plan_decode_device(lay, 0, 16, 0, pp)
+    for seq in ([8192] * 16, [8192 - 63 * b for b in range(16)], [64] * 16):
+        host = fdc.fdc_plan_decode(lay, 0, seq, pp)
+        assert dev.workspace_bytes() >= host.workspace_bytes()
+    with pytest.raises(fdc.FdcError, match="download"):
+        dev.export()
+    pp.n_workers = 8193
+    with pytest.raises(fdc.FdcError, match="n_workers"):
+        fdc.fdc_plan_decode_device(lay, 0, 16, 0, pp)
+    pp.n_workers, pp.min_split = 4096, 64
+    with pytest.raises(fdc.FdcError, match="chunks"):
+        fdc.fdc_plan_decode_device(lay, 0, 16, 0, pp)
+    pp.min_split = 1
+    with pytest.raises(fdc.FdcError, match="batch"):
+        fdc.fdc_plan_decode_device(lay, 0, 17, 0, pp)
+    big = _layout([[128] * 4], [[128] * 4], 2, 1 << 22)
+    pp.n_workers = 1
+    with pytest.raises(fdc.FdcError, match="32-bit"):
+        fdc.fdc_plan_decode_device(big, 0, 2, 0, pp)
+    # paged: the page size must be a multiple of the granule
+    pages = _layout([rk], [rv], 64, 96)
+    pp.n_workers = 256
+    with pytest.raises(fdc.FdcError, match="multiple of the granule"):
+        fdc.fdc_plan_decode_device(pages, 0, 4, 8, pp)
