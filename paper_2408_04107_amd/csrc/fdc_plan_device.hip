@@ -308,11 +308,33 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(DevPlanLaunch
         const int64_t fresh_fit = split ? fit_tokens(0, step) : INT64_MAX;   // what an untouched worker takes
         const int first_k = k;
         while (t0 < t1) {
-          uint32_t m, w, rank0;
-          int64_t fit;
           const bool fresh = next_fresh < Ws;
+          if (fresh && P == 0) {
+            // Untouched workers take the same number of tokens of this chunk each (the last one the rest),
+            // and they are handed out in id order: up to 64 hand-outs at once, one per lane.
+            const uint32_t R = (uint32_t)(t1 - t0);
+            const uint32_t F = fresh_fit > (int64_t)R ? R : (uint32_t)fresh_fit;
+            uint32_t cnt = (R + F - 1) / F;
+            cnt = min(cnt, min((uint32_t)(Ws - next_fresh), 64u));
+            cnt = (uint32_t)__builtin_amdgcn_readfirstlane((int)cnt);
+            if ((uint32_t)lane < cnt) {
+              const int lo = t0 + (int)((uint32_t)lane * F), hi = min(t1, lo + (int)F);
+              const int w = next_fresh + lane, kk = k + lane;
+              if (kk < n_max) {
+                pieces[2 * (size_t)kk] = make_int4(ci, bh, lo, hi);
+                pieces[2 * (size_t)kk + 1] = make_int4(w, 0, kk - first_k, 0);
+              }
+              wcount[w] = 1, loads[w] = (uint32_t)(hi - lo) * ds;
+            }
+            k += (int)cnt, next_fresh += (int)cnt;
+            const uint64_t adv = (uint64_t)cnt * F;
+            t0 = adv >= R ? t1 : t0 + (int)adv;
+            continue;
+          }
+          uint32_t m, w;
+          int64_t fit;
           if (fresh) {
-            m = 0, w = (uint32_t)next_fresh++, rank0 = 0, fit = fresh_fit;
+            m = 0, w = (uint32_t)next_fresh++, fit = fresh_fit;
           } else {
             if (!built) {
               for (uint32_t sg = 0; sg < 64; ++sg) rescan(sg);
@@ -322,13 +344,14 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(DevPlanLaunch
             m = (uint32_t)__builtin_amdgcn_readfirstlane((int)wave_min_u32(segmin));
             const int sl = __builtin_ctzll(__ballot(segmin == m));
             w = (uint32_t)__builtin_amdgcn_readlane((int)segarg, sl);
-            rank0 = wcount[w];
             fit = split ? fit_tokens(m, step) : INT64_MAX;
           }
           int take = t1 - t0;
           if (fit < take) take = (int)fit;
           take = __builtin_amdgcn_readfirstlane(take);
           const int end = t0 + take;
+          if (lane == 0) loads[w] = m + (uint32_t)take * ds;
+          const uint32_t rank0 = fresh ? 0u : wcount[w];
           uint32_t np = 0;
           for (int lo = t0; lo < end;) {   // one piece per page it touches
             const int hi = P > 0 ? min(end, (lo / P + 1) * P) : end;
@@ -338,7 +361,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(DevPlanLaunch
             }
             ++k, ++np, lo = hi;
           }
-          if (lane == 0) wcount[w] = rank0 + np, loads[w] = m + (uint32_t)take * ds;
+          if (lane == 0) wcount[w] = rank0 + np;
           if (!fresh) rescan(w >> seg_log2);
           t0 = end;
         }
