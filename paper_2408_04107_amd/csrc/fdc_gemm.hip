@@ -7,6 +7,8 @@
 // group and the epilogue differ. FDC_F32 layouts use a plain fp32 kernel (validation shapes).
 #include <hip/hip_runtime.h>
 
+#include <climits>
+
 #include <algorithm>
 #include <mutex>
 #include <utility>
@@ -35,6 +37,24 @@ static hipError_t ensure_dynamic_lds(const void* kern, size_t bytes) {
   return e;
 }
 
+// Compute units of the current device (cached per device).
+static hipError_t device_compute_units(int* cus) {
+  static std::mutex mu;
+  static std::vector<std::pair<int, int>> known;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& d : known)
+    if (d.first == dev) {
+      *cus = d.second;
+      return hipSuccess;
+    }
+  e = hipDeviceGetAttribute(cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e == hipSuccess) known.emplace_back(dev, *cus);
+  return e;
+}
+
 enum GemmMode { kPlain = 0, kProject = 1, kAbsorbQuery = 2, kFold = 3 };
 
 struct GemmArgs {
@@ -45,6 +65,7 @@ struct GemmArgs {
   int64_t lda, ldb, ldc;
   int M, N, K;
   int nt;    // column tiles of the large kernel (of the widest group)
+  int split_from;  // large kernel: blocks from this one on each take half (128 rows) of a tile
   int mode;
   int H, d_head, max_seq;
   int G;     // query heads per key/value head: grouped products run over the H * G query heads
@@ -465,7 +486,6 @@ __global__ __launch_bounds__(256) void grouped_rows_kernel(const GemmArgs g) {
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 constexpr int DM = 256, DN = 256, DK = 64;
 constexpr int kDmaStage = (DM + DN) * DK;     // elements per ring stage (A rows, then B rows)
-constexpr int kDmaLoads = (DM + DN) / 64;     // wave-wide loads per wave and stage (8 tile rows each)
 
 __device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, int soff) {
   // lane l of the wave lands at lds_addr + 16 * l
@@ -482,27 +502,28 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 }
 constexpr int vm_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x70 | 0xF00; }  // s_waitcnt vmcnt(n) only
 
-template <typename TC>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_dma_kernel(const GemmArgs g) {
-  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * kDmaStage];
-  // tile order: XCD-major, then 8 row tiles down before the next column tile (see gemm_bf16_kernel)
-  const int mt = (g.M + DM - 1) / DM, nt = g.nt;
-  const int tiles = mt * nt, per_xcd = (tiles + 7) / 8;
-  const int lin = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  if (lin >= tiles) return;
-  constexpr int GM = 8;
-  const int band = lin / (GM * nt), in_band = lin % (GM * nt);
-  const int band_rows = min(GM, mt - band * GM);
-  const int tm = band * GM + in_band % band_rows, tn = in_band / band_rows;
-  const int m0 = tm * DM, n0 = tn * DN;
+// One TM x TN tile of C at (m0, n0). The eight waves form a WMW x WNW grid:
+//   256 x 256, 2 x 4 waves of 128 x 64: the full tile;
+//   256 x 64,  8 x 1 waves of 32 x 64: a column tile with at most 64 valid columns (the ragged last column
+//              tile of an N that is not a multiple of 256 costs a quarter of the multiplies);
+//   128 x 256, 2 x 4 waves of 64 x 64: half a full tile, for the tiles of an incomplete last round of the
+//              launch (see the kernel).
+template <typename TC, int WMW, int WNW, int TM, int TN>
+__device__ __forceinline__ void dma_tile(const GemmArgs& g, const int m0, const int n0, uint16_t* lds) {
+  static_assert(WMW * WNW == 8 && TM % 64 == 0 && TN % 64 == 0, "eight waves, load rounds of 64 rows");
+  constexpr int WM = TM / WMW, CW = TN / WNW;    // rows and columns of a wave's tile
+  constexpr int IB = WM / 32, FB = CW / 32;      // 32 x 32 blocks of it
+  constexpr int LA = TM / 64, LB = TN / 64;      // wave-wide load rounds of the A rows and the B rows
+  constexpr int LQ = LA + LB;                    // loads per wave and stage
+  constexpr int kStage = (TM + TN) * DK;         // elements per ring stage (A rows, then B rows)
   const int M = g.M, N = g.N, K = g.K;
 
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);
-  const int wm = (wave / 4) * 128, wn = (wave % 4) * 64;
+  const int wm = (wave / WNW) * WM, wn = (wave % WNW) * CW;
   const uint16_t* A = static_cast<const uint16_t*>(g.A);
   const uint16_t* B = static_cast<const uint16_t*>(g.B);
-  const int a_rows = min(DM, M - m0), b_rows = min(DN, N - n0);
+  const int a_rows = min(TM, M - m0), b_rows = min(TN, N - n0);
   const i32x4 a_rsrc = make_rsrc(A + (int64_t)m0 * g.lda, (uint32_t)(((int64_t)(a_rows - 1) * g.lda + K) * 2));
   const i32x4 b_rsrc = make_rsrc(B + (int64_t)n0 * g.ldb, (uint32_t)(((int64_t)(b_rows - 1) * g.ldb + K) * 2));
 
@@ -525,11 +546,11 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     b_tail[j] = (row < b_rows && tail_ok) ? b_off[j] + (uint32_t)(k_tail0 * 2) : kOob;
   }
   const uint32_t lds0 = lds_addr_of(lds) + (uint32_t)(wave * 8 * DK * 2);
-  // load q (0..3: A rows, 4..7: B rows) of stage t into ring buffer s
+  // load q (0..LA-1: A rows, LA..: B rows) of stage t into ring buffer s
   auto issue1 = [&](int s, int t, int q) {
-    const bool is_a = q < 4;
-    const int j = q & 3;
-    const uint32_t dst = lds0 + (uint32_t)((s * kDmaStage + (is_a ? 0 : DM * DK) + j * 64 * DK) * 2);
+    const bool is_a = q < LA;
+    const int j = is_a ? q : q - LA;
+    const uint32_t dst = lds0 + (uint32_t)((s * kStage + (is_a ? 0 : TM * DK) + j * 64 * DK) * 2);
     const bool tail = has_tail && t == nk - 1;
     const uint32_t voff = is_a ? (tail ? a_tail[j] : a_off[j]) : (tail ? b_tail[j] : b_off[j]);
     dma16(is_a ? a_rsrc : b_rsrc, dst, voff, tail ? 0 : t * DK * 2);
@@ -541,29 +562,29 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
   for (int s = 0; s < 4; ++s) f_off[s] = f_row * DK + (((2 * s + lane / 32) ^ ((f_row / 2) % 8)) * 8);
 
-  f32x16 acc[4][2];
+  f32x16 acc[IB][FB];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < IB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < FB; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];
-  auto load_frag = [&](int s, int ks, bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
-    const uint16_t* sa = lds + s * kDmaStage + wm * DK;
-    const uint16_t* sb = lds + s * kDmaStage + DM * DK + wn * DK;
+  bf16x8 fa0[IB], fb0[FB], fa1[IB], fb1[FB];
+  auto load_frag = [&](int s, int ks, bf16x8 (&fa)[IB], bf16x8 (&fb)[FB]) {
+    const uint16_t* sa = lds + s * kStage + wm * DK;
+    const uint16_t* sb = lds + s * kStage + TM * DK + wn * DK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sa[i * 32 * DK + f_off[ks]]);
+    for (int i = 0; i < IB; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(&sa[i * 32 * DK + f_off[ks]]);
 #pragma unroll
-    for (int j = 0; j < 2; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&sb[j * 32 * DK + f_off[ks]]);
+    for (int j = 0; j < FB; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(&sb[j * 32 * DK + f_off[ks]]);
   };
   // operands swapped: the accumulator tile is C^T, a lane holds one m and runs of four n
-  auto mma = [&](bf16x8 (&fa)[4], bf16x8 (&fb)[2]) {
+  auto mma = [&](bf16x8 (&fa)[IB], bf16x8 (&fb)[FB]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < IB; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      for (int j = 0; j < FB; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
   };
   constexpr int kVm0Lgkm0 = 0x0070;   // s_waitcnt vmcnt(0) lgkmcnt(0)
 
@@ -592,22 +613,25 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __builtin_amdgcn_sched_barrier(0);
     const bool more = t + 2 < nk;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < IB; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {   // the eight loads of stage t+2 go between the last eight multiplies
+      for (int j = 0; j < FB; ++j) {   // the loads of stage t+2 go between the last multiplies, one each
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb1[j], fa1[i], acc[i][j], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        if (more) issue1(s, t + 2, i * 2 + j);
+        if (more && i * FB + j < LQ) issue1(s, t + 2, i * FB + j);
         __builtin_amdgcn_sched_barrier(0);
       }
+#pragma unroll
+    for (int q = IB * FB; q < LQ; ++q)   // a narrow tile has fewer multiplies than loads
+      if (more) issue1(s, t + 2, q);
   };
 
 #pragma unroll
-  for (int q = 0; q < kDmaLoads; ++q) issue1(0, 0, q);
+  for (int q = 0; q < LQ; ++q) issue1(0, 0, q);
   if (1 < nk) {
 #pragma unroll
-    for (int q = 0; q < kDmaLoads; ++q) issue1(1, 1, q);
-    __builtin_amdgcn_s_waitcnt(vm_imm(kDmaLoads));
+    for (int q = 0; q < LQ; ++q) issue1(1, 1, q);
+    __builtin_amdgcn_s_waitcnt(vm_imm(LQ));
   } else {
     __builtin_amdgcn_s_waitcnt(vm_imm(0));
   }
@@ -627,12 +651,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   if constexpr (sizeof(TC) == 4) {
     // fp32 C (plain mode only): 16 bytes per lane straight from the registers
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < IB; ++i) {
       const int m = m0 + wm + i * 32 + lane % 32;
       if (m >= M) continue;
       float* crow = static_cast<float*>(g.C) + (int64_t)m * g.ldc;
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < FB; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           const int n = n0 + wn + j * 32 + gq * 8 + (lane / 32) * 4;
@@ -645,12 +669,13 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
   } else {
-    // bf16 C: each wave turns 64 of its rows at a time into bf16 in a private LDS region (row
+    // bf16 C: each wave turns 64 of its rows (32 in a narrow tile) at a time into bf16 in a private LDS region (row
     // stride 144 bytes) and streams them out as 16-byte chunks; 8 lanes cover one 128-byte row of
     // the wave's tile, so a store instruction writes 8 full lines (plain) or 8 runs of 128 bytes
     // of one token's latent rows (project).
     asm volatile("s_barrier" ::: "memory");   // every wave is done with the last stage
     constexpr int EROW = 72;
+    constexpr int GB = IB < 2 ? IB : 2;   // 32-row blocks per round
     uint16_t* ep = lds + wave * (64 * EROW);
     const int c = lane % 8;
     const int n = n0 + wn + c * 8;
@@ -671,22 +696,22 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       uint8_t* cb8 = reinterpret_cast<uint8_t*>(cbase);
       auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
+      for (int h = 0; h < IB / GB; ++h) {
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii)
+        for (int ii = 0; ii < GB; ++ii)
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < FB; ++j)
 #pragma unroll
             for (int gq = 0; gq < 4; ++gq) {
-              const int i = 2 * h + ii;
+              const int i = GB * h + ii;
               uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[i][j][gq * 4 + 0]), sat(acc[i][j][gq * 4 + 1]), 0u, false);
               w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[i][j][gq * 4 + 2]), sat(acc[i][j][gq * 4 + 3]), w, true);
               *reinterpret_cast<uint32_t*>(&ep8[(ii * 32 + lane % 32) * EROW + j * 32 + gq * 8 + (lane / 32) * 4]) = w;
             }
 #pragma unroll
-        for (int it = 0; it < 8; ++it) {
+        for (int it = 0; it < 4 * GB; ++it) {
           const int row = it * 8 + lane / 8;
-          const int m = m0 + wm + h * 64 + row;
+          const int m = m0 + wm + h * 32 * GB + row;
           const uint2 v = *reinterpret_cast<const uint2*>(&ep8[row * EROW + c * 8]);
           if (m >= M || n >= N) continue;
           *reinterpret_cast<uint2*>(cb8 + (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank) = v;
@@ -695,23 +720,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       return;
     }
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int h = 0; h < IB / GB; ++h) {
 #pragma unroll
-      for (int ii = 0; ii < 2; ++ii)
+      for (int ii = 0; ii < GB; ++ii)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < FB; ++j)
 #pragma unroll
           for (int gq = 0; gq < 4; ++gq) {
-            const int i = 2 * h + ii;
+            const int i = GB * h + ii;
             uint2 v;
             v.x = cvt_pk_bf16(acc[i][j][gq * 4 + 0], acc[i][j][gq * 4 + 1]);
             v.y = cvt_pk_bf16(acc[i][j][gq * 4 + 2], acc[i][j][gq * 4 + 3]);
             *reinterpret_cast<uint2*>(&ep[(ii * 32 + lane % 32) * EROW + j * 32 + gq * 8 + (lane / 32) * 4]) = v;
           }
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
+      for (int it = 0; it < 4 * GB; ++it) {
         const int row = it * 8 + lane / 8;
-        const int m = m0 + wm + h * 64 + row;
+        const int m = m0 + wm + h * 32 * GB + row;
         const u32x4 v = *reinterpret_cast<const u32x4*>(&ep[row * EROW + c * 8]);
         if (m >= M || n >= N) continue;
         uint16_t* dst = g.mode == kProject
@@ -726,6 +751,36 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
       }
     }
+  }
+}
+
+template <typename TC>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_dma_kernel(const GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) uint16_t lds[2 * kDmaStage];
+  // A compute unit holds one workgroup, so a launch runs in rounds of as many tiles as there are compute
+  // units. When the last round is at most half full, its tiles are cut into two 128-row halves (blocks from
+  // g.split_from on, two per tile): the round then takes about half a tile's time instead of a whole one.
+  int slot = blockIdx.x, half = -1;
+  if (slot >= g.split_from) {
+    half = (slot - g.split_from) & 1;
+    slot = g.split_from + (slot - g.split_from) / 2;
+  }
+  // tile order: XCD-major, then 8 row tiles down before the next column tile (see gemm_bf16_kernel)
+  const int mt = (g.M + DM - 1) / DM, nt = g.nt;
+  const int tiles = mt * nt, per_xcd = (tiles + 7) / 8;
+  const int lin = (slot % 8) * per_xcd + slot / 8;
+  if (lin >= tiles) return;
+  constexpr int GM = 8;
+  const int band = lin / (GM * nt), in_band = lin % (GM * nt);
+  const int band_rows = min(GM, mt - band * GM);
+  const int tm = band * GM + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * DM, n0 = tn * DN;
+  if (g.N - n0 <= 64) {
+    if (half <= 0) dma_tile<TC, 8, 1, DM, 64>(g, m0, n0, lds);   // cheap already: not cut, the second block has nothing to do
+  } else if (half < 0) {
+    dma_tile<TC, 2, 4, DM, DN>(g, m0, n0, lds);
+  } else if (m0 + half * (DM / 2) < g.M) {
+    dma_tile<TC, 2, 4, DM / 2, DN>(g, m0 + half * (DM / 2), n0, lds);
   }
 }
 
@@ -1175,7 +1230,14 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     GemmArgs b = a;
     b.nt = (a.N + DN - 1) / DN;
     const int tiles = b.nt * ((a.M + DM - 1) / DM);
-    const dim3 grid((tiles + 7) / 8 * 8);
+    const int slots = (tiles + 7) / 8 * 8;
+    int cus = 0;
+    FDC_HIP_CHECK(device_compute_units(&cus));
+    cus = std::max(cus, 8) / 8 * 8;
+    const int full = slots / cus * cus, last = slots - full;   // slots of complete rounds, of the last round
+    const bool cut = last > 0 && last <= cus / 2;
+    b.split_from = cut ? full : INT_MAX;
+    const dim3 grid(cut ? full + 2 * last : slots);
     if (c_f32) hipLaunchKernelGGL(gemm_dma_kernel<float>, grid, dim3(512), 0, st, b);
     else hipLaunchKernelGGL(gemm_dma_kernel<uint16_t>, grid, dim3(512), 0, st, b);
   } else {
