@@ -22,14 +22,14 @@
 
 namespace fdc {
 
-#ifndef FDC_DECODE_LOADS
-#define FDC_DECODE_LOADS 8
-#endif
-constexpr int kTokLanes = 64 * FDC_DECODE_LOADS;  // a block holds FDC_DECODE_LOADS wave-wide loads of the wider operand
+// Wave-wide 16-byte loads of the wider operand per block: 8 KiB per wave in flight and side (4 to 16
+// measured within 2 % of each other).
+constexpr int kDecodeLoads = 8;
+constexpr int kTokLanes = 64 * kDecodeLoads;
 constexpr int kWavesPerBlock = 4;
 constexpr int kLdsFloatsPerWave = kTokLanes > 256 ? kTokLanes : 256;  // a block of one-lane rows (E4M3, rank 16) has kTokLanes tokens
 
-// Tokens per block: FDC_DECODE_LOADS loads of the wider operand, at least one load of the narrower.
+// Tokens per block: kDecodeLoads loads of the wider operand, at least one load of the narrower.
 constexpr int block_tokens(int lk, int lv) {
   int t = kTokLanes / (lk > lv ? lk : lv);
   const int need = 64 / (lk < lv ? lk : lv);
@@ -175,21 +175,6 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
   __builtin_amdgcn_sched_barrier(0);  // keep issue order K' then V': the wait counters rely on it
   load_v(0);
   __builtin_amdgcn_sched_barrier(0);
-#ifdef FDC_DECODE_STRIP  // measurement experiment only: same loads, trivial arithmetic
-  for (int t0 = 0; t0 < len; t0 += TB) {
-#pragma unroll
-    for (int i = 0; i < NK; ++i) l += __uint_as_float(kreg[i][0] ^ kreg[i][1] ^ kreg[i][2] ^ kreg[i][3]);
-    __builtin_amdgcn_sched_barrier(0);
-    load_k(t0 + TB);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < NV; ++i) acc[0] += __uint_as_float(vreg[i][0] ^ vreg[i][1] ^ vreg[i][2] ^ vreg[i][3]);
-    __builtin_amdgcn_sched_barrier(0);
-    load_v(t0 + TB);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  m = 0.f;
-#else
   for (int t0 = 0; t0 < len; t0 += TB) {
     // scores of the block -> LDS strip
 #pragma unroll
@@ -248,7 +233,6 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
     __builtin_amdgcn_sched_barrier(0);
     wave_lds_sync();
   }
-#endif
 
   // tile result: l over all lanes, acc over the lanes that share a column group
   l = group_sum<64>(l);

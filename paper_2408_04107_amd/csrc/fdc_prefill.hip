@@ -37,22 +37,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
-#ifndef FDC_PREFILL_QT
-#define FDC_PREFILL_QT 1
-#endif
-#ifndef FDC_PREFILL_ROWS
-#define FDC_PREFILL_ROWS 256
-#endif
-#ifndef FDC_PREFILL_HALVES
-#define FDC_PREFILL_HALVES 2
-#endif
-constexpr int QT = FDC_PREFILL_QT;       // 16-row MFMA tiles of queries per wave
+constexpr int QT = 1;                    // 16-row MFMA tiles of queries per wave
 constexpr int BC = 64;                   // tokens per score tile set (one softmax update)
-constexpr int NH = FDC_PREFILL_HALVES;   // score tile sets per staged block
+constexpr int NH = 2;                    // score tile sets per staged block
 constexpr int BCB = BC * NH;             // tokens per staged K'/V' block (one barrier)
 static_assert(BCB == kPrefillBlockTokens, "a page of a paged cache holds whole staged blocks");
 constexpr int kRowsPerWave = 16 * QT;
-constexpr int kRowsPerPass = FDC_PREFILL_ROWS;
+constexpr int kRowsPerPass = 256;         // query rows a workgroup works on at a time (sixteen waves)
 constexpr int kPreThreads = 64 * (kRowsPerPass / kRowsPerWave);
 constexpr int kPreWavesPerSimd = kPreThreads / 256 * (160 * 1024 / (2 * BCB * (144 + 144) * 2));  // workgroups that fit the LDS
 // LDS row lengths in elements. A 16-byte LDS read serves 16 lanes per pass, and (measured with two
