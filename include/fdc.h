@@ -32,8 +32,9 @@
  *    values (the paper combines its compression with cache quantisation in
  *    Section 6.2 and fixes no format: a reading). Every call takes FDC_FP8
  *    layouts.
- *  - fdc_layout and fdc_plan are host objects, immutable after creation,
- *    destroyed by the matching call.
+ *  - fdc_layout and fdc_plan are host objects, immutable after creation
+ *    (except that fdc_plan_download fills in the host tables of a plan whose
+ *    schedule was computed on the device), destroyed by the matching call.
  */
 #ifndef FDC_H_
 #define FDC_H_
