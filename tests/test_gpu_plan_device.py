@@ -58,6 +58,11 @@ CASES = [
     ([48] * 5, [80] * 5, [1, 63, 64, 65], 3000, 64, 2, 1, 1),
     ([128] * 8, [128] * 8, [2048] * 4, 8192, 64, 1, 1, 1),
     ([16], [16], [5000], 1, 64, 1, 1, 1),
+    # a granule that is no power of two, a worker count that is no multiple of 64
+    ([32, 96, 16], [64, 16, 128], [700, 1, 0, 48, 49, 3000], 1000, 48, 2, 1, 7),
+    # the most chunks the kernel sorts (8192), many heads; the largest worker count with it
+    ([16 + 16 * (h % 8) for h in range(128)], [128 - 16 * (h % 8) for h in range(128)], [200 + 13 * b for b in range(64)], 4096, 64, 1, 1, 1),
+    ([16, 64, 128, 32], [32, 16, 64, 128], [(37 * b) % 300 for b in range(2048)], 8192, 64, 1, 1, 1),
 ]
 
 
