@@ -1211,7 +1211,8 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     if (c_f32) hipLaunchKernelGGL(absorb_query_small_kernel<float>, grid, dim3(64), 0, st, a);
     else hipLaunchKernelGGL(absorb_query_small_kernel<uint16_t>, grid, dim3(64), 0, st, a);
   } else if ((a.mode == kAbsorbQuery || a.mode == kFold) && !a_f32 && a.K <= 128 && a.K % 8 == 0 && n_max <= 128 &&
-             a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldc % 4 == 0) {
+             a.lda % 8 == 0 && a.ldb % 8 == 0 && a.ldc % 4 == 0 &&
+             ((int64_t)a.M * a.lda + a.K) * 2 < ((int64_t)1 << 31)) {   // the kernel reads A through a 32-bit buffer range
     const dim3 grid((a.M + kRowsPerWg - 1) / kRowsPerWg, groups);
     if (c_f32) hipLaunchKernelGGL(grouped_rows_kernel<float>, grid, dim3(256), 0, st, a);
     else hipLaunchKernelGGL(grouped_rows_kernel<uint16_t>, grid, dim3(256), 0, st, a);
