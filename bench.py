@@ -544,6 +544,81 @@ def run_device_planner(fdc, gen, wl, iters=5):
             "workspace_MB_per_layer": plans[0].workspace_bytes() / 1e6}
 
 
+def run_serving_loop(fdc, gen, wl, steps=64):
+    """A decode loop as a serving system runs it, with nothing on the host between steps: the lengths live in
+    device memory and grow by one token per step, every layer appends its K'/V' rows at the sequence's end
+    (fdc_project_and_absorb_query), attends at the actual lengths on a plan made for the lengths rounded up
+    to the granule (fdc_latent_attn_decode_at), and all layers are re-planned on the GPU
+    (fdc_plan_decode_run) whenever a sequence enters a new granule: once in the 64 steps timed here, which
+    start at context - 64 and end at the workload's context."""
+    import torch
+    dev = "cuda:0"
+    ranks = wl.ranks()
+    L, H, B, S, d, dh = wl.n_layers, wl.n_heads, wl.batch, wl.context, wl.d_model, wl.d_head
+    lay = fdc.Layout(L, H, d, dh, ranks, ranks, B, S, fdc.FDC_BF16)
+    t = lay.tables()
+    gt = torch.Generator(device=dev).manual_seed(wl.seed + 1)
+    bf = torch.bfloat16
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(0), wl.min_split
+    G = pp.granule
+    kc, vc, A_cat_t, Bk, Mt, plans, wss = [], [], [], [], [], [], []
+    for l in range(L):
+        RK, RV = int(t["koff_r"][l, -1]), int(t["voff_r"][l, -1])
+        # cache contents: any finite values do (the kernels' speed does not depend on them); cheap to make
+        kc.append((torch.randn(int(t["k_bytes"][l]) // 2, generator=gt, device=dev) * 0.3).to(bf))
+        vc.append((torch.randn(int(t["v_bytes"][l]) // 2, generator=gt, device=dev) * 0.3).to(bf))
+        A_cat_t.append((torch.randn(RK + RV, d, generator=gt, device=dev) / math.sqrt(d)).to(bf))
+        Bk.append((torch.randn(RK, dh, generator=gt, device=dev) / math.sqrt(dh)).to(bf))
+        Mt.append((torch.randn(d, RV, generator=gt, device=dev) / math.sqrt(RV)).to(bf))
+        plan = fdc.fdc_plan_decode_device(lay, l, B, 0, pp)
+        ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+        off = (-ws.data_ptr()) % 256
+        ws = ws[off:off + plan.workspace_bytes()]
+        fdc.fdc_plan_upload(plan, ws)
+        plans.append(plan), wss.append(ws)
+    x = torch.randn(B, d, generator=gt, device=dev).to(bf)
+    q = torch.randn(B, H, dh, generator=gt, device=dev).to(bf)
+    tb = torch.arange(B, dtype=torch.int32, device=dev)
+    RKmax, RVmax = int(t["koff_r"][:, -1].max()), int(t["voff_r"][:, -1].max())
+    q_lat = torch.empty(B * RKmax, dtype=torch.float32, device=dev)
+    o_lat = torch.empty(B * RVmax, dtype=torch.float32, device=dev)
+    y = torch.empty(B, d, dtype=bf, device=dev)
+    scale = 1.0 / math.sqrt(dh)
+    start = S - steps
+    assert start % G == 0 and start > 0, "the loop starts on a granule boundary"
+    pos = torch.full((B,), start, dtype=torch.int32, device=dev)       # tokens already cached = position of the new one
+    lens = torch.empty_like(pos)                                       # tokens attended to in this step
+    planned = torch.empty_like(pos)
+    groups = [(plans[i:i + 32], wss[i:i + 32]) for i in range(0, L, 32)]
+
+    def step(i):
+        torch.add(pos, 1, out=lens)
+        if i % G == 0:                                                 # the host knows the step count, not the lengths
+            torch.div(lens + (G - 1), G, rounding_mode="floor", out=planned)
+            planned.mul_(G)
+            for p, w in groups:
+                fdc.fdc_plan_decode_run(p, w, planned)
+        for l in range(L):
+            fdc.fdc_project_and_absorb_query(lay, l, x, tb, pos, A_cat_t[l], kc[l], vc[l], q, Bk[l], q_lat, fdc.FDC_F32)
+            fdc.fdc_latent_attn_decode_at(lay, plans[l], lens, q_lat, kc[l], vc[l], scale, o_lat, wss[l])
+            fdc.fdc_absorb_output(lay, l, fdc.FDC_APPLY, None, None, Mt[l], o_lat, fdc.FDC_F32, B, y, fdc.FDC_BF16)
+        pos.add_(1)
+
+    step(0)                     # warm-up (plans once, appends one token)
+    pos.fill_(start)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    assert int(pos[0].item()) == S and bool(torch.isfinite(y.float()).all().item())
+    return {"workload": "%s: %d steps from context %d to %d, appends and lengths on the device, one re-plan of all "
+                        "%d layers by the GPU planner inside the timed steps" % (wl.name, steps, start, S, L),
+            "ms_per_step": ms, "n_workers": pp.n_workers}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -561,6 +636,7 @@ def main():
     ap.add_argument("--no-gqa", action="store_true")
     ap.add_argument("--no-fp8", action="store_true")
     ap.add_argument("--no-device-planner", action="store_true")
+    ap.add_argument("--no-serving-loop", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
@@ -621,6 +697,8 @@ def main():
         side("fp8_decode", lambda: run_fp8_decode_workload(fdc, gen, wl))
     if not args.no_device_planner:
         side("device_planner", lambda: run_device_planner(fdc, gen, wl))
+    if not args.no_serving_loop:
+        side("serving_loop", lambda: run_serving_loop(fdc, gen, wl))
     print(json.dumps(line))
 
 
