@@ -10,7 +10,9 @@ absorption. Inputs are synthetic, seeded, and resident in HBM before the timed r
 Prints ONE JSON line. `value` is the algorithmic HBM bytes of a whole step divided by the step
 time; `roofline` describes the dominant kernel (the decode tile kernel) from HIP events recorded
 around that kernel alone; `cpu_baseline` is the float64 oracle timed on the host on a bounded
-sample; `prefill` reports the MFMA calls of the prefill configuration in TFLOP/s.
+sample; `prefill` reports the MFMA calls of the prefill configuration in TFLOP/s. Further objects of
+the same line are side measurements of the other rows (`gqa_decode`, `fp8_decode`, `device_planner`,
+`serving_loop`); each has a --no-... switch and a failure in one of them is reported in its place.
 """
 from __future__ import annotations
 
