@@ -321,3 +321,31 @@ def test_device_plan_creation_is_host_only_and_bounds_the_host_plan():
     pp.n_workers = 256
     with pytest.raises(fdc.FdcError, match="multiple of the granule"):
         fdc.fdc_plan_decode_device(pages, 0, 4, 8, pp)
+
+
+def test_planners_are_thread_safe():
+    """The planners are plain host code behind a GIL-releasing binding; bench.py plans the layers of a step on a
+    thread pool. Eight threads planning different layers at once give the tables of the sequential calls."""
+    from concurrent.futures import ThreadPoolExecutor
+    L, H, B = 8, 32, 16
+    rk, rv = gen.adaptive_ranks(L, H, 3), gen.adaptive_ranks(L, H, 4)
+    lay = _layout(rk, rv, B, 4096)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 1024
+    seq = [4096 - 37 * b for b in range(B)]
+    want = [fdc.fdc_plan_decode(lay, l, seq, pp).export() for l in range(L)]
+    with ThreadPoolExecutor(8) as ex:
+        for _ in range(3):
+            got = list(ex.map(lambda l: fdc.fdc_plan_decode(lay, l, seq, pp).export(), range(L)))
+            for l in range(L):
+                for key in ("item_b", "item_h", "item_lo", "item_hi", "worker_ptr", "worker_items", "worker_load"):
+                    assert np.array_equal(got[l][key], want[l][key]), f"layer {l}: {key} differs under threads"
+    # an error in one thread does not leak its message into another
+    def bad(_):
+        try:
+            fdc.fdc_plan_decode(lay, 99, seq, pp)
+        except fdc.FdcError as e:
+            return str(e)
+    with ThreadPoolExecutor(4) as ex:
+        msgs = list(ex.map(bad, range(8)))
+    assert all(m and "layer 99" in m for m in msgs)
