@@ -1084,105 +1084,128 @@ static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
 }
 
 // ---- post-RoPE compression (Section 5.1: RoPE, then the rotation R truncated to r_h columns) ----
-// One workgroup = 256 token rows of one head, laid out like grouped_rows_kernel: the head's R_t rows
-// (r_h x d_head, K = d_head <= 128) go to LDS once, every wave loads the rows of its four 16-row tiles
-// straight into MFMA fragments, and a lane's eight consecutive k are four RoPE pairs (2i, 2i+1), so
-// the rotation is done in the lane's registers in fp32 (angles from the caller's cos / sin tables at
-// the row's position) and the result rounded to bf16 is the operand. The product is taken transposed:
-// a lane ends up with four consecutive latent columns of one token, stored at once. Queries go to
-// q_lat, keys into the K' cache (bf16 or E4M3 codes).
-constexpr int kRopeRows = 256;
+// One workgroup = 128 token rows and a run of kRopeHeads heads, laid out like grouped_rows_kernel: a wave
+// loads the rows of its two 16-row tiles straight into MFMA fragments, and a lane's eight consecutive k
+// are four RoPE pairs (2i, 2i+1), so the rotation is done in the lane's registers in fp32 and the result
+// rounded to bf16 is the operand. The angles (the caller's cos / sin tables at the row's position) depend
+// on the row, not on the head: a lane reads its 64 table values once and keeps them in registers for all
+// heads of the workgroup (read per head they were two thirds of the kernel's vector-memory instructions
+// and a third of its time). Per head the rotation's R_t rows (r_h x d_head, K = d_head <= 128) are staged
+// in LDS. The product is taken transposed: a lane ends up with four consecutive latent columns of one
+// token, stored at once. Queries go to q_lat, keys into the K' cache (bf16 or E4M3 codes).
+constexpr int kRopeRows = 128;
+constexpr int kRopeHeads = 4;
 
 template <typename TC, bool KEYS>
 __global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRowsBRow];
-  // blockIdx.y is the head of the input rows: a key/value head for keys, a query head for queries
-  // (which then uses the rotation of key/value head hx / G and its own columns of q_lat)
-  const int hx = blockIdx.y;
-  const int h = KEYS ? hx : hx / g.G, jq = KEYS ? 0 : hx % g.G;
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
-  const int r = g.koff_r[h + 1] - g.koff_r[h];
-  const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)hx * g.d_head;  // row stride lda = heads * d_head
-  const uint16_t* Rt = static_cast<const uint16_t*>(g.B) + (int64_t)g.koff_r[h] * g.d_head;
   const int half = g.d_head / 2;
-  {
-    const int cpr = g.d_head / 8;
-    for (int i = tid; i < r * cpr; i += 256) {
-      const int row = i / cpr, c = i - row * cpr;
-      *reinterpret_cast<u32x4*>(&lds_b[row * kRowsBRow + c * 8]) = *reinterpret_cast<const u32x4*>(Rt + (int64_t)row * g.d_head + c * 8);
-    }
-  }
-  const int row0 = blockIdx.x * kRopeRows + wave * 64;
-  union Fr { u32x4 u; bf16x8 v; };
-  Fr af[4][4];
+  const int n_heads = KEYS ? g.H : g.H * g.G;   // heads of the input rows
+  const int row0 = blockIdx.x * kRopeRows + wave * 32;
+  const int ksteps = (g.d_head + 31) / 32;
+  // the angles of the lane's rows and columns
+  float4 cs[2][4], sn[2][4];
+  int tok[2];
+  int64_t tok_dst[2];   // keys: element offset of the token's rows in the cache, without the head's part
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < 2; ++t) {
     const int row = row0 + 16 * t + ln;
     const bool row_on = row < g.M;
-    const int pos = row_on ? min(max(g.tok_pos[row], 0), g.n_pos - 1) : 0;
+    tok[t] = row_on ? row : -1;
+    const int pos_raw = row_on ? g.tok_pos[row] : 0;
+    const int pos = min(max(pos_raw, 0), g.n_pos - 1);
+    tok_dst[t] = (KEYS && row_on) ? (int64_t)g.tok_batch[row] * g.max_seq * g.RK : 0;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int col = 32 * ks + 8 * lg;
-      u32x4 out = {0, 0, 0, 0};
       if (row_on && col < g.d_head) {
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(X + (int64_t)row * g.lda + col);
-        const float4 cs = *reinterpret_cast<const float4*>(g.rope_cos + (int64_t)pos * half + col / 2);
-        const float4 sn = *reinterpret_cast<const float4*>(g.rope_sin + (int64_t)pos * half + col / 2);
-        const float cc[4] = {cs.x, cs.y, cs.z, cs.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float xe = __uint_as_float(raw[j] << 16), xo = __uint_as_float(raw[j] & 0xffff0000u);
-          out[j] = cvt_pk_bf16(xe * cc[j] - xo * ss[j], xe * ss[j] + xo * cc[j]);
-        }
+        cs[t][ks] = *reinterpret_cast<const float4*>(g.rope_cos + (int64_t)pos * half + col / 2);
+        sn[t][ks] = *reinterpret_cast<const float4*>(g.rope_sin + (int64_t)pos * half + col / 2);
+      } else {
+        cs[t][ks] = float4{0.f, 0.f, 0.f, 0.f}, sn[t][ks] = float4{0.f, 0.f, 0.f, 0.f};
       }
-      af[t][ks].u = out;
     }
   }
-  __syncthreads();
-  const int ksteps = (g.d_head + 31) / 32;
-  for (int n0 = 0; n0 < r; n0 += 16) {
-    f32x4 acc[4];
+  union Fr { u32x4 u; bf16x8 v; };
+  for (int hx = blockIdx.y * kRopeHeads; hx < min(n_heads, (int)(blockIdx.y + 1) * kRopeHeads); ++hx) {
+    // hx is the head of the input rows: a key/value head for keys, a query head for queries (which then
+    // uses the rotation of key/value head hx / G and its own columns of q_lat)
+    const int h = KEYS ? hx : hx / g.G, jq = KEYS ? 0 : hx % g.G;
+    const int r = g.koff_r[h + 1] - g.koff_r[h];
+    const uint16_t* X = static_cast<const uint16_t*>(g.A) + (int64_t)hx * g.d_head;  // row stride lda = heads * d_head
+    const uint16_t* Rt = static_cast<const uint16_t*>(g.B) + (int64_t)g.koff_r[h] * g.d_head;
+    // the rows of this head, rotated
+    Fr af[2][4];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      if (ks >= ksteps) break;
-      Fr bq;
-      const int col = 32 * ks + 8 * lg;
-      bq.u = col < g.d_head ? *reinterpret_cast<const u32x4*>(&lds_b[(n0 + ln) * kRowsBRow + col]) : u32x4{0, 0, 0, 0};
+      for (int ks = 0; ks < 4; ++ks) {
+        const int col = 32 * ks + 8 * lg;
+        u32x4 out = {0, 0, 0, 0};
+        if (tok[t] >= 0 && col < g.d_head) {
+          const u32x4 raw = *reinterpret_cast<const u32x4*>(X + (int64_t)tok[t] * g.lda + col);
+          const float cc[4] = {cs[t][ks].x, cs[t][ks].y, cs[t][ks].z, cs[t][ks].w};
+          const float ss[4] = {sn[t][ks].x, sn[t][ks].y, sn[t][ks].z, sn[t][ks].w};
 #pragma unroll
-      for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq.v, af[t][ks].v, acc[t], 0, 0, 0);
-    }
-    // register e of lane l: latent column n0 + 4 * (l / 16) + e of token row l % 16
-    const int n = n0 + 4 * lg;
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int tok = row0 + 16 * t + ln;
-      if (tok >= g.M) continue;
-      if constexpr (KEYS) {
-        const int64_t dst = (int64_t)g.tok_batch[tok] * g.max_seq * g.RK + (int64_t)g.max_seq * g.koff_r[h] +
-                            (int64_t)g.tok_pos[tok] * r + n;
-        if (g.cache_fp8) {
-          auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
-          uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][0]), sat(acc[t][1]), 0u, false);
-          w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][2]), sat(acc[t][3]), w, true);
-          *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(g.C) + dst) = w;
-        } else {
-          uint2 w;
-          w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
-          w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.C) + dst) = w;
+          for (int j = 0; j < 4; ++j) {
+            const float xe = __uint_as_float(raw[j] << 16), xo = __uint_as_float(raw[j] & 0xffff0000u);
+            out[j] = cvt_pk_bf16(xe * cc[j] - xo * ss[j], xe * ss[j] + xo * cc[j]);
+          }
         }
-      } else {
-        TC* dst = static_cast<TC*>(g.C) + (int64_t)tok * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n;
-        if constexpr (sizeof(TC) == 4) {
-          *reinterpret_cast<f32x4*>(dst) = acc[t];
+        af[t][ks].u = out;
+      }
+    __syncthreads();   // every wave is done with the previous head's rotation rows
+    {
+      const int cpr = g.d_head / 8;
+      for (int i = tid; i < r * cpr; i += 256) {
+        const int row = i / cpr, c = i - row * cpr;
+        *reinterpret_cast<u32x4*>(&lds_b[row * kRowsBRow + c * 8]) = *reinterpret_cast<const u32x4*>(Rt + (int64_t)row * g.d_head + c * 8);
+      }
+    }
+    __syncthreads();
+    for (int n0 = 0; n0 < r; n0 += 16) {
+      f32x4 acc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks >= ksteps) break;
+        Fr bq;
+        const int col = 32 * ks + 8 * lg;
+        bq.u = col < g.d_head ? *reinterpret_cast<const u32x4*>(&lds_b[(n0 + ln) * kRowsBRow + col]) : u32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int t = 0; t < 2; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq.v, af[t][ks].v, acc[t], 0, 0, 0);
+      }
+      // register e of lane l: latent column n0 + 4 * (l / 16) + e of token row l % 16
+      const int n = n0 + 4 * lg;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if (tok[t] < 0) continue;
+        if constexpr (KEYS) {
+          const int64_t dst = tok_dst[t] + (int64_t)g.max_seq * g.koff_r[h] + (int64_t)g.tok_pos[tok[t]] * r + n;
+          if (g.cache_fp8) {
+            auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
+            uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][0]), sat(acc[t][1]), 0u, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][2]), sat(acc[t][3]), w, true);
+            *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(g.C) + dst) = w;
+          } else {
+            uint2 w;
+            w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
+            w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.C) + dst) = w;
+          }
         } else {
-          uint2 w;
-          w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
-          w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
-          *reinterpret_cast<uint2*>(dst) = w;
+          TC* dst = static_cast<TC*>(g.C) + (int64_t)tok[t] * g.G * g.RK + g.G * g.koff_r[h] + jq * r + n;
+          if constexpr (sizeof(TC) == 4) {
+            *reinterpret_cast<f32x4*>(dst) = acc[t];
+          } else {
+            uint2 w;
+            w.x = cvt_pk_bf16(acc[t][0], acc[t][1]);
+            w.y = cvt_pk_bf16(acc[t][2], acc[t][3]);
+            *reinterpret_cast<uint2*>(dst) = w;
+          }
         }
       }
     }
@@ -1427,7 +1450,7 @@ fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q
   if (s != FDC_OK) return s;
   if (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_rope_absorb_query: q_lat_dtype");
   a.lda = (int64_t)lay->H * lay->G * lay->d_head;
-  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H * lay->G);
+  const dim3 grid((T + kRopeRows - 1) / kRopeRows, (lay->H * lay->G + kRopeHeads - 1) / kRopeHeads);
   if (q_lat_dtype == FDC_F32)
     hipLaunchKernelGGL((rope_compress_kernel<float, false>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
   else
@@ -1446,7 +1469,7 @@ fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* 
   if (!tok_batch) FDC_FAIL(FDC_INVALID_ARG, "fdc_rope_compress_keys: tok_batch is NULL");
   a.tok_batch = tok_batch;
   a.cache_fp8 = lay->dtype == FDC_FP8;
-  const dim3 grid((T + kRopeRows - 1) / kRopeRows, lay->H);
+  const dim3 grid((T + kRopeRows - 1) / kRopeRows, (lay->H + kRopeHeads - 1) / kRopeHeads);
   hipLaunchKernelGGL((rope_compress_kernel<uint16_t, true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
