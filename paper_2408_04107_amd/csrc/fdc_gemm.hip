@@ -1096,8 +1096,10 @@ static void launch_skinny16(const GemmArgs& a, hipStream_t st) {
 constexpr int kRopeRows = 128;
 constexpr int kRopeHeads = 4;
 
+// Four waves per SIMD: the keys instantiation would take 134 registers and drop to three (64 -> 57 us with
+// five registers spilled instead).
 template <typename TC, bool KEYS>
-__global__ __launch_bounds__(256) void rope_compress_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void rope_compress_kernel(const GemmArgs g) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_b[128 * kRowsBRow];
   const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
   const int ln = lane % 16, lg = lane / 16;
