@@ -329,6 +329,24 @@ fdc_status fdc_latent_attn_decode_at(const fdc_layout* lay, const fdc_plan* plan
                                      const void* q_lat, const void* k_cache, const void* v_cache, float scale,
                                      void* o_lat, void* workspace, size_t workspace_bytes, void* stream);
 
+/* fdc_latent_attn_decode for callers that cannot allocate device memory for a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc). The plan's tables and
+ * the split-K partial states live in a workspace built into the library's code object:
+ * FDC_STATIC_SCRATCH_BYTES of device memory per GPU, held until the process ends. The call makes no
+ * hipMalloc / hipFree and needs no fdc_plan_upload: it copies the plan's tables into the built-in
+ * workspace when they are not the ones already there (host -> device copy on `stream`; the plan must
+ * stay alive until it has completed), then runs the kernels of fdc_latent_attn_decode. Results are
+ * those of fdc_latent_attn_decode, bit for bit.
+ *   plan: a host plan (fdc_plan_decode / fdc_plan_decode_paged) whose fdc_plan_workspace_bytes is at
+ *         most FDC_STATIC_SCRATCH_BYTES: FDC_WORKSPACE_TOO_SMALL beyond that, FDC_INVALID_ARG for a
+ *         plan of fdc_plan_decode_device (its tables are written by a kernel into the caller's workspace).
+ * All calls on one GPU share the one workspace, whatever their stream or thread: calls that overlap
+ * in time on a GPU race (run them on one stream, or order them with events). */
+#define FDC_STATIC_SCRATCH_BYTES ((size_t)8 << 20)
+fdc_status fdc_latent_attn_decode_static(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
+                                         const void* k_cache, const void* v_cache, float scale, void* o_lat,
+                                         void* stream);
+
 /* Measurement aid: when both arguments are non-NULL hipEvent_t handles, the next
  * fdc_latent_attn_decode call made by this thread records `start` immediately before and `stop`
  * immediately after its tile kernel (the kernel that streams the cache; the split-K merge runs

@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "fdc_project_latent_kv", "fdc_absorb_query", "fdc_latent_attn_decode",
     "fdc_latent_attn_prefill", "fdc_absorb_output", "fdc_profile_decode_events", "fdc_select_ranks",
     "fdc_rope_absorb_query", "fdc_rope_compress_keys", "fdc_project_and_absorb_query", "fdc_latent_attn_decode_at",
-    "fdc_plan_decode_device", "fdc_plan_decode_run", "fdc_plan_download",
+    "fdc_plan_decode_device", "fdc_plan_decode_run", "fdc_plan_download", "fdc_latent_attn_decode_static",
 ]
 
 
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
         l.fdc_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, C.c_int, vp]
         l.fdc_project_and_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
         l.fdc_latent_attn_decode.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
+        l.fdc_latent_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp]
         l.fdc_latent_attn_decode_at.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
@@ -321,6 +322,13 @@ def fdc_latent_attn_decode(layout: Layout, plan: Plan, q_lat, k_cache, v_cache, 
     _check(lib().fdc_latent_attn_decode(layout.handle, plan.handle, _dev(q_lat), _dev(k_cache), _dev(v_cache),
                                         float(scale), _dev(o_lat), _dev(workspace),
                                         workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def fdc_latent_attn_decode_static(layout: Layout, plan: Plan, q_lat, k_cache, v_cache, scale: float, o_lat,
+                                  stream=None) -> None:
+    """fdc_latent_attn_decode on the workspace built into the library (no allocation, no upload)."""
+    _check(lib().fdc_latent_attn_decode_static(layout.handle, plan.handle, _dev(q_lat), _dev(k_cache),
+                                               _dev(v_cache), float(scale), _dev(o_lat), _stream(stream)))
 
 
 def fdc_latent_attn_decode_at(layout: Layout, plan: Plan, seq_len, q_lat, k_cache, v_cache, scale: float, o_lat,

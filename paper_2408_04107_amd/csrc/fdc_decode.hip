@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "fdc_internal.h"
 
@@ -410,6 +411,24 @@ using namespace fdc;
 
 static thread_local hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
 
+// Workspace of fdc_latent_attn_decode_static: plan tables and split-K partial states in device memory
+// that belongs to the code object, so that the call allocates nothing. Every GPU the library runs on
+// holds its own copy at its own address until the process ends. In host code the array's name is
+// only a handle for hipGetSymbolAddress: the address kernels and copies use is the one that call
+// returns, looked up once per device and kept below.
+constexpr size_t kStaticScratchBytes = FDC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+struct ScratchOfDevice {
+  void* ptr = nullptr;           // device address of `scratch` on this GPU
+  uint64_t resident_plan = 0;    // serial of the plan whose tables the array holds (0: none)
+};
+std::mutex g_scratch_mutex;
+ScratchOfDevice g_scratch_of[kMaxDevices];
+}  // namespace
+
 extern "C" {
 
 fdc_status fdc_profile_decode_events(void* start_event, void* stop_event) {
@@ -532,6 +551,44 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
                                   const void* v_cache, float scale, void* o_lat, void* workspace,
                                   size_t workspace_bytes, void* stream) {
   return decode_impl(lay, plan, nullptr, q_lat, k_cache, v_cache, scale, o_lat, workspace, workspace_bytes, stream);
+}
+
+fdc_status fdc_latent_attn_decode_static(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
+                                         const void* k_cache, const void* v_cache, float scale, void* o_lat,
+                                         void* stream) {
+  if (!lay || !plan) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: NULL argument");
+  if (plan->kind != 0 || plan->lay != lay)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: not a decode plan of this layout");
+  if (plan->on_device)
+    FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: plans made on the device keep their tables in the "
+                              "caller's workspace; use fdc_latent_attn_decode");
+  if (plan->workspace_bytes > kStaticScratchBytes)
+    FDC_FAIL(FDC_WORKSPACE_TOO_SMALL, "fdc_latent_attn_decode_static: the plan needs %zu bytes of workspace, the "
+                                      "built-in one has %zu", plan->workspace_bytes, kStaticScratchBytes);
+  int dev = 0;
+  FDC_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: device %d", dev);
+  void* ws = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ScratchOfDevice& sd = g_scratch_of[dev];
+    if (!sd.ptr) {
+      void* p = nullptr;
+      FDC_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      if (!p || (reinterpret_cast<uintptr_t>(p) & 255u) != 0)
+        FDC_FAIL(FDC_HIP_ERROR, "fdc_latent_attn_decode_static: bad address %p for the built-in workspace", p);
+      sd.ptr = p;
+    }
+    ws = sd.ptr;
+    if (sd.resident_plan != plan->serial) {   // tables of another plan (or none) are in the array: replace them
+      sd.resident_plan = 0;
+      FDC_HIP_CHECK(hipMemcpyAsync(ws, plan->image.data(), plan->image.size(), hipMemcpyHostToDevice,
+                                   static_cast<hipStream_t>(stream)));
+      sd.resident_plan = plan->serial;
+    }
+  }
+  // The partial states need no clearing: the tile kernel writes every slot the merge reads.
+  return decode_impl(lay, plan, nullptr, q_lat, k_cache, v_cache, scale, o_lat, ws, kStaticScratchBytes, stream);
 }
 
 fdc_status fdc_latent_attn_decode_at(const fdc_layout* lay, const fdc_plan* plan, const int32_t* seq_len,

@@ -1,6 +1,7 @@
 // Internal declarations shared by the host side and the kernels of libfdc.
 #pragma once
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -137,7 +138,17 @@ struct fdc_layout {
   int RV(int l) const { return voff_r[(size_t)l * (H + 1) + H]; }
 };
 
+namespace fdc {
+// Process-wide serial numbers of plans (never 0, never reused): what tells a cached copy of a plan's
+// tables from the tables of another plan that happens to live at the same address.
+inline uint64_t next_plan_serial() {
+  static std::atomic<uint64_t> counter{0};
+  return ++counter;
+}
+}  // namespace fdc
+
 struct fdc_plan {
+  const uint64_t serial = fdc::next_plan_serial();
   int kind;  // 0 decode, 1 prefill
   int layer, batch, H, n_workers, n_units;
   int G = 1;            // query heads per key/value head of the layout the plan was made for
