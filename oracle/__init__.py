@@ -18,8 +18,10 @@ Modules
 Pin status: every function is pinned by the CPU tests (full-rank equals
 standard attention, exact-rank equals uncompressed attention, closed forms,
 brute force, scheduling invariants and the paper's worked scheduling example),
-except that the KV-chunk splitting of the decode planner and the causal-cost
-mode of the prefill planner extend the paper: those parts are pinned only by
-invariants (coverage, load sums, list-scheduling bounds), i.e. "parity
-unpinned" by the paper itself.
+The KV-chunk splitting of the decode planner, the softmax weight and the
+causal-cost mode of the prefill planner extend the paper (it prints no numbers
+for them): besides the invariants (coverage, load sums, list-scheduling bounds)
+each of their decisions -- the fit rule and its tie, the order of equal-cost
+chunks, the cost formulas, the hand-out order -- is pinned by schedules worked
+out by hand from the stated reading (tests/test_oracle_planner.py).
 """

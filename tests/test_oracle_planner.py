@@ -120,6 +120,114 @@ def test_decode_no_split_is_one_task_per_head_sorted_descending():
     assert plan["worker_load"].tolist() == [334100, 179900, 84500 + 34300 + 4160 + 3136, 63700 + 45500 + 16448]
 
 
+def _worker_lists(plan, W, key="worker_tiles"):
+    return [plan[key][plan["worker_ptr"][w]:plan["worker_ptr"][w + 1]].tolist() for w in range(W)]
+
+
+def test_decode_split_room_of_half_a_step_rounds_up_hand_worked():
+    # Divisible-work extension. One head, rk = rv = 16: d_sum = 33, one granule of 64 tokens costs
+    # step = 2112. Sequences of 256 and 64 tokens on W = 2: total = 320 * 33 = 10560, mean = 5280
+    # = 2.5 steps. Chunks in descending cost: the 256-token unit (8448), then the 64-token unit (2112).
+    #   8448 -> worker 0 (load 0): room 5280 = 2.5 steps, nearest granule count is a tie, ties go UP:
+    #           3 granules = 192 tokens stay, load 6336; the other 64 tokens go on
+    #        -> worker 1 (load 0): room 2.5 steps, they fit: load 2112
+    #   2112 -> worker 1 (2112 < 6336): room 5280 - 2112 = 3168 = 1.5 steps -> 2 granules, fits: load 4224
+    # (Ties down would cut the first unit at 128 and send the short unit to worker 0.)
+    plan = op.plan_decode([256, 64], [16], [16], 2, granule=64, min_split=1, split=True)
+    assert plan["tile_t0"].tolist() == [0, 192, 0] and plan["tile_t1"].tolist() == [192, 256, 64]
+    assert plan["tile_b"].tolist() == [0, 0, 1]
+    assert plan["tile_cost"].tolist() == [6336, 2112, 2112]
+    assert plan["unit_tile_ptr"].tolist() == [0, 2, 3]
+    assert _worker_lists(plan, 2) == [[0], [1, 2]]
+    assert plan["worker_load"].tolist() == [6336, 4224]
+    # a room below half a step still takes one granule: 3 workers, sequences 192 and 64:
+    # total 8448, mean 2816 = 1.33 steps. 6336 -> w0 keeps 1 granule (1.33 -> 1), load 2112; the rest (128)
+    # -> w1 keeps 1 granule, load 2112; the rest (64) -> w2, load 2112. Then 2112 -> w0 (all equal, lowest
+    # id): room 704 = 0.33 steps -> 0 granules, raised to one: load 4224.
+    plan = op.plan_decode([192, 64], [16], [16], 3, granule=64, min_split=1, split=True)
+    assert plan["tile_t0"].tolist() == [0, 64, 128, 0] and plan["tile_t1"].tolist() == [64, 128, 192, 64]
+    assert _worker_lists(plan, 3) == [[0, 3], [1], [2]]
+    assert plan["worker_load"].tolist() == [4224, 2112, 2112]
+
+
+def test_decode_equal_cost_chunks_go_out_lowest_id_first_hand_worked():
+    # The paper's rule (no splitting), one head of d_sum 33, W = 2, sequences 64, 64, 64, 128.
+    # Costs 2112, 2112, 2112, 4224. Sorted: unit 3, then the three equal ones in id order 0, 1, 2.
+    #   unit 3 -> w0 (4224); unit 0 -> w1 (2112); unit 1 -> w1 (2112 < 4224; 4224);
+    #   unit 2 -> loads equal, lowest worker: w0 (6336).
+    plan = op.plan_decode([64, 64, 64, 128], [16], [16], 2, split=False)
+    assert _worker_lists(plan, 2) == [[3, 2], [0, 1]]
+    assert plan["worker_load"].tolist() == [6336, 4224]
+    # Equal-cost chunks of ONE unit (min_split = 2, splitting on): 256 tokens -> chunks [0,128), [128,256)
+    # of cost 4224 each; mean = 4224 = 2 steps. Chunk 0 first -> w0 (room 2 steps: fits), chunk 1 -> w1.
+    plan = op.plan_decode([256], [16], [16], 2, granule=64, min_split=2, split=True)
+    assert plan["tile_t0"].tolist() == [0, 128] and plan["tile_t1"].tolist() == [128, 256]
+    assert _worker_lists(plan, 2) == [[0], [1]]
+    # Two heads of equal d_sum (16 + 32 + 1 = 32 + 16 + 1 = 49), one sequence: head 0 goes out first.
+    plan = op.plan_decode([128], [16, 32], [32, 16], 2, split=False)
+    assert plan["tile_cost"].tolist() == [6272, 6272] and _worker_lists(plan, 2) == [[0], [1]]
+
+
+def test_decode_softmax_cost_replaces_the_plus_one_hand_worked():
+    # d_sum = rk + rv + softmax_cost. Heads A (16 + 16) and B (64 + 64); sequences 400 and 110; W = 2, no split.
+    #               softmax_cost 1 (paper): d_sum 33 / 129     softmax_cost 7: d_sum 39 / 135
+    #   tile 0 (b0, A)   13200                                   15600
+    #   tile 1 (b0, B)   51600                                   54000
+    #   tile 2 (b1, A)    3630                                    4290
+    #   tile 3 (b1, B)   14190                                   14850
+    # paper:  1 -> w0; then 3, 0, 2 all to w1 (14190, 27390, 31020 < 51600)
+    # cost 7: 1 -> w0; then 0, 3, 2 all to w1 (15600, 30450, 34740 < 54000): tiles 0 and 3 swap places
+    plan = op.plan_decode([400, 110], [16, 64], [16, 64], 2, split=False)
+    assert plan["tile_cost"].tolist() == [13200, 51600, 3630, 14190]
+    assert _worker_lists(plan, 2) == [[1], [3, 0, 2]] and plan["worker_load"].tolist() == [51600, 31020]
+    plan = op.plan_decode([400, 110], [16, 64], [16, 64], 2, split=False, softmax_cost=7)
+    assert plan["tile_cost"].tolist() == [15600, 54000, 4290, 14850]
+    assert _worker_lists(plan, 2) == [[1], [0, 3, 2]] and plan["worker_load"].tolist() == [54000, 34740]
+    # with splitting the granule step scales too: rk = rv = 16, softmax_cost 7 -> d_sum 39, step 2496;
+    # sequences 256 and 64 on two workers: mean = 320 * 39 / 2 = 6240 = 2.5 steps -> same cuts as with d_sum 33
+    plan = op.plan_decode([256, 64], [16], [16], 2, granule=64, split=True, softmax_cost=7)
+    assert plan["tile_t1"].tolist() == [192, 256, 64] and plan["tile_cost"].tolist() == [7488, 2496, 2496]
+    assert plan["worker_load"].tolist() == [7488, 4992]
+
+
+def test_prefill_causal_mode_costs_and_hand_out_order_hand_worked():
+    # Causal cost mode: a task costs d_sum * (number of (query row, visible key) pairs); ALL tasks are handed
+    # out in descending cost order (ties: lower task id) to the least-loaded worker (ties: lower id).
+    # Heads: d_sum 33 (16 + 16 + 1) and 97 (48 + 48 + 1); base row block 16:
+    #   B_r = [round_up_16(ceil(16 * 97 / 33) = 48) = 48, 16]. One prompt of 64 tokens.
+    # Row i sees i + 1 keys; rows [a, b) see b(b+1)/2 - a(a+1)/2 pairs:
+    #   task 0  h0 [0, 48)   1176 pairs * 33 = 38808
+    #   task 1  h0 [48, 64)   904 pairs * 33 = 29832
+    #   task 2  h1 [0, 16)    136 pairs * 97 = 13192
+    #   task 3  h1 [16, 32)   392 pairs * 97 = 38024
+    #   task 4  h1 [32, 48)   648 pairs * 97 = 62856
+    #   task 5  h1 [48, 64)   904 pairs * 97 = 87688
+    # order 5, 4, 0, 3, 1, 2 on W = 2:  5 -> w0 (87688); 4 -> w1 (62856); 0 -> w1 (101664);
+    #   3 -> w0 (125712); 1 -> w1 (131496); 2 -> w0 (138904)
+    plan = op.plan_prefill([64], [64], [16, 48], [16, 48], 2, br_base=16, br_cap=256, cost_mode="causal")
+    assert plan["br"].tolist() == [48, 16]
+    assert list(zip(plan["task_h"].tolist(), plan["task_q0"].tolist(), plan["task_q1"].tolist())) == \
+        [(0, 0, 48), (0, 48, 64), (1, 0, 16), (1, 16, 32), (1, 32, 48), (1, 48, 64)]
+    assert plan["task_cost"].tolist() == [38808, 29832, 13192, 38024, 62856, 87688]
+    assert _worker_lists(plan, 2, "worker_tasks") == [[5, 3, 2], [4, 0, 1]]
+    assert plan["worker_load"].tolist() == [138904, 131496]
+    # the paper's mode on the same input: cost rows * s_kv * d_sum, rounds in task order
+    paper = op.plan_prefill([64], [64], [16, 48], [16, 48], 2, br_base=16, br_cap=256, cost_mode="paper")
+    assert paper["task_cost"].tolist() == [48 * 64 * 33, 16 * 64 * 33] + [16 * 64 * 97] * 4
+    assert _worker_lists(paper, 2, "worker_tasks") == [[0, 2, 4], [1, 3, 5]]
+    # chunked prompt: the 32 queries are positions 68..99 of 100 keys, row i sees 69 + i keys.
+    # one head (d_sum 33, B_r 16): [0,16) = 16*69 + 120 = 1224 pairs, [16,32) = 16*85 + 120 = 1480 pairs
+    plan = op.plan_prefill([32], [100], [16], [16], 2, br_base=16, br_cap=16, cost_mode="causal")
+    assert plan["task_cost"].tolist() == [1224 * 33, 1480 * 33]
+    assert _worker_lists(plan, 2, "worker_tasks") == [[1], [0]]
+    # equal costs (two heads of d_sum 49, one block each): the lower task id goes first, to the lower worker;
+    # with softmax_cost 7 both are 55 * 136
+    plan = op.plan_prefill([16], [16], [16, 32], [32, 16], 2, br_base=16, br_cap=16, cost_mode="causal")
+    assert plan["task_cost"].tolist() == [136 * 49] * 2 and _worker_lists(plan, 2, "worker_tasks") == [[0], [1]]
+    plan = op.plan_prefill([16], [16], [16, 32], [32, 16], 2, br_base=16, br_cap=16, cost_mode="causal", softmax_cost=7)
+    assert plan["task_cost"].tolist() == [136 * 55] * 2
+
+
 def test_lpt_tie_breaks():
     lists, loads = op.lpt_assign([5, 5, 5, 5], 3)
     assert lists == [[0, 3], [1], [2]] and loads == [10, 5, 5]
