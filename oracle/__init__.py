@@ -17,7 +17,7 @@ Modules
 
 Pin status: every function is pinned by the CPU tests (full-rank equals
 standard attention, exact-rank equals uncompressed attention, closed forms,
-brute force, scheduling invariants and the paper's worked scheduling example),
+brute force, scheduling invariants and the paper's worked scheduling example).
 The KV-chunk splitting of the decode planner, the softmax weight and the
 causal-cost mode of the prefill planner extend the paper (it prints no numbers
 for them): besides the invariants (coverage, load sums, list-scheduling bounds)
