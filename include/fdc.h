@@ -311,7 +311,10 @@ fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* 
  *   q_lat [batch, RK] f32, o_lat [batch, RV] f32, scale > 0 and finite, normally 1/sqrt(d_head)
  *   (FDC_INVALID_ARG otherwise; the same holds for fdc_latent_attn_prefill).
  *   workspace: prepared by fdc_plan_upload for this plan. Sequences with seq_len 0 give zeros.
- * Calls that share a workspace must not overlap in time. */
+ * Calls that share a workspace must not overlap in time.
+ * Precision: multi-head layouts keep q', the scores and the softmax weights in fp32. Grouped-query
+ * layouts run both products on the matrix core: q' enters as the sum of two bf16 terms (16 bits of
+ * its mantissa), the softmax weights as bf16, sums are fp32. */
 fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
                                   const void* k_cache, const void* v_cache, float scale, void* o_lat,
                                   void* workspace, size_t workspace_bytes, void* stream);
@@ -367,7 +370,10 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
  *   mode FDC_FOLD : M_h = B_v^h . W_o^h for every head; Bv [RV, d_head], Wo_t, Mt all layout dtype
  *                   (Mt fp32 in an FDC_F32 layout). o_lat, y ignored.
  *   mode FDC_APPLY: y [T, d_model] = o_lat [T, RV] . M;  o_lat_dtype / y_dtype say how they are
- *                   stored. Bv, Wo_t ignored. */
+ *                   stored. Bv, Wo_t ignored. In a bf16 / E4M3 layout the product runs on the matrix
+ *                   core with bf16 operands: an fp32 o_lat is rounded to bf16 on its way in (the
+ *                   precision Mt itself has), sums are fp32. The same holds for fp32 activations of
+ *                   the other projections. */
 enum { FDC_FOLD = 0, FDC_APPLY = 1 };
 fdc_status fdc_absorb_output(const fdc_layout* lay, int layer, int mode, const void* Bv, const void* Wo_t,
                              void* Mt, const void* o_lat, fdc_dtype o_lat_dtype, int T, void* y,

@@ -111,17 +111,31 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
   const uint32_t rk2 = (uint32_t)rk * ES, rv2 = (uint32_t)rv * ES;   // bytes per cached row
   constexpr uint32_t kOob = 0x80000000u;
 
-  // Q' operand: lane (ln, lg) holds k = 32 ks + 8 lg .. + 8 of query ln (zero rows past the group)
-  GqFrag qf[KS];
+  // Q' operand: lane (ln, lg) holds k = 32 ks + 8 lg .. + 8 of query ln (zero rows past the group).
+  // q' arrives in fp32 and a bf16 operand keeps 8 bits of it, which alone would put the scores of a
+  // peaked softmax outside the output tolerance; so q' = qf + ql with qf = bf16(q') and
+  // ql = bf16(q' - qf) (16 bits together), and the score product is taken with both. The matrix
+  // core is idle most of the time in this kernel (the stream is the limit), the second product is free.
+  GqFrag qf[KS], ql[KS];
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
     const int col = ES == 2 ? 32 * ks + 8 * lg : 64 * (ks / 2) + 16 * lg + 8 * (ks % 2);
     if (ln < g && col < rk) {
       const float* qp = q_lat + td.q_elem + ln * rk + col;
       const float4 a = *reinterpret_cast<const float4*>(qp), b = *reinterpret_cast<const float4*>(qp + 4);
-      qf[ks].u = gq_u32x4{gq_pack(a.x, a.y), gq_pack(a.z, a.w), gq_pack(b.x, b.y), gq_pack(b.z, b.w)};
+      const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      float r[8];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t hi = gq_pack(v[2 * e], v[2 * e + 1]);
+        qf[ks].u[e] = hi;
+        r[2 * e] = v[2 * e] - __uint_as_float(hi << 16);
+        r[2 * e + 1] = v[2 * e + 1] - __uint_as_float(hi & 0xffff0000u);
+      }
+      ql[ks].u = gq_u32x4{gq_pack(r[0], r[1]), gq_pack(r[2], r[3]), gq_pack(r[4], r[5]), gq_pack(r[6], r[7])};
     } else {
       qf[ks].u = gq_u32x4{0, 0, 0, 0};
+      ql[ks].u = gq_u32x4{0, 0, 0, 0};
     }
   }
 
@@ -176,11 +190,13 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
         GqFrag kf;
         if constexpr (ES == 2) {
           kf.u = kreg[nb][j][0];
-          st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0].v, gq_f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[0].v, gq_f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[0].v, st[nb][j], 0, 0, 0);
 #pragma unroll
           for (int ks = 1; ks < M; ++ks) {
             if (ks >= rk32) break;
             kf.u = kreg[nb][j][ks];
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[ks].v, st[nb][j], 0, 0, 0);
             st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[ks].v, st[nb][j], 0, 0, 0);
           }
         } else {
@@ -191,8 +207,10 @@ __device__ __forceinline__ void gqa_tile(const DecTile& td, const float* __restr
             gq_u32x4 lo, hi;
             gq_widen16(kreg[nb][j][kl], lo, hi);
             kf.u = lo;
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[2 * kl].v, st[nb][j], 0, 0, 0);
             st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[2 * kl].v, st[nb][j], 0, 0, 0);
             kf.u = hi;
+            st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, ql[2 * kl + 1].v, st[nb][j], 0, 0, 0);
             st[nb][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[2 * kl + 1].v, st[nb][j], 0, 0, 0);
           }
         }

@@ -239,7 +239,7 @@ def test_decode_at_actual_lengths_on_a_plan_for_rounded_up_lengths(W, granule, m
     q_lat = torch.from_numpy((rng.standard_normal((B, g * cache.RK)) * 2.0).astype(np.float32)).cuda()
     scale = 1.0 / math.sqrt(d_h)
     qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
-    q_used = q_lat.cpu().numpy().astype(np.float64) if g == 1 else q_lat.to(torch.bfloat16).to(torch.float64).cpu().numpy()
+    q_used = q_lat.cpu().numpy().astype(np.float64)
     keep = {(b, h, s): cache.unit(s, b, h).clone() for b in range(B) for h in range(H) for s in "kv"}
     for back in (0, 1, granule // 2, granule - 1):
         actual = [max(p - back, 0) if p else 0 for p in planned]

@@ -118,8 +118,7 @@ def test_decode_attention_on_e4m3_codes(W, granule, min_split, g):
         fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
     torch.cuda.synchronize()
     out = o_lat.cpu().numpy().astype(np.float64)
-    # the grouped kernel feeds q' to the matrix core as bf16
-    q64 = (q_lat if g == 1 else q_lat.to(BF)).to(torch.float64).cpu().numpy()
+    q64 = q_lat.to(torch.float64).cpu().numpy()
     qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     got_all, ref_all = [], []
     for b, n in enumerate(seq):

@@ -170,12 +170,11 @@ def test_absorb_output_fold_and_apply(case, dtype, io):
     torch.cuda.synchronize()
     # apply is checked on the stored Mt (the oracle of this call), heads = column blocks of o_lat
     M_stored = f64(Mt).T
-    o64 = f64(o_lat)
-    if dtype == fdc.FDC_BF16 and o_dt == fdc.FDC_F32:
-        o64 = gen.round_to_bf16(o64)     # the MFMA path reads fp32 activations as bf16 operands
+    o64 = f64(o_lat)                     # as passed: fp32 activations become bf16 MFMA operands inside the call
     y_ref = oa.apply_output([o64[:, off[h]:off[h + 1]] for h in range(H)],
                             [M_stored[off[h]:off[h + 1]] for h in range(H)])
-    tol = 5e-6 if (dtype == fdc.FDC_F32) else (5e-3 if y_dt == fdc.FDC_BF16 else 2e-5)
+    # bf16 layouts: operands (and a bf16 y) carry 2^-9 roundings, the spec bar; an fp32 layout is exact to fp32
+    tol = 5e-6 if (dtype == fdc.FDC_F32) else 5e-3
     ma, rl = assert_close(f64(y), y_ref, "y", rel_l2_tol=tol)
     say(f"  apply max_abs={ma:.2e} rel_l2={rl:.2e}")
 

@@ -64,7 +64,7 @@ def run_gqa_decode(rk, rv, g, seq, W, min_split=1, split=1, granule=64, q_gain=1
     fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)
     torch.cuda.synchronize()
     out = o_lat.cpu().numpy().astype(np.float64)
-    q_used = f64(q_lat.to(BF))           # the operand of the score product
+    q_used = f64(q_lat)      # the fp32 q' the caller passed (the kernel's bf16 operand rounding is inside the tolerance)
     qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     units = check_units if check_units is not None else [(b, h) for b in range(B) for h in range(H)]
     got_all, ref_all = [], []
@@ -186,7 +186,7 @@ def test_gqa_absorb_query_fold_apply_and_rope(g, T):
         y = torch.full((T, d), float("nan"), dtype=BF, device="cuda:0")
         fdc.fdc_absorb_output(lay, 0, fdc.FDC_APPLY, None, None, Mt, o_lat, dt, T, y, fdc.FDC_BF16)
         torch.cuda.synchronize()
-        ref = f64(o_lat.to(BF)) @ f64(Mt).T                        # operands enter the product as bf16
+        ref = f64(o_lat) @ f64(Mt).T                               # o' as passed (fp32 o' becomes a bf16 operand inside the call)
         ma, rl = assert_close(f64(y), ref, "y")
         say(f"  apply dtype={dt} max_abs={ma:.2e} rel_l2={rl:.2e}")
     # post-RoPE query rotation with the rotation of the key/value head

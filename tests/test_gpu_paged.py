@@ -77,7 +77,7 @@ def test_paged_decode(g, P, granule, W, min_split):
     torch.cuda.synchronize()
     out = o_lat.cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(out))
-    q_used = q_lat.to(torch.float64).cpu().numpy() if g == 1 else q_lat.to(BF).to(torch.float64).cpu().numpy()
+    q_used = q_lat.to(torch.float64).cpu().numpy()
     qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     kbuf, vbuf = cache.k.to(torch.float64).cpu().numpy(), cache.v.to(torch.float64).cpu().numpy()
     got_all, ref_all = [], []

@@ -100,8 +100,7 @@ def test_decode_random_combination(seed):
     torch.cuda.synchronize()
     out = o_lat.cpu().numpy().astype(np.float64)
     assert np.all(np.isfinite(out)), "some output was never written"
-    # the grouped kernel feeds q' to the matrix core as bf16
-    q64 = (q_lat if g == 1 else q_lat.to(torch.bfloat16)).to(torch.float64).cpu().numpy()
+    q64 = q_lat.to(torch.float64).cpu().numpy()
     qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     koff, voff = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
 
