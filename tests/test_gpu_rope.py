@@ -115,19 +115,41 @@ def test_rope_compress_keys_and_v_only_projection(case):
     say(f"  V' max_abs={ma:.2e} rel_l2={rl:.2e}")
 
 
+def exact_rotations(H, d_h, g):
+    """Orthogonal matrices whose entries bf16 holds exactly: a Sylvester Hadamard matrix scaled by
+    1/sqrt(d_h) (d_h a power of four: entries +-2^-k), with rows and columns permuted and signs flipped
+    per head. With such an R the rotation handed to the library IS orthogonal, so the identity of
+    Section 3 holds for the library's input and not only for its unrounded ancestor."""
+    Hm = np.array([[1.0]])
+    while Hm.shape[0] < d_h:
+        Hm = np.block([[Hm, Hm], [Hm, -Hm]])
+    assert Hm.shape[0] == d_h and math.sqrt(d_h) == int(math.sqrt(d_h))
+    out = []
+    for _ in range(H):
+        R = Hm[g.permutation(d_h)][:, g.permutation(d_h)] * g.choice([-1.0, 1.0], size=(1, d_h)) / math.sqrt(d_h)
+        assert np.allclose(R @ R.T, np.eye(d_h), atol=1e-12) and np.array_equal(gen.round_to_bf16(R), R)
+        out.append(R)
+    return out
+
+
 def test_post_rope_decode_chain_full_rank_equals_rope_attention():
     """Keys rotated and compressed into the cache, query absorbed, decode attention: at full rank the
-    result is standard RoPE attention on the uncompressed keys (Section 3 identity), up to bf16."""
+    result is standard RoPE attention on the uncompressed keys (Section 3 identity). The reference is
+    computed in float64 from the raw inputs (k, q, angles), so the error is what the chain's bf16
+    roundings add: the rotated key and query as matrix-core operands and the stored K' (three roundings
+    of score operands: ds = sqrt(3) * 1.13e-3 * |s| with |s| about 1 here, and a score error ds moves the
+    output by about ds relative), i.e. about 2e-3; the bar is the benchmark spec's 5e-3."""
     say("post-RoPE decode chain at full rank")
     g = gen.make_rng(7)
     H, d_h, S, d = 4, 64, 333, 128
     rk = [d_h] * H
     lay = fdc.Layout(1, H, d, d_h, [rk], [rk], 1, S, fdc.FDC_BF16)
     cache = Cache(lay)
-    Rs, R_t = rotations(H, d_h, rk, g)
+    Rs = exact_rotations(H, d_h, g)
+    R_t = np.concatenate([R.T for R in Rs], axis=0)
     cos, sin = orp.rope_tables(S, d_h)
     k = dev(g.standard_normal((S, H, d_h)), BF)
-    q = dev(g.standard_normal((1, H, d_h)) * 2.0, BF)
+    q = dev(g.standard_normal((1, H, d_h)), BF)
     zero = torch.zeros(S, dtype=torch.int32, device="cuda:0")
     pos = torch.arange(S, dtype=torch.int32, device="cuda:0")
     cs, sn, R_d = dev(cos, torch.float32), dev(sin, torch.float32), dev(R_t, BF)
@@ -150,5 +172,5 @@ def test_post_rope_decode_chain_full_rank_equals_rope_attention():
         Kp = orp.rope(f64(k)[:, h, :], np.arange(S), cos32, sin32)
         qp = orp.rope(f64(q)[:, h, :], [S - 1], cos32, sin32)[0]
         ref.append(oa.latent_attn_decode(qp, Kp, cache.unit_f64("v", 0, h, S), scale))   # uncompressed RoPE attention
-    ma, rl = assert_close(f64(o_lat)[0], np.concatenate(ref), "o' vs RoPE attention", rel_l2_tol=1.5e-2)
+    ma, rl = assert_close(f64(o_lat)[0], np.concatenate(ref), "o' vs RoPE attention")
     say(f"  max_abs={ma:.2e} rel_l2={rl:.2e}")
