@@ -266,10 +266,17 @@ void fdc_plan_destroy(fdc_plan* plan);
  *                                               heads (head-major), then all V heads
  *   k_cache, v_cache    the layer's K' / V' buffers (sizes from fdc_layout_tables)
  * k_cache may be NULL: then A_cat_t holds only the RV value rows and only V' is written (post-RoPE
- * path, where K' comes from fdc_rope_compress_keys). T = 0 is a no-op. */
+ * path, where K' comes from fdc_rope_compress_keys). T = 0 is a no-op.
+ *   status   device int32 (4-byte aligned) or NULL. tok_batch and tok_pos are device data the host
+ *            cannot check: a row whose tok_batch is outside [0, max_batch) or whose tok_pos is outside
+ *            [0, max_seq) is SKIPPED by the kernel (nothing is stored for it, every other row is written
+ *            as usual) and, when status is not NULL, FDC_FAULT_TOK_BATCH / FDC_FAULT_TOK_POS is OR-ed into
+ *            *status. The caller clears the word and reads it when it likes; the call itself still
+ *            returns FDC_OK. The other cache writers below take the same argument. */
+enum { FDC_FAULT_TOK_BATCH = 1, FDC_FAULT_TOK_POS = 2 };
 fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x, int T,
                                  const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
-                                 void* k_cache, void* v_cache, void* stream);
+                                 void* k_cache, void* v_cache, int32_t* status, void* stream);
 
 /* q'_h = q_h . (B_k^h)^T per head (Section 2: Q K^T = E (W_Q B_K^T) K'^T).
  *   q      [T, H, d_head]        layout dtype
@@ -285,7 +292,7 @@ fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int
 fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const void* x, int T,
                                         const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
                                         void* k_cache, void* v_cache, const void* q, const void* Bk, void* q_lat,
-                                        fdc_dtype q_lat_dtype, void* stream);
+                                        fdc_dtype q_lat_dtype, int32_t* status, void* stream);
 
 /* Post-RoPE compression of Q and K (Section 5.1; steps 5 and 6 of the design overview): RoPE, then
  * the common rotation R of the head truncated to its first r_h columns, (Q_p R_p)(K_p R_p)^T ~= Q_p K_p^T.
@@ -298,13 +305,17 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
  *                              rotated by the angle whose cosine / sine is cos_t[p, i] / sin_t[p, i]
  *   R_t       [RK, d_head]     head h = rows koff_r[h] .. koff_r[h+1]: the first rk[h] columns of R^h,
  *                              one kept direction per row (the layout of Bk)
- *   q_lat     [T, RK] (q_lat_dtype);   k_cache: the layer's K' buffer. */
+ *   q_lat     [T, RK] (q_lat_dtype);   k_cache: the layer's K' buffer.
+ *   status    as for fdc_project_latent_kv: a row whose tok_pos has no angle (outside [0, n_pos)), and a key
+ *             row whose tok_batch / tok_pos lies outside the cache, is skipped (its q_lat row / cache row
+ *             is left untouched) and flagged. */
 fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const int32_t* tok_pos,
                                  const float* cos_t, const float* sin_t, int n_pos, const void* R_t,
-                                 void* q_lat, fdc_dtype q_lat_dtype, void* stream);
+                                 void* q_lat, fdc_dtype q_lat_dtype, int32_t* status, void* stream);
 fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* k, int T,
                                   const int32_t* tok_batch, const int32_t* tok_pos, const float* cos_t,
-                                  const float* sin_t, int n_pos, const void* R_t, void* k_cache, void* stream);
+                                  const float* sin_t, int n_pos, const void* R_t, void* k_cache, int32_t* status,
+                                  void* stream);
 
 /* Decode attention on the latent cache, one query per sequence (Section 5, step 7; Section 5.3
  * decode scheduling): o'_h = softmax_t(scale * <q'_h, K'_h[t]>) . V'_h over t < seq_len[b].

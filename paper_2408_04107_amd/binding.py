@@ -89,17 +89,17 @@ def lib() -> C.CDLL:
         l.fdc_plan_upload.argtypes = [vp, vp, C.c_size_t, vp]
         l.fdc_plan_destroy.argtypes = [vp]
         l.fdc_plan_destroy.restype = None
-        l.fdc_project_latent_kv.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp]
+        l.fdc_project_latent_kv.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
         l.fdc_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, C.c_int, vp]
-        l.fdc_project_and_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp]
+        l.fdc_project_and_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp, vp, C.c_int, vp, vp]
         l.fdc_latent_attn_decode.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         l.fdc_latent_attn_decode_static.argtypes = [vp, vp, vp, vp, vp, C.c_float, vp, vp]
         l.fdc_latent_attn_decode_at.argtypes = [vp, vp, vp, vp, vp, vp, C.c_float, vp, vp, C.c_size_t, vp]
         l.fdc_latent_attn_prefill.argtypes = [vp, vp, vp, vp, vp, C.c_float, C.c_int, vp, vp, C.c_size_t, vp]
         l.fdc_absorb_output.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp, C.c_int, C.c_int, vp, C.c_int, vp]
         l.fdc_profile_decode_events.argtypes = [vp, vp]
-        l.fdc_rope_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, C.c_int, vp]
-        l.fdc_rope_compress_keys.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp]
+        l.fdc_rope_absorb_query.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, C.c_int, vp, vp]
+        l.fdc_rope_compress_keys.argtypes = [vp, C.c_int, vp, C.c_int, vp, vp, vp, vp, C.c_int, vp, vp, vp, vp]
         l.fdc_select_ranks.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_double), C.c_double, C.c_int, i32p]
         _lib = l
     return _lib
@@ -297,10 +297,11 @@ def fdc_plan_upload(plan: Plan, workspace, stream=None) -> None:
 
 
 def fdc_project_latent_kv(layout: Layout, layer: int, x, tok_batch, tok_pos, A_cat, k_cache, v_cache,
-                          stream=None) -> None:
+                          stream=None, status=None) -> None:
+    """status: device int32 tensor (one element) that collects the fault bits of skipped rows, or None."""
     T = int(x.shape[0])
     _check(lib().fdc_project_latent_kv(layout.handle, layer, _dev(x), T, _dev(tok_batch), _dev(tok_pos),
-                                       _dev(A_cat), _dev(k_cache), _dev(v_cache), _stream(stream)))
+                                       _dev(A_cat), _dev(k_cache), _dev(v_cache), _dev(status), _stream(stream)))
 
 
 def fdc_absorb_query(layout: Layout, layer: int, q, Bk, q_lat, q_lat_dtype: int, stream=None) -> None:
@@ -310,11 +311,11 @@ def fdc_absorb_query(layout: Layout, layer: int, q, Bk, q_lat, q_lat_dtype: int,
 
 
 def fdc_project_and_absorb_query(layout: Layout, layer: int, x, tok_batch, tok_pos, A_cat, k_cache, v_cache,
-                                 q, Bk, q_lat, q_lat_dtype: int, stream=None) -> None:
+                                 q, Bk, q_lat, q_lat_dtype: int, stream=None, status=None) -> None:
     T = int(x.shape[0])
     _check(lib().fdc_project_and_absorb_query(layout.handle, layer, _dev(x), T, _dev(tok_batch), _dev(tok_pos),
                                               _dev(A_cat), _dev(k_cache), _dev(v_cache), _dev(q), _dev(Bk),
-                                              _dev(q_lat), q_lat_dtype, _stream(stream)))
+                                              _dev(q_lat), q_lat_dtype, _dev(status), _stream(stream)))
 
 
 def fdc_latent_attn_decode(layout: Layout, plan: Plan, q_lat, k_cache, v_cache, scale: float, o_lat,
@@ -369,14 +370,14 @@ def fdc_select_ranks(theta, r: float, multiple: int = 16) -> np.ndarray:
 
 
 def fdc_rope_absorb_query(layout: Layout, layer: int, q, tok_pos, cos_t, sin_t, R_t, q_lat, q_lat_dtype: int,
-                          stream=None) -> None:
+                          stream=None, status=None) -> None:
     _check(lib().fdc_rope_absorb_query(layout.handle, layer, _dev(q), int(q.shape[0]), _dev(tok_pos), _dev(cos_t),
                                        _dev(sin_t), int(cos_t.shape[0]), _dev(R_t), _dev(q_lat), q_lat_dtype,
-                                       _stream(stream)))
+                                       _dev(status), _stream(stream)))
 
 
 def fdc_rope_compress_keys(layout: Layout, layer: int, k, tok_batch, tok_pos, cos_t, sin_t, R_t, k_cache,
-                           stream=None) -> None:
+                           stream=None, status=None) -> None:
     _check(lib().fdc_rope_compress_keys(layout.handle, layer, _dev(k), int(k.shape[0]), _dev(tok_batch),
                                         _dev(tok_pos), _dev(cos_t), _dev(sin_t), int(cos_t.shape[0]), _dev(R_t),
-                                        _dev(k_cache), _stream(stream)))
+                                        _dev(k_cache), _dev(status), _stream(stream)))

@@ -488,6 +488,9 @@ fdc_status fdc_plan_upload(const fdc_plan* plan, void* workspace, size_t workspa
 static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const int32_t* lens, const void* q_lat,
                               const void* k_cache, const void* v_cache, float scale, void* o_lat, void* workspace,
                               size_t workspace_bytes, void* stream) {
+  // a pending profiling request belongs to THIS call, whether it succeeds or not
+  hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
   if (!lay || !plan || !q_lat || !k_cache || !v_cache || !o_lat || !workspace)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: NULL argument");
   if (plan->kind != 0 || plan->lay != lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode: not a decode plan of this layout");
@@ -509,8 +512,6 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
   const float scale_log2 = scale * kLog2e;
-  hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
-  g_prof_start = g_prof_stop = nullptr;
   if (plan->G > 1 && lay->dtype == FDC_F32)
     FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
   if (plan->on_device || !plan->item_b.empty()) {   // a device plan's tile count is not known here: empty workers return at once
@@ -556,6 +557,12 @@ fdc_status fdc_latent_attn_decode(const fdc_layout* lay, const fdc_plan* plan, c
 fdc_status fdc_latent_attn_decode_static(const fdc_layout* lay, const fdc_plan* plan, const void* q_lat,
                                          const void* k_cache, const void* v_cache, float scale, void* o_lat,
                                          void* stream) {
+  struct DropProfileRequest {   // a pending profiling request belongs to this call even if it fails before the launch
+    bool armed = true;
+    ~DropProfileRequest() {
+      if (armed) g_prof_start = g_prof_stop = nullptr;
+    }
+  } drop;
   if (!lay || !plan) FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: NULL argument");
   if (plan->kind != 0 || plan->lay != lay)
     FDC_FAIL(FDC_INVALID_ARG, "fdc_latent_attn_decode_static: not a decode plan of this layout");
@@ -588,6 +595,7 @@ fdc_status fdc_latent_attn_decode_static(const fdc_layout* lay, const fdc_plan* 
     }
   }
   // The partial states need no clearing: the tile kernel writes every slot the merge reads.
+  drop.armed = false;
   return decode_impl(lay, plan, nullptr, q_lat, k_cache, v_cache, scale, o_lat, ws, kStaticScratchBytes, stream);
 }
 

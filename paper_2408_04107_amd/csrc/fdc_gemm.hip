@@ -67,7 +67,8 @@ struct GemmArgs {
   int nt;    // column tiles of the large kernel (of the widest group)
   int split_from;  // large kernel: blocks from this one on each take half (128 rows) of a tile
   int mode;
-  int H, d_head, max_seq;
+  int H, d_head, max_seq, max_batch;
+  int32_t* fault;  // cache writers: device word that collects kFaultBatch / kFaultPos (may be NULL)
   int G;     // query heads per key/value head: grouped products run over the H * G query heads
   int RK, RV;
   const int32_t* tok_batch;
@@ -130,6 +131,18 @@ __device__ __forceinline__ void store_cache(const GemmArgs& g, void* cache, int6
   }
 }
 
+// Destination token of input row m of a cache writer. Rows whose tok_batch / tok_pos lie outside
+// the cache are skipped by every writer (nothing is stored for them) and noted in the caller's
+// status word; the indices are device data, so no host check can catch them.
+constexpr int kFaultBatch = 1, kFaultPos = 2;
+__device__ __forceinline__ bool token_dst(const GemmArgs& g, int m, int* b, int* pos) {
+  *b = g.tok_batch[m], *pos = g.tok_pos[m];
+  const bool b_ok = (unsigned)*b < (unsigned)g.max_batch, p_ok = (unsigned)*pos < (unsigned)g.max_seq;
+  if (b_ok && p_ok) return true;
+  if (g.fault) atomicOr(g.fault, (b_ok ? 0 : kFaultBatch) | (p_ok ? 0 : kFaultPos));
+  return false;
+}
+
 // Cache element for output column n of the concatenated [K heads | V heads] projection.
 // Returns the buffer (0 = K', 1 = V') and the element offset for token (b, pos).
 __device__ __forceinline__ int64_t project_dst(const GemmArgs& g, int n, int b, int pos, int* side) {
@@ -159,8 +172,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
   float acc = 0.f;
   for (int k = 0; k < g.K; ++k) acc = fmaf(a[k], b[k], acc);
   if (g.mode == kProject) {
-    int side;
-    const int64_t e = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+    int side, b, pos;
+    if (!token_dst(g, m, &b, &pos)) return;
+    const int64_t e = project_dst(g, n, b, pos, &side);
     static_cast<float*>(side ? g.C2 : g.C)[e] = acc;
   } else {
     store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc);
@@ -340,7 +354,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         const int m = m0 + wm + i * 32 + (e / 4) * 8 + (lane / 32) * 4 + e % 4;
         if (m >= g.M) continue;
         if (g.mode == kProject) {
-          store_cache(g, cache, (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank, acc[i][j][e]);
+          int b, pos;
+          if (token_dst(g, m, &b, &pos))
+            store_cache(g, cache, (int64_t)b * seq_stride + col_off + (int64_t)pos * rank, acc[i][j][e]);
         } else {
           store_out(static_cast<TC*>(g.C) + gr.c_off + (int64_t)m * g.ldc + n, acc[i][j][e]);
         }
@@ -714,7 +730,9 @@ __device__ __forceinline__ void dma_tile(const GemmArgs& g, const int m0, const 
           const int m = m0 + wm + h * 32 * GB + row;
           const uint2 v = *reinterpret_cast<const uint2*>(&ep8[row * EROW + c * 8]);
           if (m >= M || n >= N) continue;
-          *reinterpret_cast<uint2*>(cb8 + (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank) = v;
+          int b, pos;
+          if (!token_dst(g, m, &b, &pos)) continue;
+          *reinterpret_cast<uint2*>(cb8 + (int64_t)b * seq_stride + col_off + (int64_t)pos * rank) = v;
         }
       }
       return;
@@ -739,9 +757,10 @@ __device__ __forceinline__ void dma_tile(const GemmArgs& g, const int m0, const 
         const int m = m0 + wm + h * 32 * GB + row;
         const u32x4 v = *reinterpret_cast<const u32x4*>(&ep[row * EROW + c * 8]);
         if (m >= M || n >= N) continue;
-        uint16_t* dst = g.mode == kProject
-                            ? cbase + (int64_t)g.tok_batch[m] * seq_stride + col_off + (int64_t)g.tok_pos[m] * rank
-                            : cbase + (int64_t)m * g.ldc + n;
+        int b = 0, pos = 0;
+        if (g.mode == kProject && !token_dst(g, m, &b, &pos)) continue;
+        uint16_t* dst = g.mode == kProject ? cbase + (int64_t)b * seq_stride + col_off + (int64_t)pos * rank
+                                           : cbase + (int64_t)m * g.ldc + n;
         if (n + 7 < N && wide) {
           *reinterpret_cast<u32x4*>(dst) = v;
         } else {
@@ -908,8 +927,9 @@ __global__ __launch_bounds__(kSkinnyWaves * 64) void gemm_skinny_kernel(const Ge
         const int m = 16 * wave + 4 * lg + e;
         if (m >= g.M) continue;
         if (g.mode == kProject) {
-          int side;
-          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+          int side, b, pos;
+          if (!token_dst(g, m, &b, &pos)) continue;
+          const int64_t dst = project_dst(g, n, b, pos, &side);
           store_cache(g, side ? g.C2 : g.C, dst, sum[e]);
         } else {
           store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
@@ -1035,8 +1055,9 @@ __device__ __forceinline__ void skinny16_body(const GemmArgs& g, const int col_t
         const int m = 4 * lg + e;
         if (m >= g.M) continue;
         if (g.mode == kProject) {
-          int side;
-          const int64_t dst = project_dst(g, n, g.tok_batch[m], g.tok_pos[m], &side);
+          int side, b, pos;
+          if (!token_dst(g, m, &b, &pos)) continue;
+          const int64_t dst = project_dst(g, n, b, pos, &side);
           store_cache(g, side ? g.C2 : g.C, dst, sum[e]);
         } else {
           store_out(static_cast<TC*>(g.C) + (int64_t)m * g.ldc + n, sum[e]);
@@ -1118,7 +1139,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     tok[t] = row_on ? row : -1;
     const int pos_raw = row_on ? g.tok_pos[row] : 0;
     const int pos = min(max(pos_raw, 0), g.n_pos - 1);
-    tok_dst[t] = (KEYS && row_on) ? (int64_t)g.tok_batch[row] * g.max_seq * g.RK : 0;
+    tok_dst[t] = 0;
+    if (row_on && (unsigned)pos_raw >= (unsigned)g.n_pos) {   // no angle for this position: the row is dropped
+      if (g.fault) atomicOr(g.fault, kFaultPos);
+      tok[t] = -1;
+    } else if (KEYS && row_on) {   // keys go into the cache: a row with a bad sequence or position is dropped
+      int b, pc;
+      if (token_dst(g, row, &b, &pc)) tok_dst[t] = (int64_t)b * g.max_seq * g.RK;
+      else tok[t] = -1;
+    }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int col = 32 * ks + 8 * lg;
@@ -1216,7 +1245,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 
 static void fill_tables(GemmArgs& a, const fdc_layout* lay, int layer) {
   const int H = lay->H;
-  a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq;
+  a.H = H, a.d_head = lay->d_head, a.max_seq = lay->max_seq, a.max_batch = lay->max_batch;
   a.G = lay->G;
   a.RK = lay->RK(layer), a.RV = lay->RV(layer);
   std::copy_n(&lay->koff_r[(size_t)layer * (H + 1)], H + 1, a.koff_r);
@@ -1296,7 +1325,7 @@ extern "C" {
 
 fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x, int T, const int32_t* tok_batch,
                                  const int32_t* tok_pos, const void* A_cat_t, void* k_cache, void* v_cache,
-                                 void* stream) {
+                                 int32_t* status, void* stream) {
   fdc_status s = check_common("fdc_project_latent_kv", lay, layer, T);
   if (s != FDC_OK) return s;
   if (T == 0) return FDC_OK;
@@ -1312,7 +1341,7 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
   a.cache_fp8 = lay->dtype == FDC_FP8;
   a.M = T, a.N = a.v_only ? a.RV : a.RK + a.RV, a.K = lay->d_model;
   a.mode = kProject;
-  a.tok_batch = tok_batch, a.tok_pos = tok_pos;
+  a.tok_batch = tok_batch, a.tok_pos = tok_pos, a.fault = status;
   return launch(lay, a, 1, a.N, false, false, static_cast<hipStream_t>(stream));
 }
 
@@ -1341,13 +1370,13 @@ fdc_status fdc_absorb_query(const fdc_layout* lay, int layer, const void* q, int
 fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const void* x, int T,
                                         const int32_t* tok_batch, const int32_t* tok_pos, const void* A_cat_t,
                                         void* k_cache, void* v_cache, const void* q, const void* Bk, void* q_lat,
-                                        fdc_dtype q_lat_dtype, void* stream) {
+                                        fdc_dtype q_lat_dtype, int32_t* status, void* stream) {
   // one launch only where both halves take their few-row kernels; otherwise the two calls in turn
   if (!lay || lay->dtype == FDC_F32 || T < 1 || T > 16 || layer < 0 || layer >= lay->L || !x || !tok_batch ||
       !tok_pos || !A_cat_t || !v_cache || !q || !Bk || !q_lat || !aligned16(x) || !aligned16(A_cat_t) ||
       (k_cache && !aligned16(k_cache)) || !aligned16(v_cache) || !aligned16(q) || !aligned16(Bk) ||
       !aligned16(q_lat) || (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) || lay->H > kMaxHeads) {
-    fdc_status s = fdc_project_latent_kv(lay, layer, x, T, tok_batch, tok_pos, A_cat_t, k_cache, v_cache, stream);
+    fdc_status s = fdc_project_latent_kv(lay, layer, x, T, tok_batch, tok_pos, A_cat_t, k_cache, v_cache, status, stream);
     if (s != FDC_OK) return s;
     return fdc_absorb_query(lay, layer, q, T, Bk, q_lat, q_lat_dtype, stream);
   }
@@ -1359,7 +1388,7 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
   p.cache_fp8 = lay->dtype == FDC_FP8;
   p.M = T, p.N = p.v_only ? p.RV : p.RK + p.RV, p.K = lay->d_model;
   p.mode = kProject;
-  p.tok_batch = tok_batch, p.tok_pos = tok_pos;
+  p.tok_batch = tok_batch, p.tok_pos = tok_pos, p.fault = status;
   GemmArgs a{};
   fill_tables(a, lay, layer);
   a.A = q, a.B = Bk, a.C = q_lat;
@@ -1445,9 +1474,10 @@ static fdc_status rope_common(const char* fn, const fdc_layout* lay, int layer, 
 
 fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q, int T, const int32_t* tok_pos,
                                  const float* cos_t, const float* sin_t, int n_pos, const void* R_t, void* q_lat,
-                                 fdc_dtype q_lat_dtype, void* stream) {
+                                 fdc_dtype q_lat_dtype, int32_t* status, void* stream) {
   if (T == 0 && lay) return FDC_OK;
   GemmArgs a{};
+  a.fault = status;
   fdc_status s = rope_common("fdc_rope_absorb_query", lay, layer, q, T, tok_pos, cos_t, sin_t, n_pos, R_t, q_lat, &a);
   if (s != FDC_OK) return s;
   if (q_lat_dtype != FDC_BF16 && q_lat_dtype != FDC_F32) FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_rope_absorb_query: q_lat_dtype");
@@ -1463,9 +1493,10 @@ fdc_status fdc_rope_absorb_query(const fdc_layout* lay, int layer, const void* q
 
 fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* k, int T, const int32_t* tok_batch,
                                   const int32_t* tok_pos, const float* cos_t, const float* sin_t, int n_pos,
-                                  const void* R_t, void* k_cache, void* stream) {
+                                  const void* R_t, void* k_cache, int32_t* status, void* stream) {
   if (T == 0 && lay) return FDC_OK;
   GemmArgs a{};
+  a.fault = status;
   fdc_status s = rope_common("fdc_rope_compress_keys", lay, layer, k, T, tok_pos, cos_t, sin_t, n_pos, R_t, k_cache, &a);
   if (s != FDC_OK) return s;
   if (!tok_batch) FDC_FAIL(FDC_INVALID_ARG, "fdc_rope_compress_keys: tok_batch is NULL");

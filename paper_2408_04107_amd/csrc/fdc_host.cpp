@@ -20,7 +20,10 @@ void set_error(const char* fmt, ...) {
   va_start(ap, fmt);
   vsnprintf(buf, sizeof(buf), fmt, ap);
   va_end(ap);
-  g_error = buf;
+  try {
+    g_error = buf;
+  } catch (...) {   // no memory even for the text: keep whatever was there
+  }
 }
 
 // Min-heap of (load, worker id): the top is the least-loaded worker, ties to the lowest id.
@@ -83,8 +86,9 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
         FDC_FAIL(FDC_UNSUPPORTED_RANK, "fdc_layout_create: rank %d at index %zu is not a multiple of 16 in [16, %d]",
                  r, i, d_head);
   }
-  fdc_layout* lay = new (std::nothrow) fdc_layout();
-  if (!lay) FDC_FAIL(FDC_INVALID_ARG, "fdc_layout_create: out of host memory");
+  return guarded("fdc_layout_create", [&]() -> fdc_status {
+  std::unique_ptr<fdc_layout> holder(new fdc_layout());
+  fdc_layout* lay = holder.get();
   lay->L = n_layers, lay->H = n_heads, lay->d_model = d_model, lay->d_head = d_head;
   lay->max_batch = max_batch, lay->max_seq = max_seq, lay->dtype = dtype;
   lay->elem_size = dtype == FDC_BF16 ? 2 : (dtype == FDC_FP8 ? 1 : 4);
@@ -107,8 +111,9 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
     lay->k_elems[l] = (int64_t)max_batch * max_seq * runk;
     lay->v_elems[l] = (int64_t)max_batch * max_seq * runv;
   }
-  *out = lay;
+  *out = holder.release();
   return FDC_OK;
+  });
 }
 
 fdc_status fdc_layout_create_gqa(int n_layers, int n_kv_heads, int q_per_kv, int d_model, int d_head, const int32_t* rk,
@@ -144,6 +149,7 @@ void fdc_layout_destroy(fdc_layout* lay) { delete lay; }
 fdc_status fdc_select_ranks(int n, int d_head, const double* theta, double r, int multiple, int32_t* ranks) {
   if (!theta || !ranks) FDC_FAIL(FDC_INVALID_ARG, "fdc_select_ranks: NULL argument");
   if (n < 0 || d_head <= 0 || multiple <= 0) FDC_FAIL(FDC_BAD_SHAPE, "fdc_select_ranks: bad sizes");
+  return guarded("fdc_select_ranks", [&]() -> fdc_status {
   std::vector<double> tails((size_t)d_head + 1);
   for (int h = 0; h < n; ++h) {
     const double* th = theta + (size_t)h * d_head;
@@ -156,6 +162,7 @@ fdc_status fdc_select_ranks(int n, int d_head, const double* theta, double r, in
     ranks[h] = (int32_t)((j_found + 1 + multiple - 1) / multiple * multiple);
   }
   return FDC_OK;
+  });
 }
 
 // ------------------------------------------------------------------------------------ planner
@@ -304,8 +311,8 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
     tile_of_piece[keyed[tid].second] = (int32_t)tid;
   }
 
-  fdc_plan* p = new (std::nothrow) fdc_plan();
-  if (!p) FDC_FAIL(FDC_INVALID_ARG, "%s: out of host memory", fn);
+  std::unique_ptr<fdc_plan> holder(new fdc_plan());
+  fdc_plan* p = holder.get();
   p->kind = 0, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
   p->G = lay->G;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer), p->total_q_rows = batch;
@@ -400,7 +407,7 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = std::max<size_t>(n * p->G, 1) * kPartialStride * sizeof(float);
   p->workspace_bytes = p->off_partials + p->partial_bytes;
-  *out = p;
+  *out = holder.release();
   return FDC_OK;
 }
 
@@ -408,7 +415,7 @@ extern "C" {
 
 fdc_status fdc_plan_decode(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
                            const fdc_plan_params* pr, fdc_plan** out) {
-  return plan_decode_impl("fdc_plan_decode", lay, layer, batch, seq_len, nullptr, 0, pr, out);
+  return guarded("fdc_plan_decode", [&] { return plan_decode_impl("fdc_plan_decode", lay, layer, batch, seq_len, nullptr, 0, pr, out); });
 }
 
 fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, const int32_t* seq_len,
@@ -418,7 +425,9 @@ fdc_status fdc_plan_decode_paged(const fdc_layout* lay, int layer, int batch, co
     if (out) *out = nullptr;
     FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_decode_paged: block_table is NULL");
   }
-  return plan_decode_impl("fdc_plan_decode_paged", lay, layer, batch, seq_len, block_table, max_pages, pr, out);
+  return guarded("fdc_plan_decode_paged", [&] {
+    return plan_decode_impl("fdc_plan_decode_paged", lay, layer, batch, seq_len, block_table, max_pages, pr, out);
+  });
 }
 
 }  // extern "C"
@@ -470,8 +479,8 @@ static fdc_status plan_prefill_impl(const char* fn, const fdc_layout* lay, int l
   int64_t d_max = 0;
   for (int h = 0; h < H; ++h) d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost, d_max = std::max(d_max, d_sum[h]);
 
-  fdc_plan* p = new (std::nothrow) fdc_plan();
-  if (!p) FDC_FAIL(FDC_INVALID_ARG, "%s: out of host memory", fn);
+  std::unique_ptr<fdc_plan> holder(new fdc_plan());
+  fdc_plan* p = holder.get();
   p->kind = 1, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W, p->n_units = batch * H;
   p->G = g;
   p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
@@ -582,7 +591,7 @@ static fdc_status plan_prefill_impl(const char* fn, const fdc_layout* lay, int l
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = 0;
   p->workspace_bytes = p->off_partials + 256;
-  *out = p;
+  *out = holder.release();
   return FDC_OK;
 }
 
@@ -590,7 +599,7 @@ extern "C" {
 
 fdc_status fdc_plan_prefill(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
                             const int32_t* kv_len, const fdc_plan_params* pr, fdc_plan** out) {
-  return plan_prefill_impl("fdc_plan_prefill", lay, layer, batch, q_len, kv_len, nullptr, 0, pr, out);
+  return guarded("fdc_plan_prefill", [&] { return plan_prefill_impl("fdc_plan_prefill", lay, layer, batch, q_len, kv_len, nullptr, 0, pr, out); });
 }
 
 fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, const int32_t* q_len,
@@ -600,7 +609,9 @@ fdc_status fdc_plan_prefill_paged(const fdc_layout* lay, int layer, int batch, c
     if (out) *out = nullptr;
     FDC_FAIL(FDC_INVALID_ARG, "fdc_plan_prefill_paged: block_table is NULL");
   }
-  return plan_prefill_impl("fdc_plan_prefill_paged", lay, layer, batch, q_len, kv_len, block_table, max_pages, pr, out);
+  return guarded("fdc_plan_prefill_paged", [&] {
+    return plan_prefill_impl("fdc_plan_prefill_paged", lay, layer, batch, q_len, kv_len, block_table, max_pages, pr, out);
+  });
 }
 
 fdc_status fdc_plan_export(const fdc_plan* p, fdc_plan_tables* o) {

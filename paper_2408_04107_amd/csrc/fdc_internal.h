@@ -5,6 +5,9 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <exception>
+#include <memory>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -25,6 +28,22 @@ void set_error(const char* fmt, ...);
     hipError_t e_ = (expr);                                                        \
     if (e_ != hipSuccess) FDC_FAIL(FDC_HIP_ERROR, "%s: %s", #expr, hipGetErrorString(e_)); \
   } while (0)
+
+// Runs the body of an entry point that allocates host memory (std::vector, std::string): no C++
+// exception may cross the C boundary, so a failed allocation becomes an error status with text.
+template <typename F>
+inline fdc_status guarded(const char* fn, F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    set_error("%s: out of host memory", fn);
+  } catch (const std::exception& e) {
+    set_error("%s: %s", fn, e.what());
+  } catch (...) {
+    set_error("%s: unknown failure", fn);
+  }
+  return FDC_INVALID_ARG;
+}
 
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t round_up(int64_t a, int64_t m) { return ceil_div(a, m) * m; }

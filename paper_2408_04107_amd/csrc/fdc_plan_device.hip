@@ -469,8 +469,8 @@ using namespace fdc;
 
 extern "C" {
 
-fdc_status fdc_plan_decode_device(const fdc_layout* lay, int layer, int batch, int max_pages,
-                                  const fdc_plan_params* pr, fdc_plan** out) {
+static fdc_status plan_decode_device_body(const fdc_layout* lay, int layer, int batch, int max_pages,
+                                          const fdc_plan_params* pr, fdc_plan** out) {
   const char* fn = "fdc_plan_decode_device";
   if (!out) FDC_FAIL(FDC_INVALID_ARG, "%s: out is NULL", fn);
   *out = nullptr;
@@ -518,8 +518,8 @@ fdc_status fdc_plan_decode_device(const fdc_layout* lay, int layer, int batch, i
                           (paged ? (int64_t)batch * H * (max_pages - 1) : 0);
   const int64_t n_max = std::max<int64_t>(1, std::min(by_granule, by_fill));
 
-  fdc_plan* p = new (std::nothrow) fdc_plan();
-  if (!p) FDC_FAIL(FDC_INVALID_ARG, "%s: out of host memory", fn);
+  std::unique_ptr<fdc_plan> holder(new fdc_plan());
+  fdc_plan* p = holder.get();
   p->kind = 0, p->on_device = true, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W;
   p->n_units = batch * H, p->G = lay->G, p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
   p->total_q_rows = batch, p->n_merge_units = p->n_units * p->G, p->n_max = n_max;
@@ -579,8 +579,13 @@ fdc_status fdc_plan_decode_device(const fdc_layout* lay, int layer, int batch, i
   const int32_t* koff_r = &lay->koff_r[(size_t)layer * (H + 1)];
   const int32_t* voff_r = &lay->voff_r[(size_t)layer * (H + 1)];
   for (int h = 0; h < H; ++h) tab[h] = rk[h], tab[H + h] = rv[h], tab[2 * H + h] = koff_r[h], tab[3 * H + h] = voff_r[h];
-  *out = p;
+  *out = holder.release();
   return FDC_OK;
+}
+
+fdc_status fdc_plan_decode_device(const fdc_layout* lay, int layer, int batch, int max_pages,
+                                  const fdc_plan_params* pr, fdc_plan** out) {
+  return guarded("fdc_plan_decode_device", [&] { return plan_decode_device_body(lay, layer, batch, max_pages, pr, out); });
 }
 
 fdc_status fdc_plan_decode_run(fdc_plan* const* plans, void* const* workspaces, int n_plans, const int32_t* seq_len,
@@ -618,7 +623,10 @@ fdc_status fdc_plan_decode_run(fdc_plan* const* plans, void* const* workspaces, 
     if (std::find(done.begin(), done.end(), dev) == done.end()) {
       FDC_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(plan_decode_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPlanMaxLds - 64));
-      done.push_back(dev);
+      try {
+        done.push_back(dev);
+      } catch (...) {   // not remembered: the attribute is simply set again next time
+      }
     }
   }
   hipLaunchKernelGGL(plan_decode_kernel, dim3(n_plans), dim3(kPlanThreads), lds_bytes, static_cast<hipStream_t>(stream),
@@ -628,7 +636,7 @@ fdc_status fdc_plan_decode_run(fdc_plan* const* plans, void* const* workspaces, 
   return FDC_OK;
 }
 
-fdc_status fdc_plan_download(fdc_plan* p, const void* workspace, void* stream) {
+static fdc_status plan_download_body(fdc_plan* p, const void* workspace, void* stream) {
   const char* fn = "fdc_plan_download";
   if (!p || !workspace) FDC_FAIL(FDC_INVALID_ARG, "%s: NULL argument", fn);
   if (p->kind != 0 || !p->on_device) FDC_FAIL(FDC_INVALID_ARG, "%s: not a plan made by fdc_plan_decode_device", fn);
@@ -667,6 +675,10 @@ fdc_status fdc_plan_download(fdc_plan* p, const void* workspace, void* stream) {
   if (hd.status & kPlanBadPage)
     FDC_FAIL(FDC_BAD_SHAPE, "%s: a block-table entry on the device was outside the layout's pages; page 0 was used", fn);
   return FDC_OK;
+}
+
+fdc_status fdc_plan_download(fdc_plan* p, const void* workspace, void* stream) {
+  return guarded("fdc_plan_download", [&] { return plan_download_body(p, workspace, stream); });
 }
 
 }  // extern "C"

@@ -276,3 +276,27 @@ def test_decode_at_actual_lengths_on_a_plan_for_rounded_up_lengths(W, granule, m
                                   cache.v, scale, o2, ws)
     torch.cuda.synchronize()
     assert torch.equal(o1, o2)
+
+
+def test_profiling_request_is_consumed_by_a_failing_call():
+    """A request made with fdc_profile_decode_events belongs to the next decode call of the thread even when
+    that call fails validation; it must not fire on a later call."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    ev = [ctypes.c_void_p(), ctypes.c_void_p()]
+    for e in ev:
+        assert hip.hipEventCreate(ctypes.byref(e)) == 0
+    _, _, _, (lay, plan, cache, q_lat, o_lat, ws, scale) = run_decode([16, 64], [32, 16], [300, 100], 8, seed=2)
+    fdc.fdc_profile_decode_events(ev[0].value, ev[1].value)
+    with pytest.raises(fdc.FdcError):
+        fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, -1.0, o_lat, ws)      # bad scale
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)         # must not record
+    torch.cuda.synchronize()
+    ms = ctypes.c_float(-1.0)
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), ev[0], ev[1]) != 0      # never recorded
+    fdc.fdc_profile_decode_events(ev[0].value, ev[1].value)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    assert hip.hipEventElapsedTime(ctypes.byref(ms), ev[0], ev[1]) == 0 and ms.value > 0
+    for e in ev:
+        hip.hipEventDestroy(e)

@@ -349,3 +349,41 @@ def test_planners_are_thread_safe():
     with ThreadPoolExecutor(4) as ex:
         msgs = list(ex.map(bad, range(8)))
     assert all(m and "layer 99" in m for m in msgs)
+
+
+def test_out_of_host_memory_is_a_status_not_an_exception():
+    """No C++ exception may cross the C boundary: with the address space capped, a planner call that
+    needs gigabytes of host tables returns an error status with text and the process lives on.
+    Runs in a child process (the cap cannot be lifted again)."""
+    import subprocess
+    import sys
+    code = r"""
+import resource, sys
+sys.path.insert(0, %r)
+import numpy as np
+import paper_2408_04107_amd as fdc
+lay = fdc.Layout(1, 2, 256, 128, np.array([[16, 64]], dtype=np.int32), np.array([[32, 16]], dtype=np.int32), 4, 4096, fdc.FDC_BF16)
+pp = fdc.fdc_plan_params_default()
+pp.n_workers = 64
+fdc.fdc_plan_decode(lay, 0, [4096] * 4, pp)            # the library is loaded and works
+soft, hard = resource.getrlimit(resource.RLIMIT_AS)
+used = int(open('/proc/self/statm').read().split()[0]) * resource.getpagesize()
+resource.setrlimit(resource.RLIMIT_AS, (used + (256 << 20), hard))
+pp.n_workers = 200_000_000                              # per-worker tables alone are several GB
+for call in (lambda: fdc.fdc_plan_decode(lay, 0, [4096] * 4, pp),
+             lambda: fdc.fdc_plan_prefill(lay, 0, [4096] * 4, [4096] * 4, pp)):
+    try:
+        call()
+        print('NO ERROR')
+    except fdc.FdcError as e:
+        print('STATUS', e.status, str(e))
+pp.n_workers = 64
+p = fdc.fdc_plan_decode(lay, 0, [4096] * 4, pp)       # and the library still works afterwards
+print('ALIVE', p.export()['n_items'])
+""" % ROOT
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    out = r.stdout
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in out.splitlines() if l.startswith("STATUS")]
+    assert len(lines) == 2 and all("out of host memory" in l and "STATUS -1" in l for l in lines), out
+    assert "ALIVE" in out
