@@ -303,51 +303,65 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
 }
 
 // ---- split-K merge --------------------------------------------------------------------------
-// One workgroup per unit: o' = sum_j acc_j 2^(m_j - M) / sum_j l_j 2^(m_j - M), M = max_j m_j.
-// Thread (q, g) owns column quad q (4 floats of acc) and the tiles j = g, g + G, ...; a group first
-// combines its own tiles against the group's maximum, then the G group states are combined
-// through LDS in a fixed order. One pass over the partial states, one barrier.
-template <int G>
-__global__ __launch_bounds__(32 * G) void decode_merge_kernel(const DecUnit* __restrict__ units,
-                                                              const float* __restrict__ partials,
-                                                              float* __restrict__ o_lat) {
+// o' = sum_j acc_j 2^(m_j - M) / sum_j l_j 2^(m_j - M), M = max_j m_j, over the tiles j of a unit.
+//
+// Units cut into many tiles (long contexts): one workgroup of sixteen wavefronts per unit. Wave w
+// takes the tiles w, w + 16, w + 32, ... eight at a time (every load of a batch in flight together;
+// a lane owns two output columns) and keeps a running (M, L, acc) in registers; the sixteen wave
+// states are then combined through LDS in wave order. A unit of 270 tiles costs three dependent
+// rounds of loads per wave, where one thread per (column quad, tile group) walking its tiles one
+// after the other took nine.
+constexpr int kWideWaves = 16;
+constexpr int kWideBatch = 8;
+constexpr int kMergeWaveMax = 64;   // units of up to this many tiles belong to the one-wavefront kernel below
+
+__global__ __launch_bounds__(kWideWaves * 64) void decode_merge_wide_kernel(const DecUnit* __restrict__ units,
+                                                                            const float* __restrict__ partials,
+                                                                            float* __restrict__ o_lat) {
   const DecUnit u = units[blockIdx.x];
   const int n = u.tile_end - u.tile_begin;
-  const int tid = threadIdx.x;
-  if (n == 1) return;  // the tile kernel wrote the normalised output itself
-  if (n == 0) {
-    for (int c = tid; c < u.rv; c += 32 * G) o_lat[u.o_elem + c] = 0.f;
-    return;
-  }
-  __shared__ float accs[G][132];  // [g][0..127] acc, [128] l, [129] m
-  const int q = tid % 32, g = tid / 32;
-  const bool col_on = q * 4 < u.rv;
+  const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+  if (n <= kMergeWaveMax) return;  // merged by decode_merge_wave_kernel (or, a single tile, final already)
+  __shared__ float accs[kWideWaves][130];  // [w][0..127] acc, [128] L, [129] M
+  const bool on = 2 * lane < u.rv;
   const float* base = partials + (int64_t)u.tile_begin * kPartialStride;
-  float mg = -INFINITY;
-  for (int j = g; j < n; j += G) mg = fmaxf(mg, base[(int64_t)j * kPartialStride]);
-  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
-  float lsum = 0.f;
-  for (int j = g; j < n; j += G) {
-    const float* pp = base + (int64_t)j * kPartialStride;
-    const float w = __builtin_amdgcn_exp2f(pp[0] - mg);
-    lsum += pp[1] * w;
-    if (col_on) {
-      const float4 v = *reinterpret_cast<const float4*>(pp + 4 + q * 4);
-      a.x += v.x * w, a.y += v.y * w, a.z += v.z * w, a.w += v.w * w;
+  float M = -INFINITY, L = 0.f, ax = 0.f, ay = 0.f;
+  for (int j0 = wave; j0 < n; j0 += kWideWaves * kWideBatch) {
+    float2 ml[kWideBatch], v[kWideBatch];
+#pragma unroll
+    for (int t = 0; t < kWideBatch; ++t) {
+      const float* pp = base + (int64_t)min(j0 + kWideWaves * t, n - 1) * kPartialStride;  // past the end: a valid slot, weight 0
+      ml[t] = *reinterpret_cast<const float2*>(pp);
+      v[t] = *reinterpret_cast<const float2*>(pp + 4 + (on ? 2 * lane : 0));
     }
+    float bm = M;
+#pragma unroll
+    for (int t = 0; t < kWideBatch; ++t) {
+      if (j0 + kWideWaves * t >= n) ml[t].x = -INFINITY;
+      bm = fmaxf(bm, ml[t].x);
+    }
+    const float w0 = __builtin_amdgcn_exp2f(M - bm);  // first batch: 2^(-inf) = 0
+    L *= w0, ax *= w0, ay *= w0;
+#pragma unroll
+    for (int t = 0; t < kWideBatch; ++t) {
+      const float w = __builtin_amdgcn_exp2f(ml[t].x - bm);
+      L = fmaf(ml[t].y, w, L), ax = fmaf(v[t].x, w, ax), ay = fmaf(v[t].y, w, ay);
+    }
+    M = bm;
   }
-  accs[g][q * 4 + 0] = a.x, accs[g][q * 4 + 1] = a.y, accs[g][q * 4 + 2] = a.z, accs[g][q * 4 + 3] = a.w;
-  if (q == 0) accs[g][128] = lsum, accs[g][129] = mg;
+  // a wave without tiles (n < 16) leaves M = -inf, L = 0: weight 0 below
+  accs[wave][2 * lane] = ax, accs[wave][2 * lane + 1] = ay;
+  if (lane == 0) accs[wave][128] = L, accs[wave][129] = M;
   __syncthreads();
   if (tid < u.rv) {
-    float M = -INFINITY;
+    float Mx = -INFINITY;
 #pragma unroll
-    for (int k = 0; k < G; ++k) M = fmaxf(M, accs[k][129]);
+    for (int k = 0; k < kWideWaves; ++k) Mx = fmaxf(Mx, accs[k][129]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int k = 0; k < G; ++k) {
-      const float w = __builtin_amdgcn_exp2f(accs[k][129] - M);  // groups without tiles: m = -inf, w = 0
-      num += accs[k][tid] * w, den += accs[k][128] * w;
+    for (int k = 0; k < kWideWaves; ++k) {
+      const float w = __builtin_amdgcn_exp2f(accs[k][129] - Mx);
+      num = fmaf(accs[k][tid], w, num), den = fmaf(accs[k][128], w, den);
     }
     o_lat[u.o_elem + tid] = num / den;
   }
@@ -368,7 +382,7 @@ __global__ __launch_bounds__(kMergeWaves * 64) void decode_merge_wave_kernel(con
   const int lane = threadIdx.x % 64;
   const DecUnit u = units[unit];
   const int n = u.tile_end - u.tile_begin;
-  if (n == 1) return;  // the tile kernel wrote the normalised output itself
+  if (n == 1 || n > kMergeWaveMax) return;  // one tile: the tile kernel wrote the normalised output itself; many: the wide kernel
   const bool on = 2 * lane < u.rv;
   if (n == 0) {
     if (on) *reinterpret_cast<float2*>(o_lat + u.o_elem + 2 * lane) = make_float2(0.f, 0.f);
@@ -535,13 +549,18 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
     FDC_HIP_CHECK(hipGetLastError());
     if (ev1) FDC_HIP_CHECK(hipEventRecord(ev1, st));
   }
-  // wide workgroups only when some unit has many tiles (long contexts)
-  if (plan->max_items_per_unit > 64)
-    hipLaunchKernelGGL(decode_merge_kernel<32>, dim3(plan->n_merge_units), dim3(1024), 0, st, units, partials,
-                       static_cast<float*>(o_lat));
-  else
+  // One rule for every plan, so that a result does not depend on where the plan was made: a unit of at most
+  // kMergeWaveMax tiles is merged by one wavefront in slot order, a unit of more by sixteen. Each kernel skips
+  // the other's units. A host plan knows which kinds it has; for a device plan the host only knows how many
+  // granules a sequence can hold.
+  const bool any_wide = plan->on_device ? plan->max_unit_granules > kMergeWaveMax : plan->max_items_per_unit > kMergeWaveMax;
+  const bool any_wave = plan->on_device || plan->min_items_per_unit <= kMergeWaveMax;
+  if (any_wave)
     hipLaunchKernelGGL(decode_merge_wave_kernel, dim3((plan->n_merge_units + kMergeWaves - 1) / kMergeWaves),
                        dim3(kMergeWaves * 64), 0, st, units, partials, static_cast<float*>(o_lat), plan->n_merge_units);
+  if (any_wide)
+    hipLaunchKernelGGL(decode_merge_wide_kernel, dim3(plan->n_merge_units), dim3(kWideWaves * 64), 0, st, units, partials,
+                       static_cast<float*>(o_lat));
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

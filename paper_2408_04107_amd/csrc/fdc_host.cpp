@@ -324,8 +324,10 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
     p->item_cost[tid] = (int64_t)(pc.t1 - pc.t0) * d_sum[pc.h];
     p->unit_item_ptr[(size_t)pc.b * H + pc.h + 1] += 1;
   }
+  p->min_items_per_unit = p->n_units > 0 ? p->unit_item_ptr[1] : 0;
   for (int u = 0; u < p->n_units; ++u) {
     p->max_items_per_unit = std::max(p->max_items_per_unit, p->unit_item_ptr[u + 1]);
+    p->min_items_per_unit = std::min(p->min_items_per_unit, p->unit_item_ptr[u + 1]);
     p->unit_item_ptr[u + 1] += p->unit_item_ptr[u];
   }
   // worker lists in hand-out order (pieces are in that order): counting sort into CSR form

@@ -176,6 +176,7 @@ struct fdc_plan {
   int RK, RV;
   int64_t total_q_rows;   // prefill: T
   int max_items_per_unit = 0;  // decode: most tiles any unit was cut into
+  int min_items_per_unit = 0;  // decode: fewest (empty units count as 0)
   // exported tables
   std::vector<int32_t> item_b, item_h, item_lo, item_hi, unit_item_ptr, worker_ptr, worker_items, br;
   std::vector<int64_t> item_cost, worker_load;
@@ -191,6 +192,7 @@ struct fdc_plan {
   // workspace are sized for n_max pieces, an upper bound known without the sequence lengths.
   bool on_device = false, downloaded = false;
   int64_t n_max = 0;
+  int64_t max_unit_granules = 0;   // most pieces one unit can be cut into: ceil(capacity / granule)
   std::vector<int64_t> d_sum;   // per head, for item_cost after a download
   size_t off_header = 0, off_export = 0, lds_bytes = 0;
 };

@@ -523,6 +523,7 @@ static fdc_status plan_decode_device_body(const fdc_layout* lay, int layer, int 
   p->kind = 0, p->on_device = true, p->layer = layer, p->batch = batch, p->H = H, p->n_workers = W;
   p->n_units = batch * H, p->G = lay->G, p->lay = lay, p->RK = lay->RK(layer), p->RV = lay->RV(layer);
   p->total_q_rows = batch, p->n_merge_units = p->n_units * p->G, p->n_max = n_max;
+  p->max_unit_granules = granules;   // cuts fall on granule multiples (pages are multiples of the granule)
   p->d_sum.resize(H);
   for (int h = 0; h < H; ++h) p->d_sum[h] = (int64_t)rk[h] + rv[h] + pr->softmax_cost;
 

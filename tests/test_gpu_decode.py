@@ -294,6 +294,7 @@ def test_profiling_request_is_consumed_by_a_failing_call():
     torch.cuda.synchronize()
     ms = ctypes.c_float(-1.0)
     assert hip.hipEventElapsedTime(ctypes.byref(ms), ev[0], ev[1]) != 0      # never recorded
+    hip.hipGetLastError()                                                     # that failure was the test's own: clear it
     fdc.fdc_profile_decode_events(ev[0].value, ev[1].value)
     fdc.fdc_latent_attn_decode(lay, plan, q_lat, cache.k, cache.v, scale, o_lat, ws)
     torch.cuda.synchronize()
