@@ -11,8 +11,9 @@ Prints ONE JSON line. `value` is the algorithmic HBM bytes of a whole step divid
 time; `roofline` describes the dominant kernel (the decode tile kernel) from HIP events recorded
 around that kernel alone; `cpu_baseline` is the float64 oracle timed on the host on a bounded
 sample; `prefill` reports the MFMA calls of the prefill configuration in TFLOP/s. Further objects of
-the same line are side measurements of the other rows (`gqa_decode`, `fp8_decode`, `device_planner`,
-`serving_loop`); each has a --no-... switch and a failure in one of them is reported in its place.
+the same line are side measurements of the other rows (`c2_uniform_decode`, `c4_long_decode`: one layer over
+rotating cache copies; `gqa_decode`, `fp8_decode`, `device_planner`, `serving_loop`); each has a --no-... switch
+and a failure in one of them is reported in its place.
 """
 from __future__ import annotations
 
@@ -267,41 +268,95 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     return result, state
 
 
-def cpu_baseline(state, budget_s=12.0):
-    """The float64 oracle (as it stands) on the host, over units of layer 0 of the same workload."""
-    import torch
+def cpu_baseline(state, budget_s=8.0):
+    """The float64 oracle (as it stands) on the host cores, over (sequence, head) decode units of layer 0 of the
+    same workload. The legs run in a child process that never touches the GPU (so it may fork workers): one
+    thread; one single-threaded process per core over independent units (`value`); numpy's own threads on
+    one unit at a time."""
+    import subprocess
+    ranks, S = state["ranks"], state["S"]
+    spec = {"ranks": [int(r) for r in ranks[0]], "S": int(S), "scale": float(state["scale"]), "budget": budget_s}
+    r = subprocess.run([sys.executable, os.path.abspath(__file__), "--oracle-legs", json.dumps(spec)],
+                       capture_output=True, text=True, timeout=300)
+    if r.returncode != 0:
+        raise RuntimeError("oracle timing failed: " + r.stderr[-500:])
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
+_LEG_DATA = []   # units of the oracle timing; forked workers inherit it, so only an index travels per unit
+
+
+def _oracle_unit(i):
     from oracle import attention as oa
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    except Exception:
-        cores = 1
-    lay, t, ranks = state["lay"], state["tables"], state["ranks"]
-    B, S, H = state["B"], state["S"], state["H"]
-    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
-    q = state["q_lat"][:B * RK].view(B, RK).to(torch.float64).cpu().numpy()
-    g = np.random.Generator(np.random.PCG64(0))
-    units = [(int(b), int(h)) for b, h in zip(g.integers(0, B, 24), g.integers(0, H, 24))]
-    data = []
-    for b, h in units:
-        r = int(ranks[0][h])
-        ks = b * S * RK + int(t["koff"][0, h])
-        vs = b * S * RV + int(t["voff"][0, h])
-        K = state["kc"][0][ks:ks + S * r].view(S, r).to(torch.float64).cpu().numpy()
-        V = state["vc"][0][vs:vs + S * r].view(S, r).to(torch.float64).cpu().numpy()
-        data.append((q[b, int(t["koff_r"][0, h]):int(t["koff_r"][0, h + 1])], K, V, S * 2 * r * 2))
-    done_bytes, n_units = 0, 0
-    t0 = time.perf_counter()
-    while time.perf_counter() - t0 < budget_s:
-        for qq, K, V, nbytes in data:
-            oa.latent_attn_decode(qq, K, V, state["scale"])
-            done_bytes += nbytes
-            n_units += 1
-    dt = time.perf_counter() - t0
-    return {"value": done_bytes / dt / 1e9, "unit": "GB/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_units} (sequence, head) decode units of layer 0 (24 distinct, context {S}, "
-                      f"bf16 bytes counted as for the GPU), {dt:.1f} s of numpy float64",
-            "us_per_unit": dt * 1e6 / n_units}
+    qq, K, V, scale, nbytes = _LEG_DATA[i]
+    oa.latent_attn_decode(qq, K, V, scale)
+    return nbytes
+
+
+def _one_blas_thread():
+    from threadpoolctl import threadpool_limits
+    threadpool_limits(limits=1)
+
+
+def oracle_legs(spec):
+    """Child-process part of cpu_baseline: no torch, no GPU."""
+    import multiprocessing as mp
+    from threadpoolctl import threadpool_info, threadpool_limits
+    from workloads import generators as gen
+    ranks, S, scale, budget = spec["ranks"], spec["S"], spec["scale"], spec["budget"]
+    blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    nproc = os.cpu_count() or 1
+    cores = max(1, min(nproc, 16))          # the GPU box gives one GPU's job 16 cores, whatever nproc says
+    g = gen.make_rng(0)
+    data = _LEG_DATA
+    for h in g.integers(0, len(ranks), 32):
+        r = ranks[int(h)]
+        K = gen.round_to_bf16(gen.direct_latent(S, r, 32.0, g))
+        V = gen.round_to_bf16(gen.direct_latent(S, r, 32.0, g))
+        data.append((g.standard_normal(r), K, V, scale, S * 2 * r * 2))
+
+    def leg(pool, budget_):
+        done, n_units = 0, 0
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < budget_:
+            idx = range(len(data))
+            done += sum(pool.map(_oracle_unit, idx, chunksize=1)) if pool else sum(_oracle_unit(i) for i in idx)
+            n_units += len(data)
+        dt = time.perf_counter() - t0
+        return {"value": done / dt / 1e9, "unit": "GB/s", "us_per_unit": dt * 1e6 / n_units, "units": n_units, "seconds": dt}
+
+    with threadpool_limits(limits=1):
+        single = leg(None, budget * 0.4)
+    with mp.get_context("fork").Pool(cores, initializer=_one_blas_thread) as pool:
+        leg(pool, 0.5)                      # start the workers
+        per_core = leg(pool, budget)
+    blas = leg(None, budget * 0.4)
+    return {"value": per_core["value"], "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"{per_core['units']} (sequence, head) decode units of layer 0 (32 distinct, context {S}, bf16 bytes "
+                      f"counted as for the GPU), {per_core['seconds']:.1f} s, one single-threaded process per core over "
+                      "independent units",
+            "us_per_unit": per_core["us_per_unit"], "nproc": nproc,
+            "single_thread": {"value": single["value"], "unit": "GB/s", "us_per_unit": single["us_per_unit"],
+                              "seconds": single["seconds"]},
+            "numpy_threads_one_unit_at_a_time": {"value": blas["value"], "unit": "GB/s", "threads": int(blas_threads),
+                                                 "us_per_unit": blas["us_per_unit"], "seconds": blas["seconds"]}}
+
+
+# Vector-ALU cost of the softmax per score in the prefill kernel, from its instruction mix: per lane and 16 scores
+# about 67 ordinary vector instructions (scale-and-subtract fma, running sum, maximum, packing to bf16, masks)
+# and 17 v_exp_f32; measured issue cost with four waves per SIMD 2.4 and 8.5 cycles per wave instruction
+# (the transcendental runs at quarter rate and does not overlap other vector work): 305 cycles per 1024 scores.
+VALU_CYCLES_PER_SCORE = 305.0 / 1024.0
+N_SIMD, SHADER_HZ = 256 * 4, 2.4e9
+
+
+def valu_ceiling(n_scores, flops):
+    """What the vector ALU alone allows: the time its softmax work takes on all SIMDs at the peak clock, and the
+    TFLOP/s of the two products if nothing else took time. The lower of this and the MFMA peak bounds the kernel."""
+    ms = n_scores * VALU_CYCLES_PER_SCORE / (N_SIMD * SHADER_HZ) * 1e3
+    tf = flops / (ms * 1e-3) / 1e12
+    return {"valu_only_ms": ms, "TFLOPs_if_valu_bound": tf, "binding_ceiling_TFLOPs": min(tf, MFMA_BF16_PEAK_TFLOPS),
+            "bound": "valu/exp" if tf < MFMA_BF16_PEAK_TFLOPS else "mfma"}
 
 
 def run_prefill_workload(fdc, gen, iters=20, warm=10):
@@ -377,6 +432,9 @@ def run_prefill_workload(fdc, gen, iters=20, warm=10):
         if not name.startswith("rope_"):
             total_ms += ms          # the five calls of the RoPE-free chain; the post-RoPE calls are alternatives
         out[name] = {"ms": ms, "TFLOPs": flops / (ms * 1e-3) / 1e12, "frac_of_bf16_mfma_peak": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        if name == "latent_attn_prefill":
+            n_scores = float(B * H * (S * (S + 1) // 2))
+            out[name]["softmax_valu_ceiling"] = valu_ceiling(n_scores, flops)
     out["total_ms"] = total_ms
     # attention alone by rank bucket: every head at the same rank (MFMA-bound when wide, exp-bound when narrow)
     buckets = {}
@@ -406,7 +464,9 @@ def run_prefill_workload(fdc, gen, iters=20, warm=10):
         torch.cuda.synchronize()
         ms = s.elapsed_time(e) / iters
         fl = float(B * H * rr * 2 * 2 * (S * (S + 1) // 2))
-        buckets["rank_%d" % rr] = {"ms": ms, "TFLOPs": fl / (ms * 1e-3) / 1e12}
+        buckets["rank_%d" % rr] = {"ms": ms, "TFLOPs": fl / (ms * 1e-3) / 1e12,
+                                   "frac_of_bf16_mfma_peak": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                                   "softmax_valu_ceiling": valu_ceiling(float(B * H * (S * (S + 1) // 2)), fl)}
     out["latent_attn_prefill_by_uniform_rank"] = buckets
     return out
 
@@ -460,6 +520,71 @@ def run_gqa_decode_workload(fdc, gen, iters=20):
             "tile_kernel_us": tile, "tile_kernel_GBps": cache_bytes / tile / 1e3,
             "frac_of_hbm_peak": cache_bytes / tile / 1e3 / HBM_PEAK_GBPS,
             "call_us": call_us, "call_GBps": cache_bytes / call_us / 1e3}
+
+
+def run_single_layer_decode(fdc, gen, name, copies=4, iters=24):
+    """One decode-attention layer of a single-layer configuration (uniform rank 64 at batch 8 x 4096, whose cache is
+    exactly the size of the last-level cache; or one 131072-token sequence cut into >= 256 chunks per head), timed
+    over `copies` rotating copies of the cache so that no launch finds its bytes in the last-level cache."""
+    import torch
+    dev = "cuda:0"
+    wl = gen.CONFIGS[name]
+    ranks = wl.ranks()
+    H, B, S, dh = wl.n_heads, wl.batch, wl.context, wl.d_head
+    lay = fdc.Layout(1, H, wl.d_model, dh, ranks, ranks, B, S, fdc.FDC_BF16)
+    t = lay.tables()
+    RK, RV = int(t["koff_r"][0, -1]), int(t["voff_r"][0, -1])
+    gt = torch.Generator(device=dev).manual_seed(wl.seed + 3)
+    bf = torch.bfloat16
+    kcs, vcs = [], []
+    for _ in range(copies):
+        k = torch.empty(int(t["k_bytes"][0]) // 2, dtype=bf, device=dev)
+        v = torch.empty(int(t["v_bytes"][0]) // 2, dtype=bf, device=dev)
+        fill_latent(k, lay, t["koff_r"][0], ranks[0], B, S, wl.decay, gt)
+        fill_latent(v, lay, t["voff_r"][0], ranks[0], B, S, wl.decay, gt)
+        kcs.append(k), vcs.append(v)
+    q_lat = torch.randn(B, RK, generator=gt, device=dev)
+    o_lat = torch.empty(B, RV, device=dev)
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(0), wl.min_split
+    plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
+    ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + plan.workspace_bytes()]
+    fdc.fdc_plan_upload(plan, ws)
+    scale = 1.0 / math.sqrt(dh)
+    fn = lambda i: fdc.fdc_latent_attn_decode(lay, plan, q_lat, kcs[i % copies], vcs[i % copies], scale, o_lat, ws)
+    for i in range(2 * copies):
+        fn(i)
+    torch.cuda.synchronize()
+    ev = HipEvents(2 * iters)
+    for i in range(iters):
+        fdc.fdc_profile_decode_events(ev.ev[2 * i], ev.ev[2 * i + 1])
+        fn(i)
+    torch.cuda.synchronize()
+    tile_us = [ev.ms(2 * i, 2 * i + 1) * 1e3 for i in range(iters)]
+    ev.destroy()
+    s_, e_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s_.record()
+    for i in range(iters):
+        fn(i)
+    e_.record()
+    torch.cuda.synchronize()
+    call_us = s_.elapsed_time(e_) * 1e3 / iters
+    tab = plan.export()
+    nbytes = float(decode_bytes(tab, ranks[0], ranks[0], [S] * B, RK, RV, B))
+    per_unit = np.diff(tab["unit_item_ptr"])
+    merge_bytes = float(sum(int(n) * (int(ranks[0][u % H]) + 2) * 4 for u, n in enumerate(per_unit) if n > 1))
+    tile = float(np.mean(tile_us))
+    return {"workload": "%s: %d heads, batch %d, context %d, min_split %d, %d rotating cache copies of %.0f MB" %
+                        (name, H, B, S, wl.min_split, copies, (kcs[0].numel() + vcs[0].numel()) * 2 / 1e6),
+            "n_workers": pp.n_workers, "tiles": int(tab["n_items"]), "tiles_per_unit_min_max": [int(per_unit.min()), int(per_unit.max())],
+            "algorithmic_bytes": nbytes,
+            "tile_kernel_us": tile, "tile_kernel_us_min": float(np.min(tile_us)), "tile_kernel_GBps": nbytes / tile / 1e3,
+            "tile_kernel_frac_of_hbm_peak": nbytes / tile / 1e3 / HBM_PEAK_GBPS,
+            "call_us": call_us, "call_GBps": (nbytes + merge_bytes) / call_us / 1e3,
+            "call_frac_of_hbm_peak": (nbytes + merge_bytes) / call_us / 1e3 / HBM_PEAK_GBPS,
+            "merge_and_launch_us": call_us - tile}
 
 
 def run_fp8_decode_workload(fdc, gen, wl, iters=12):
@@ -643,7 +768,12 @@ def main():
     ap.add_argument("--no-fp8", action="store_true")
     ap.add_argument("--no-device-planner", action="store_true")
     ap.add_argument("--no-serving-loop", action="store_true")
+    ap.add_argument("--no-single-layer", action="store_true", help="skip the uniform-rank and long-context side objects")
+    ap.add_argument("--oracle-legs", default=None, help=argparse.SUPPRESS)   # child process of cpu_baseline
     args = ap.parse_args()
+    if args.oracle_legs:
+        print(json.dumps(oracle_legs(json.loads(args.oracle_legs))))
+        return
     if args.gpus != 1:
         print("bench.py: this build measures one GPU; --gpus N with N > 1 is not supported "
               "(no collective is part of this path)", file=sys.stderr)
@@ -695,6 +825,9 @@ def main():
         except Exception as exc:   # noqa: BLE001
             line[name] = {"error": f"{type(exc).__name__}: {exc}"}
             print(f"bench.py: {name} failed: {exc}", file=sys.stderr)
+    if not args.no_single_layer:
+        side("c2_uniform_decode", lambda: run_single_layer_decode(fdc, gen, "c2_uniform_decode"))
+        side("c4_long_decode", lambda: run_single_layer_decode(fdc, gen, "c4_long_decode"))
     if not args.no_prefill:
         side("prefill", lambda: run_prefill_workload(fdc, gen))
     if not args.no_gqa:
