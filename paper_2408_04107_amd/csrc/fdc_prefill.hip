@@ -58,7 +58,8 @@ constexpr int VROW = 128 + 16;           // V' tile: 288 bytes (the transposing 
 constexpr int kStageElems = BCB * KROW + BCB * VROW;  // one buffer: K' tile then V' tile
 constexpr float kLog2eP = 1.4426950408889634f;
 constexpr float kRaise = 5.0f;           // lazy softmax reference: p <= 2^5 between raises
-constexpr int RK32 = 4, RV16 = 8;        // unroll bounds: ceil(rk / 32) <= 4, rv / 16 <= 8
+// (the k-steps ceil(rk / 32) <= 4 of the score product and the column tiles rv / 16 <= 8 of the output are
+// template parameters of the task body: an upper bound of the head's own counts)
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {  // v_cvt_pk_bf16_f32, round to nearest even
   union { bf16x2 v; uint32_t u; } r;
@@ -88,12 +89,65 @@ union Frag {
   bf16x8 v;
 };
 
-// One instantiation serves every rank: the k-steps of the score product and the column tiles of
-// the output are fully unrolled loops with wave-uniform guards, so register arrays keep
-// compile-time indices and narrow heads skip the unused steps.
+// The two products of a 64-token set, with the number of k-steps / column tiles as a compile-time
+// constant (the caller switches on the head's rank class). With run-time bounds the unrolled loops
+// kept a branch after every step, so each LDS read sat in a basic block of its own right in front
+// of the multiply that needs it and its whole latency was exposed, step after step. Here a
+// fragment is requested as soon as the multiply that used its registers has been issued, one tile
+// ahead, so the reads of tile j + 1 are in flight under the multiplies of tile j.
+template <int RK32T, int NQ>
+__device__ __forceinline__ void score_tiles(const uint16_t* __restrict__ lk, const Frag (*qf)[RK32T], f32x4 (*st)[NQ], int ln, int lg) {
+  Frag kf[RK32T];
+  const uint16_t* src = lk + ln * KROW + 8 * lg;
+#pragma unroll
+  for (int ks = 0; ks < RK32T; ++ks) kf[ks].u = *reinterpret_cast<const u32x4*>(src + 32 * ks);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+#pragma unroll
+    for (int ks = 0; ks < RK32T; ++ks) {
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < NQ; ++i)
+        st[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks].v, qf[i][ks].v, ks == 0 ? zero : st[j][i], 0, 0, 0);
+      if (j < 3) kf[ks].u = *reinterpret_cast<const u32x4*>(src + 16 * (j + 1) * KROW + 32 * ks);
+    }
+  }
+}
+
+// O^T += V'^T P^T for RV16T column tiles. A operand: lane (ln, lg) must hold column 16 c + ln for the
+// tokens 32 jp + 4 lg + e and 32 jp + 16 + 4 lg + e (the order P has them). Transposing load: inside
+// the 16-lane group lg, source lane s addresses token 4 lg + s / 4, columns 16 c + 4 (s % 4) ..
+template <int RV16T, int NQ>
+__device__ __forceinline__ void pv_tiles(const uint16_t* __restrict__ lv, const Frag (*pf)[2], f32x4 (*oacc)[RV16T], int ln, int lg) {
+  const uint16_t* vsrc = lv + (4 * lg + ln / 4) * VROW + 4 * (ln % 4);
+  auto load = [&](int idx) {
+    const uint16_t* a0 = vsrc + (32 * (idx % 2)) * VROW + 16 * (idx / 2);
+    union { s16x4 s; u32x2 u; } lo, hi;
+    lo.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
+    hi.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 16 * VROW));
+    Frag f;
+    f.u = u32x4{lo.u[0], lo.u[1], hi.u[0], hi.u[1]};
+    return f;
+  };
+  Frag vf[2];
+  vf[0] = load(0);
+#pragma unroll
+  for (int idx = 0; idx < 2 * RV16T; ++idx) {
+    if (idx + 1 < 2 * RV16T) vf[(idx + 1) & 1] = load(idx + 1);
+#pragma unroll
+    for (int i = 0; i < NQ; ++i)
+      oacc[i][idx / 2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[idx & 1].v, pf[i][idx % 2].v, oacc[i][idx / 2], 0, 0, 0);
+  }
+}
+
+// The body of a task is instantiated per rank class (RK32 = k-steps of the score product, RV16 = column
+// tiles of the output, the head's own counts or the next instantiated ones above): loop bounds are
+// compile-time, so the products are straight-line code with their LDS reads pipelined, and the
+// accumulators of a narrow head take the registers that head needs and no more. The kernel switches
+// per task; a workgroup runs one instantiation at a time.
 // TC is the cache element: uint16_t (bf16) or uint8_t (E4M3 codes, widened to bf16, which holds them
 // exactly, on their way from the staging registers to LDS; everything after that is the same).
-template <typename TC>
+template <typename TC, int RK32, int RV16>
 __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* __restrict__ q_lat,
                                              const TC* __restrict__ kc, const TC* __restrict__ vc,
                                              float scale_log2, int causal, uint16_t* __restrict__ o_lat,
@@ -102,7 +156,8 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   const int rk = t.rk_rv & 0xffff, rv = t.rk_rv >> 16;
   const int rk32 = (rk + 31) / 32, rv16 = rv / 16;
   const int RKP = rk32 * 32;  // rank of the K' rows in LDS, padded with zeros
-  const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
+  const int tid = threadIdx.x, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // known uniform: conditions on it become scalar branches
   const int ln = lane % 16, lg = lane / 16;
   const TC* kbase = kc + t.k_elem;
   const TC* vbase = vc + t.v_elem;
@@ -246,24 +301,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         const uint16_t* lv = lds + buf * kStageElems + BCB * KROW + hf * BC * VROW;
         // S^T tiles: st[j][i] = tokens 16 j .. of the block x query rows of tile i
         f32x4 st[4][QT];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          {  // first k-step starts from a constant zero accumulator (no register clearing)
-            Frag kf;
-            kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 8 * lg]);
-            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int i = 0; i < QT; ++i) st[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[i][0].v, zero, 0, 0, 0);
-          }
-#pragma unroll
-          for (int ks = 1; ks < RK32; ++ks) {
-            if (ks >= rk32) break;
-            Frag kf;
-            kf.u = *reinterpret_cast<const u32x4*>(&lk[(16 * j + ln) * KROW + 32 * ks + 8 * lg]);
-#pragma unroll
-            for (int i = 0; i < QT; ++i) st[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf.v, qf[i][ks].v, st[j][i], 0, 0, 0);
-          }
-        }
+        score_tiles<RK32, QT>(lk, qf, st, ln, lg);
         // mask, online softmax. Lane (ln, lg) holds tokens c0 + 16 j + 4 lg + e of row ln.
         // p = 2^((s - m) * scale * log2 e) as one fma per score.
         const bool need_mask = (causal && c0 + BC - 1 > t.pos0 + wrow0) || c0 + BC > t.kv_len;
@@ -272,6 +310,9 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         for (int i = 0; i < QT; ++i) {
           const int pos = pos_base + 16 * i;
           if (need_mask) {
+            // only the sets on the causal diagonal and at the end of the keys come here; the empty statement keeps
+            // the compiler from turning the branch into sixteen compares and selects that every set would execute
+            asm volatile("" ::: "memory");
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -320,25 +361,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
             pf[i][jp].u[3] = pack_bf16(p[2 * jp + 1][2], p[2 * jp + 1][3]);
           }
         }
-        // O^T += V'^T P^T. A operand: lane (ln, lg) must hold column 16 c + ln for the tokens
-        // 32 jp + 4 lg + e and 32 jp + 16 + 4 lg + e (the order P has them). Transposing load: inside
-        // the 16-lane group lg, source lane s addresses token 4 lg + s / 4, columns 16 c + 4 (s % 4) ..
-        const uint16_t* vsrc = lv + (4 * lg + ln / 4) * VROW + 4 * (ln % 4);
-#pragma unroll
-        for (int c = 0; c < RV16; ++c) {
-          if (c >= rv16) break;
-#pragma unroll
-          for (int jp = 0; jp < 2; ++jp) {
-            const uint16_t* a0 = vsrc + (32 * jp) * VROW + 16 * c;
-            union { s16x4 s; u32x2 u; } lo, hi;
-            lo.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0));
-            hi.s = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(a0 + 16 * VROW));
-            Frag vf;
-            vf.u = u32x4{lo.u[0], lo.u[1], hi.u[0], hi.u[1]};
-#pragma unroll
-            for (int i = 0; i < QT; ++i) oacc[i][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf.v, pf[i][jp].v, oacc[i][c], 0, 0, 0);
-          }
-        }
+        pv_tiles<RV16, QT>(lv, pf, oacc, ln, lg);
       }
       }
       if (more) stage(buf ^ 1);  // the other buffer was last read before the previous barrier
@@ -379,7 +402,28 @@ __global__ __launch_bounds__(kPreThreads) __attribute__((amdgpu_waves_per_eu(kPr
   const int i0 = worker_ptr[w], i1 = worker_ptr[w + 1];
   for (int it = i0; it < i1; ++it) {
     const PreTask t = tasks[worker_items[it]];
-    prefill_task<TC>(t, q_lat, kc, vc, scale_log2, causal, o_lat, page_table, page_stride_k, page_stride_v, lds);
+    // one copy of the task body per (k-steps, column tiles) class of the head; column-tile counts 5 and 7 round
+    // up (the padded tile multiplies whatever the LDS columns behind a row's rank hold, stride padding or stale
+    // data of a wider head, into accumulators of their own, and the output columns past rv are never stored)
+    const int rk32 = ((t.rk_rv & 0xffff) + 31) / 32, rv16 = (t.rk_rv >> 16) / 16;
+#define FDC_PRE(a, b) prefill_task<TC, a, b>(t, q_lat, kc, vc, scale_log2, causal, o_lat, page_table, page_stride_k, page_stride_v, lds)
+#define FDC_PRE_ROW(a)                                      \
+  switch (rv16) {                                           \
+    case 1: FDC_PRE(a, 1); break;                           \
+    case 2: FDC_PRE(a, 2); break;                           \
+    case 3: FDC_PRE(a, 3); break;                           \
+    case 4: FDC_PRE(a, 4); break;                           \
+    case 5: case 6: FDC_PRE(a, 6); break;                   \
+    default: FDC_PRE(a, 8); break;                          \
+  }
+    switch (rk32) {
+      case 1: FDC_PRE_ROW(1) break;
+      case 2: FDC_PRE_ROW(2) break;
+      case 3: FDC_PRE_ROW(3) break;
+      default: FDC_PRE_ROW(4) break;
+    }
+#undef FDC_PRE_ROW
+#undef FDC_PRE
   }
 }
 
