@@ -362,9 +362,10 @@ fdc_status fdc_latent_attn_decode_static(const fdc_layout* lay, const fdc_plan* 
                                          void* stream);
 
 /* Measurement aid: when both arguments are non-NULL hipEvent_t handles, the next
- * fdc_latent_attn_decode call made by this thread records `start` immediately before and `stop`
- * immediately after its tile kernel (the kernel that streams the cache; the split-K merge runs
- * after `stop`), on that call's stream. The request is consumed by that call; NULLs cancel it. */
+ * fdc_latent_attn_decode call made by this thread attaches them to the dispatch of its tile kernel
+ * (the kernel that streams the cache): `start` takes the time that kernel begins, `stop` the time
+ * it ends, on that call's stream; the split-K merge runs after `stop`. The request is consumed by
+ * that call, whether it succeeds or not; NULLs cancel it. */
 fdc_status fdc_profile_decode_events(void* start_event, void* stop_event);
 
 /* Prefill attention on the latent cache (Section 5, step 7; Section 5.3 prefill scheduling).

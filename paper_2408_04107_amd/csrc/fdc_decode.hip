@@ -15,6 +15,7 @@
 // (m, l, acc) in a slot of their own (no atomics, deterministic) and a second small kernel merges
 // them.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 #include <mutex>
@@ -529,25 +530,31 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   if (plan->G > 1 && lay->dtype == FDC_F32)
     FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
   if (plan->on_device || !plan->item_b.empty()) {   // a device plan's tile count is not known here: empty workers return at once
-    if (ev0) FDC_HIP_CHECK(hipEventRecord(ev0, st));
+    // a profiling request attaches its two events to the tile kernel's own dispatch (its begin and its end)
+#define FDC_LAUNCH_TILES(kern, ...)                                                          \
+  do {                                                                                       \
+    if (ev0) hipExtLaunchKernelGGL(kern, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__);      \
+    else hipLaunchKernelGGL(kern, grid, block, 0, st, __VA_ARGS__);                          \
+  } while (0)
     if (plan->G > 1) {
       fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat), k_cache, v_cache,
-                                        lay->dtype == FDC_FP8, scale, static_cast<float*>(o_lat), partials, W, planned, lens, st);
+                                        lay->dtype == FDC_FP8, scale, static_cast<float*>(o_lat), partials, W, planned, lens,
+                                        ev0, ev1, st);
       if (gs != FDC_OK) return gs;
     } else if (lay->dtype == FDC_BF16)
-      hipLaunchKernelGGL(decode_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles,
-                         static_cast<const float*>(q_lat), static_cast<const uint16_t*>(k_cache),
-                         static_cast<const uint16_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
+      FDC_LAUNCH_TILES(decode_tiles_kernel<uint16_t>, heads, wtiles, static_cast<const float*>(q_lat),
+                       static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache), scale_log2,
+                       static_cast<float*>(o_lat), partials, W, planned, lens);
     else if (lay->dtype == FDC_FP8)
-      hipLaunchKernelGGL(decode_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles,
-                         static_cast<const float*>(q_lat), static_cast<const uint8_t*>(k_cache),
-                         static_cast<const uint8_t*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
+      FDC_LAUNCH_TILES(decode_tiles_kernel<uint8_t>, heads, wtiles, static_cast<const float*>(q_lat),
+                       static_cast<const uint8_t*>(k_cache), static_cast<const uint8_t*>(v_cache), scale_log2,
+                       static_cast<float*>(o_lat), partials, W, planned, lens);
     else
-      hipLaunchKernelGGL(decode_tiles_kernel<float>, grid, block, 0, st, heads, wtiles,
-                         static_cast<const float*>(q_lat), static_cast<const float*>(k_cache),
-                         static_cast<const float*>(v_cache), scale_log2, static_cast<float*>(o_lat), partials, W, planned, lens);
+      FDC_LAUNCH_TILES(decode_tiles_kernel<float>, heads, wtiles, static_cast<const float*>(q_lat),
+                       static_cast<const float*>(k_cache), static_cast<const float*>(v_cache), scale_log2,
+                       static_cast<float*>(o_lat), partials, W, planned, lens);
+#undef FDC_LAUNCH_TILES
     FDC_HIP_CHECK(hipGetLastError());
-    if (ev1) FDC_HIP_CHECK(hipEventRecord(ev1, st));
   }
   // One rule for every plan, so that a result does not depend on where the plan was made: a unit of at most
   // kMergeWaveMax tiles is merged by one wavefront in slot order, a unit of more by sixteen. Each kernel skips

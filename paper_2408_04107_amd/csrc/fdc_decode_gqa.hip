@@ -23,6 +23,7 @@
 // past the tile's end). Results go to the same partial-state slots / outputs as the multi-head
 // kernel, one per query head, and the same merge kernel combines them.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 
@@ -366,16 +367,30 @@ fdc_status decode_gqa_workers_per_cu(int* waves) {
 
 fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const void* kc,
                              const void* vc, bool e4m3, float scale, float* o_lat, float* partials, int n_workers,
-                             const int32_t* planned_len, const int32_t* seq_len, hipStream_t st) {
+                             const int32_t* planned_len, const int32_t* seq_len, hipEvent_t ev0, hipEvent_t ev1,
+                             hipStream_t st) {
   const dim3 grid((n_workers + kGqaWaves - 1) / kGqaWaves), block(kGqaWaves * 64);
-  if (e4m3)
-    hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles, q_lat,
-                       static_cast<const uint8_t*>(kc), static_cast<const uint8_t*>(vc), scale * kGqaLog2e, o_lat,
-                       partials, n_workers, planned_len, seq_len);
-  else
-    hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles, q_lat,
-                       static_cast<const uint16_t*>(kc), static_cast<const uint16_t*>(vc), scale * kGqaLog2e, o_lat,
-                       partials, n_workers, planned_len, seq_len);
+  const float scale_log2 = scale * kGqaLog2e;
+  // ev0 / ev1 (both or neither): events of the kernel's own dispatch, for the caller's profiling request
+  if (e4m3) {
+    const uint8_t* k8 = static_cast<const uint8_t*>(kc);
+    const uint8_t* v8 = static_cast<const uint8_t*>(vc);
+    if (ev0)
+      hipExtLaunchKernelGGL(decode_gqa_tiles_kernel<uint8_t>, grid, block, 0, st, ev0, ev1, 0, heads, wtiles, q_lat, k8, v8,
+                            scale_log2, o_lat, partials, n_workers, planned_len, seq_len);
+    else
+      hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint8_t>, grid, block, 0, st, heads, wtiles, q_lat, k8, v8, scale_log2,
+                         o_lat, partials, n_workers, planned_len, seq_len);
+  } else {
+    const uint16_t* k16 = static_cast<const uint16_t*>(kc);
+    const uint16_t* v16 = static_cast<const uint16_t*>(vc);
+    if (ev0)
+      hipExtLaunchKernelGGL(decode_gqa_tiles_kernel<uint16_t>, grid, block, 0, st, ev0, ev1, 0, heads, wtiles, q_lat, k16,
+                            v16, scale_log2, o_lat, partials, n_workers, planned_len, seq_len);
+    else
+      hipLaunchKernelGGL(decode_gqa_tiles_kernel<uint16_t>, grid, block, 0, st, heads, wtiles, q_lat, k16, v16, scale_log2,
+                         o_lat, partials, n_workers, planned_len, seq_len);
+  }
   FDC_HIP_CHECK(hipGetLastError());
   return FDC_OK;
 }

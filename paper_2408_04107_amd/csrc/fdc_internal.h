@@ -139,7 +139,8 @@ fdc_status decode_gqa_workers_per_cu(int* waves);
 namespace fdc {
 fdc_status launch_decode_gqa(const DecWorker* heads, const DecTile* wtiles, const float* q_lat, const void* kc,
                              const void* vc, bool e4m3, float scale, float* o_lat, float* partials, int n_workers,
-                             const int32_t* planned_len, const int32_t* seq_len, hipStream_t st);
+                             const int32_t* planned_len, const int32_t* seq_len, hipEvent_t ev0, hipEvent_t ev1,
+                             hipStream_t st);
 }
 #endif
 
