@@ -14,6 +14,8 @@ Modules
   planner    decode LPT list scheduling, prefill row-block rescaling and
              last-round redistribution                   (Section 5.3)
   rank_select  per-head compression rate from the singular-value removal rate (Eq. 1)
+  rope, gqa    post-RoPE rotation (Sections 3, 5.1) and grouped queries (Section 5.1)
+  fp8, fp4     quantised storage of the latent rows: E4M3 and E2M1 codes (a reading of Section 6.2)
 
 Pin status: every function is pinned by the CPU tests (full-rank equals
 standard attention, exact-rank equals uncompressed attention, closed forms,
