@@ -12,7 +12,7 @@ time; `roofline` describes the dominant kernel (the decode tile kernel) from HIP
 around that kernel alone; `cpu_baseline` is the float64 oracle timed on the host on a bounded
 sample; `prefill` reports the MFMA calls of the prefill configuration in TFLOP/s. Further objects of
 the same line are side measurements of the other rows (`c2_uniform_decode`, `c4_long_decode`: one layer over
-rotating cache copies; `gqa_decode`, `fp8_decode`, `device_planner`, `serving_loop`); each has a --no-... switch
+rotating cache copies; `gqa_decode`, `fp8_decode`, `fp4_decode`, `device_planner`, `serving_loop`); each has a --no-... switch
 and a failure in one of them is reported in its place.
 """
 from __future__ import annotations
@@ -587,27 +587,29 @@ def run_single_layer_decode(fdc, gen, name, copies=4, iters=24):
             "merge_and_launch_us": call_us - tile}
 
 
-def run_fp8_decode_workload(fdc, gen, wl, iters=12):
+def run_fp8_decode_workload(fdc, gen, wl, iters=12, fp4=False):
     """Decode attention of layer 0 of the decode workload with the cache stored as E4M3 codes
-    (FDC_FP8 layout): the same tokens and ranks at half the cache bytes."""
+    (FDC_FP8 layout): the same tokens and ranks at half the cache bytes; or as E2M1 codes (FDC_FP4 layout,
+    two codes per byte): a quarter of the bytes."""
     import torch
     dev = "cuda:0"
     ranks = wl.ranks()[:1]
     H, B, S, dh = wl.n_heads, wl.batch, wl.context, wl.d_head
-    lay = fdc.Layout(1, H, wl.d_model, dh, ranks, ranks, B, S, fdc.FDC_FP8)
+    lay = fdc.Layout(1, H, wl.d_model, dh, ranks, ranks, B, S, fdc.FDC_FP4 if fp4 else fdc.FDC_FP8)
     t = lay.tables()
     RK = int(t["koff_r"][0, -1])
     gt = torch.Generator(device=dev).manual_seed(9)
     n = int(t["k_bytes"][0])
-    copies = 3   # rotate cache copies so that no launch finds its bytes in the last-level cache
-    # random finite codes: any byte but the two NaN patterns
-    mk = lambda: torch.randint(0, 0x7F, (n,), generator=gt, device=dev, dtype=torch.uint8) | \
-        (torch.randint(0, 2, (n,), generator=gt, device=dev, dtype=torch.uint8) << 7)
+    copies = 4 if fp4 else 3   # rotate cache copies so that no launch finds its bytes in the last-level cache
+    # random finite codes: any byte but the two NaN patterns (every byte is a pair of finite E2M1 codes)
+    mk = (lambda: torch.randint(0, 256, (n,), generator=gt, device=dev, dtype=torch.uint8)) if fp4 else \
+        (lambda: torch.randint(0, 0x7F, (n,), generator=gt, device=dev, dtype=torch.uint8) |
+         (torch.randint(0, 2, (n,), generator=gt, device=dev, dtype=torch.uint8) << 7))
     kcs, vcs = [mk() for _ in range(copies)], [mk() for _ in range(copies)]
     q_lat = torch.randn(B, RK, generator=gt, device=dev) * 0.01
     o_lat = torch.empty(B, RK, device=dev)
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(3), wl.min_split
+    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(4 if fp4 else 3), wl.min_split
     plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
     ws = torch.empty(plan.workspace_bytes() + 256, dtype=torch.uint8, device=dev)
     off = (-ws.data_ptr()) % 256
@@ -624,8 +626,9 @@ def run_fp8_decode_workload(fdc, gen, wl, iters=12):
     torch.cuda.synchronize()
     tile = float(np.mean([ev.ms(2 * i, 2 * i + 1) for i in range(iters)])) * 1e3
     ev.destroy()
-    cache_bytes = float(B * S * 2 * int(np.sum(ranks[0])))    # one byte per cached element
-    return {"workload": "layer 0 of %s with an E4M3 cache (one byte per element)" % wl.name,
+    cache_bytes = float(B * S * 2 * int(np.sum(ranks[0]))) * (0.5 if fp4 else 1.0)    # one byte (half a byte) per cached element
+    return {"workload": "layer 0 of %s with an %s" % (wl.name, "E2M1 cache (half a byte per element)" if fp4 else
+                                                      "E4M3 cache (one byte per element)"),
             "n_workers": pp.n_workers, "tiles": int(plan.export()["n_items"]),
             "tile_kernel_us": tile, "tile_kernel_GBps": cache_bytes / tile / 1e3,
             "frac_of_hbm_peak": cache_bytes / tile / 1e3 / HBM_PEAK_GBPS,
@@ -834,6 +837,7 @@ def main():
         side("gqa_decode", lambda: run_gqa_decode_workload(fdc, gen))
     if not args.no_fp8:
         side("fp8_decode", lambda: run_fp8_decode_workload(fdc, gen, wl))
+        side("fp4_decode", lambda: run_fp8_decode_workload(fdc, gen, wl, fp4=True))
     if not args.no_device_planner:
         side("device_planner", lambda: run_device_planner(fdc, gen, wl))
     if not args.no_serving_loop:

@@ -31,7 +31,16 @@
  *    B_v.W_o multiplied by them), so attention works on the decoded code
  *    values (the paper combines its compression with cache quantisation in
  *    Section 6.2 and fixes no format: a reading). Every call takes FDC_FP8
- *    layouts.
+ *    layouts. FDC_FP4 = the caches hold OCP E2M1 codes (the 4-bit element type of
+ *    the Microscaling formats: +-{0, 0.5, 1, 1.5, 2, 3, 4, 6}; round to nearest,
+ *    ties to the even mantissa, saturating at +-6), two per byte: the element
+ *    with the even column index in bits 3..0, its right neighbour in bits 7..4;
+ *    a buffer holds elems / 2 bytes and element offsets are halved to address it.
+ *    As for FDC_FP8 no scales are stored; here a scale per (head, latent column)
+ *    folds into the factors. Supported by fdc_project_latent_kv,
+ *    fdc_project_and_absorb_query, fdc_rope_compress_keys, multi-head
+ *    fdc_latent_attn_decode(_at, _static) and fdc_latent_attn_prefill; grouped
+ *    decode attention over an FDC_FP4 cache is FDC_UNSUPPORTED_DTYPE.
  *  - fdc_layout and fdc_plan are host objects, immutable after creation
  *    (except that fdc_plan_download fills in the host tables of a plan whose
  *    schedule was computed on the device), destroyed by the matching call.
@@ -57,7 +66,7 @@ typedef enum {
   FDC_UNSUPPORTED_DTYPE = -7
 } fdc_status;
 
-typedef enum { FDC_BF16 = 0, FDC_F32 = 1, FDC_FP8 = 2 } fdc_dtype;
+typedef enum { FDC_BF16 = 0, FDC_F32 = 1, FDC_FP8 = 2, FDC_FP4 = 3 } fdc_dtype;
 
 typedef struct fdc_layout fdc_layout;
 typedef struct fdc_plan fdc_plan;
@@ -150,8 +159,8 @@ typedef struct {
 void fdc_plan_params_default(fdc_plan_params* p);
 
 /* Number of workers that are resident at once on the current HIP device for the decode
- * (kind 0), prefill (kind 1), grouped-query decode (kind 2, layouts with q_per_kv > 1) or E4M3-cache
- * decode (kind 3, FDC_FP8 layouts) kernel.
+ * (kind 0), prefill (kind 1), grouped-query decode (kind 2, layouts with q_per_kv > 1), E4M3-cache
+ * decode (kind 3, FDC_FP8 layouts) or E2M1-cache decode (kind 4, FDC_FP4 layouts) kernel.
  * Needs a GPU (FDC_HIP_ERROR otherwise). */
 fdc_status fdc_suggest_workers(int kind, int32_t* n_workers);
 

@@ -16,7 +16,7 @@ import numpy as np
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfdc.so")
 
-FDC_BF16, FDC_F32, FDC_FP8 = 0, 1, 2
+FDC_BF16, FDC_F32, FDC_FP8, FDC_FP4 = 0, 1, 2, 3
 FDC_FOLD, FDC_APPLY = 0, 1
 
 EXPORTED_SYMBOLS = [

@@ -47,6 +47,7 @@ constexpr int kBufferFlags = 0x00020000;  // word 3 of a gfx9 raw buffer descrip
 constexpr int kStreamPolicy = 2;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // ---- small device helpers -------------------------------------------------------------------
 template <int CTRL>
@@ -82,9 +83,15 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 template <typename T>
 struct Elem;
+// EL elements per lane and load, BITS per element, Reg the loaded registers (a 16-byte load, 8 bytes for E2M1 so
+// that the narrowest row, sixteen codes, is still one lane's load).
 template <>
 struct Elem<uint16_t> {  // bf16 bits
-  static constexpr int EL = 8;
+  static constexpr int EL = 8, BITS = 16;
+  typedef u32x4 Reg;
+  __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
+  }
   __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
     f[0] = __uint_as_float(r[0] << 16), f[1] = __uint_as_float(r[0] & 0xffff0000u);
     f[2] = __uint_as_float(r[1] << 16), f[3] = __uint_as_float(r[1] & 0xffff0000u);
@@ -94,7 +101,11 @@ struct Elem<uint16_t> {  // bf16 bits
 };
 template <>
 struct Elem<uint8_t> {  // OCP E4M3 codes: sixteen elements per 16-byte load, decoded in pairs (v_cvt_pk_f32_fp8)
-  static constexpr int EL = 16;
+  static constexpr int EL = 16, BITS = 8;
+  typedef u32x4 Reg;
+  __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
+  }
   __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -105,8 +116,31 @@ struct Elem<uint8_t> {  // OCP E4M3 codes: sixteen elements per 16-byte load, de
   }
 };
 template <>
+struct Elem<fp4_t> {  // OCP E2M1 codes: sixteen elements per 8-byte load, decoded a byte (two codes) at a time
+  static constexpr int EL = 16, BITS = 4;
+  typedef u32x2 Reg;
+  __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
+    return __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, kStreamPolicy);
+  }
+  __device__ static __forceinline__ void widen(const u32x2& r, float* f) {
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+      const auto b0 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r[w], 1.0f, 0);   // byte 0: elements 8 w, 8 w + 1
+      const auto b1 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r[w], 1.0f, 1);
+      const auto b2 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r[w], 1.0f, 2);
+      const auto b3 = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(r[w], 1.0f, 3);
+      f[8 * w + 0] = b0[0], f[8 * w + 1] = b0[1], f[8 * w + 2] = b1[0], f[8 * w + 3] = b1[1];
+      f[8 * w + 4] = b2[0], f[8 * w + 5] = b2[1], f[8 * w + 6] = b3[0], f[8 * w + 7] = b3[1];
+    }
+  }
+};
+template <>
 struct Elem<float> {
-  static constexpr int EL = 4;
+  static constexpr int EL = 4, BITS = 32;
+  typedef u32x4 Reg;
+  __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
+  }
   __device__ static __forceinline__ void widen(const u32x4& r, float* f) {
     f[0] = __uint_as_float(r[0]), f[1] = __uint_as_float(r[1]);
     f[2] = __uint_as_float(r[2]), f[3] = __uint_as_float(r[3]);
@@ -146,26 +180,27 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
   // block) and loads of padded lanes (offset forced out of range) return zeros in hardware, so
   // the stream has no branches. The range check covers the VGPR offset only, so the whole
   // row offset is kept there.
-  const int k_row_bytes = rk * (int)sizeof(T), v_row_bytes = rv * (int)sizeof(T);
+  constexpr int BITS = Elem<T>::BITS, LB = EL * BITS / 8;   // bits per element, bytes per lane and load
+  const int k_row_bytes = rk * BITS / 8, v_row_bytes = rv * BITS / 8;
   const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<T*>(kc + td.k_elem), 0, len * k_row_bytes, kBufferFlags);
+      const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(kc) + td.k_elem * BITS / 8), 0, len * k_row_bytes, kBufferFlags);
   const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<T*>(vc + td.v_elem), 0, len * v_row_bytes, kBufferFlags);
-  const uint32_t k_lane = k_on ? (uint32_t)(sk * k_row_bytes + ck * 16) : 0x80000000u;
-  const uint32_t v_lane = v_on ? (uint32_t)(sv * v_row_bytes + cv * 16) : 0x80000000u;
+      const_cast<uint8_t*>(reinterpret_cast<const uint8_t*>(vc) + td.v_elem * BITS / 8), 0, len * v_row_bytes, kBufferFlags);
+  const uint32_t k_lane = k_on ? (uint32_t)(sk * k_row_bytes + ck * LB) : 0x80000000u;
+  const uint32_t v_lane = v_on ? (uint32_t)(sv * v_row_bytes + cv * LB) : 0x80000000u;
 
-  u32x4 kreg[NK], vreg[NV];
+  typename Elem<T>::Reg kreg[NK], vreg[NV];
   auto load_k = [&](int t0) {
     const uint32_t base = k_lane + (uint32_t)(t0 * k_row_bytes);
 #pragma unroll
     for (int i = 0; i < NK; ++i)
-      kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, (int)(base + (uint32_t)(i * RK_ROWS * k_row_bytes)), 0, kStreamPolicy);
+      kreg[i] = Elem<T>::load(k_rsrc, (int)(base + (uint32_t)(i * RK_ROWS * k_row_bytes)));
   };
   auto load_v = [&](int t0) {
     const uint32_t base = v_lane + (uint32_t)(t0 * v_row_bytes);
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-      vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, (int)(base + (uint32_t)(i * RV_ROWS * v_row_bytes)), 0, kStreamPolicy);
+      vreg[i] = Elem<T>::load(v_rsrc, (int)(base + (uint32_t)(i * RV_ROWS * v_row_bytes)));
   };
 
   float acc[EL];
@@ -470,6 +505,11 @@ fdc_status fdc_suggest_workers(int kind, int32_t* n_workers) {
     FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<uint8_t>,
                                                                kWavesPerBlock * 64, 0));
     *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
+  } else if (kind == 4) {
+    int nb = 0;
+    FDC_HIP_CHECK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, decode_tiles_kernel<fp4_t>,
+                                                               kWavesPerBlock * 64, 0));
+    *n_workers = prop.multiProcessorCount * std::max(nb, 1) * kWavesPerBlock;
   } else if (kind == 2) {
     int waves = 0;
     fdc_status st = decode_gqa_workers_per_cu(&waves);
@@ -527,7 +567,7 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
   const float scale_log2 = scale * kLog2e;
-  if (plan->G > 1 && lay->dtype == FDC_F32)
+  if (plan->G > 1 && (lay->dtype == FDC_F32 || lay->dtype == FDC_FP4))
     FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
   if (plan->on_device || !plan->item_b.empty()) {   // a device plan's tile count is not known here: empty workers return at once
     // a profiling request attaches its two events to the tile kernel's own dispatch (its begin and its end)
@@ -548,6 +588,10 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
     else if (lay->dtype == FDC_FP8)
       FDC_LAUNCH_TILES(decode_tiles_kernel<uint8_t>, heads, wtiles, static_cast<const float*>(q_lat),
                        static_cast<const uint8_t*>(k_cache), static_cast<const uint8_t*>(v_cache), scale_log2,
+                       static_cast<float*>(o_lat), partials, W, planned, lens);
+    else if (lay->dtype == FDC_FP4)
+      FDC_LAUNCH_TILES(decode_tiles_kernel<fp4_t>, heads, wtiles, static_cast<const float*>(q_lat),
+                       static_cast<const fp4_t*>(k_cache), static_cast<const fp4_t*>(v_cache), scale_log2,
                        static_cast<float*>(o_lat), partials, W, planned, lens);
     else
       FDC_LAUNCH_TILES(decode_tiles_kernel<float>, heads, wtiles, static_cast<const float*>(q_lat),

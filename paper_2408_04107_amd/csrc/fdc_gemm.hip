@@ -75,6 +75,7 @@ struct GemmArgs {
   const int32_t* tok_pos;
   int v_only;             // project: B holds only the V' rows, every column goes to the V' cache
   int cache_fp8;          // project: the caches hold E4M3 codes (one byte per element) instead of bf16
+  int cache_fp4;          // project: the caches hold E2M1 codes, two per byte (even column in the low nibble)
   const float* rope_cos;  // post-RoPE path: [n_pos, d_head / 2]
   const float* rope_sin;
   int n_pos;
@@ -122,8 +123,21 @@ __device__ __forceinline__ void store_out<uint16_t>(uint16_t* p, float v) { *p =
 
 // One cache element: bf16, or the E4M3 code of the value saturated to +-448 (v_cvt_pk_fp8_f32 rounds
 // to nearest even and would turn larger values into NaN).
+// Two values -> one byte of E2M1 codes (v_cvt_scalef32_pk_fp4_f32 with scale 1: round to nearest even;
+// the inputs are clamped to the format's range first): lo in bits 3..0, hi in bits 7..4.
+__device__ __forceinline__ uint32_t fp4_pair(float lo, float hi) {
+  const float a = fminf(fmaxf(lo, -6.f), 6.f), b = fminf(fmaxf(hi, -6.f), 6.f);
+  return __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(0u, a, b, 1.0f, 0) & 0xffu;
+}
+
+// E2M1 caches: every caller has neighbouring lanes hold neighbouring columns of one row (the even
+// column in the even lane), and a row's two lanes take the same branches, so the even lane fetches its
+// neighbour's value and writes the byte they share.
 __device__ __forceinline__ void store_cache(const GemmArgs& g, void* cache, int64_t e, float v) {
-  if (g.cache_fp8) {
+  if (g.cache_fp4) {
+    const float right = __shfl_xor(v, 1);
+    if ((threadIdx.x & 1) == 0) static_cast<uint8_t*>(cache)[e >> 1] = (uint8_t)fp4_pair(v, right);
+  } else if (g.cache_fp8) {
     const float c = fminf(fmaxf(v, -448.f), 448.f);
     static_cast<uint8_t*>(cache)[e] = (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(c, 0.f, 0u, false) & 0xffu);
   } else {
@@ -1216,7 +1230,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         if (tok[t] < 0) continue;
         if constexpr (KEYS) {
           const int64_t dst = tok_dst[t] + (int64_t)g.max_seq * g.koff_r[h] + (int64_t)g.tok_pos[tok[t]] * r + n;
-          if (g.cache_fp8) {
+          if (g.cache_fp4) {   // four consecutive columns: two bytes
+            const uint32_t w = fp4_pair(acc[t][0], acc[t][1]) | (fp4_pair(acc[t][2], acc[t][3]) << 8);
+            *reinterpret_cast<uint16_t*>(static_cast<uint8_t*>(g.C) + (dst >> 1)) = (uint16_t)w;
+          } else if (g.cache_fp8) {
             auto sat = [](float v) { return fminf(fmaxf(v, -448.f), 448.f); };
             uint32_t w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][0]), sat(acc[t][1]), 0u, false);
             w = __builtin_amdgcn_cvt_pk_fp8_f32(sat(acc[t][2]), sat(acc[t][3]), w, true);
@@ -1281,7 +1298,7 @@ static fdc_status launch(const fdc_layout* lay, const GemmArgs& a, int groups, i
     else if (c_f32) launch_skinny<uint16_t, float>(a, st);
     else launch_skinny<uint16_t, uint16_t>(a, st);
   } else if (!a_f32 && groups == 1 && (a.mode == kPlain || a.mode == kProject) && a.K % 8 == 0 && a.lda % 8 == 0 &&
-             a.ldb % 8 == 0) {
+             a.ldb % 8 == 0 && !(a.mode == kProject && a.cache_fp4)) {   // E2M1 caches take the per-element epilogue below
     GemmArgs b = a;
     b.nt = (a.N + DN - 1) / DN;
     const int tiles = b.nt * ((a.M + DM - 1) / DM);
@@ -1338,7 +1355,7 @@ fdc_status fdc_project_latent_kv(const fdc_layout* lay, int layer, const void* x
   a.A = x, a.B = A_cat_t, a.C = k_cache, a.C2 = v_cache;
   a.lda = lay->d_model, a.ldb = lay->d_model, a.ldc = 0;
   a.v_only = k_cache == nullptr;
-  a.cache_fp8 = lay->dtype == FDC_FP8;
+  a.cache_fp8 = lay->dtype == FDC_FP8, a.cache_fp4 = lay->dtype == FDC_FP4;
   a.M = T, a.N = a.v_only ? a.RV : a.RK + a.RV, a.K = lay->d_model;
   a.mode = kProject;
   a.tok_batch = tok_batch, a.tok_pos = tok_pos, a.fault = status;
@@ -1385,7 +1402,7 @@ fdc_status fdc_project_and_absorb_query(const fdc_layout* lay, int layer, const 
   p.A = x, p.B = A_cat_t, p.C = k_cache, p.C2 = v_cache;
   p.lda = lay->d_model, p.ldb = lay->d_model, p.ldc = 0;
   p.v_only = k_cache == nullptr;
-  p.cache_fp8 = lay->dtype == FDC_FP8;
+  p.cache_fp8 = lay->dtype == FDC_FP8, p.cache_fp4 = lay->dtype == FDC_FP4;
   p.M = T, p.N = p.v_only ? p.RV : p.RK + p.RV, p.K = lay->d_model;
   p.mode = kProject;
   p.tok_batch = tok_batch, p.tok_pos = tok_pos, p.fault = status;
@@ -1501,7 +1518,7 @@ fdc_status fdc_rope_compress_keys(const fdc_layout* lay, int layer, const void* 
   if (s != FDC_OK) return s;
   if (!tok_batch) FDC_FAIL(FDC_INVALID_ARG, "fdc_rope_compress_keys: tok_batch is NULL");
   a.tok_batch = tok_batch;
-  a.cache_fp8 = lay->dtype == FDC_FP8;
+  a.cache_fp8 = lay->dtype == FDC_FP8, a.cache_fp4 = lay->dtype == FDC_FP4;
   const dim3 grid((T + kRopeRows - 1) / kRopeRows, (lay->H + kRopeHeads - 1) / kRopeHeads);
   hipLaunchKernelGGL((rope_compress_kernel<uint16_t, true>), grid, dim3(256), 0, static_cast<hipStream_t>(stream), a);
   FDC_HIP_CHECK(hipGetLastError());

@@ -77,7 +77,7 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
   if (d_head < 16 || d_head > 128 || d_head % 16 != 0)
     FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_head %d must be a multiple of 16 in [16, 128]", d_head);
   if (d_model % 8 != 0) FDC_FAIL(FDC_BAD_SHAPE, "fdc_layout_create: d_model %d must be a multiple of 8", d_model);
-  if (dtype != FDC_BF16 && dtype != FDC_F32 && dtype != FDC_FP8)
+  if (dtype != FDC_BF16 && dtype != FDC_F32 && dtype != FDC_FP8 && dtype != FDC_FP4)
     FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_layout_create: dtype %d", (int)dtype);
   const size_t n = (size_t)n_layers * n_heads;
   for (size_t i = 0; i < n; ++i) {
@@ -91,7 +91,7 @@ fdc_status fdc_layout_create(int n_layers, int n_heads, int d_model, int d_head,
   fdc_layout* lay = holder.get();
   lay->L = n_layers, lay->H = n_heads, lay->d_model = d_model, lay->d_head = d_head;
   lay->max_batch = max_batch, lay->max_seq = max_seq, lay->dtype = dtype;
-  lay->elem_size = dtype == FDC_BF16 ? 2 : (dtype == FDC_FP8 ? 1 : 4);
+  lay->elem_bits = dtype == FDC_BF16 ? 16 : (dtype == FDC_FP8 ? 8 : (dtype == FDC_FP4 ? 4 : 32));
   lay->rk.assign(rk, rk + n);
   lay->rv.assign(rv, rv + n);
   lay->koff.resize(n), lay->voff.resize(n);
@@ -137,8 +137,8 @@ fdc_status fdc_layout_tables(const fdc_layout* lay, int64_t* koff, int64_t* voff
   if (koff_r) std::copy(lay->koff_r.begin(), lay->koff_r.end(), koff_r);
   if (voff_r) std::copy(lay->voff_r.begin(), lay->voff_r.end(), voff_r);
   for (int l = 0; l < lay->L; ++l) {
-    if (k_bytes) k_bytes[l] = lay->k_elems[l] * lay->elem_size;
-    if (v_bytes) v_bytes[l] = lay->v_elems[l] * lay->elem_size;
+    if (k_bytes) k_bytes[l] = lay->k_elems[l] * lay->elem_bits / 8;   // ranks are multiples of 16: whole bytes
+    if (v_bytes) v_bytes[l] = lay->v_elems[l] * lay->elem_bits / 8;
   }
   return FDC_OK;
 }

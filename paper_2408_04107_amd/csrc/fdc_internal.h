@@ -99,6 +99,11 @@ struct DecUnit {
   int32_t rv;
 };
 
+// Cache element of an E2M1 layout: a byte holds two codes, so buffers are addressed in bytes = elements / 2.
+struct fp4_t {
+  uint8_t pair;
+};
+
 // Tokens of a K'/V' block the prefill kernel stages at a time; a page holds a whole number of them.
 constexpr int kPrefillBlockTokens = 128;
 
@@ -149,7 +154,7 @@ struct fdc_layout {
   int L, H, d_model, d_head, max_batch, max_seq;
   int G = 1;  // query heads per key/value head
   fdc_dtype dtype;
-  int elem_size;
+  int elem_bits;   // bits per cached element
   std::vector<int32_t> rk, rv;          // [L*H]
   std::vector<int32_t> koff_r, voff_r;  // [L*(H+1)]
   std::vector<int64_t> koff, voff;      // [L*H]

@@ -24,6 +24,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "fdc_internal.h"
 
@@ -159,10 +160,14 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   const int tid = threadIdx.x, lane = tid % 64;
   const int wave = __builtin_amdgcn_readfirstlane(tid / 64);   // known uniform: conditions on it become scalar branches
   const int ln = lane % 16, lg = lane / 16;
-  const TC* kbase = kc + t.k_elem;
-  const TC* vbase = vc + t.v_elem;
-  constexpr int ES = (int)sizeof(TC);   // bytes per cached element
-  constexpr int EPC = 16 / ES;          // elements per 16-byte chunk of the cache
+  // cache element: bf16 (TC = uint16_t), an E4M3 code (uint8_t) or an E2M1 code (fp4_t: two per byte). A staging
+  // chunk is what a lane loads at once: 16 bytes, 8 for E2M1 (sixteen codes, so that the narrowest row is a chunk)
+  constexpr bool kFp4 = sizeof(TC) == 1 && !std::is_same<TC, uint8_t>::value;
+  constexpr int BITS = kFp4 ? 4 : 8 * (int)sizeof(TC);
+  constexpr int CB = kFp4 ? 8 : 16;     // bytes per chunk
+  constexpr int EPC = CB * 8 / BITS;    // elements per chunk
+  const uint8_t* kbase = reinterpret_cast<const uint8_t*>(kc) + t.k_elem * BITS / 8;
+  const uint8_t* vbase = reinterpret_cast<const uint8_t*>(vc) + t.v_elem * BITS / 8;
 
   // zero the rank padding of both K' tiles once: staging never writes those columns
   if (RKP != rk) {
@@ -184,9 +189,9 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
   const int k_sweeps = (BCB + k_rps - 1) / k_rps, v_sweeps = (BCB + v_rps - 1) / v_rps;
   // the unit's K' and V' rows [0, kv_len) as raw buffers (at most 131072 * 256 bytes each)
   const __amdgpu_buffer_rsrc_t k_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(kbase), 0, t.kv_len * rk * ES, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(kbase), 0, t.kv_len * rk * BITS / 8, 0x00020000);
   const __amdgpu_buffer_rsrc_t v_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(vbase), 0, t.kv_len * rv * ES, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(vbase), 0, t.kv_len * rv * BITS / 8, 0x00020000);
   // per sweep: byte offset of the lane's chunk in block 0 (out of range when the lane has no row)
   // and its LDS element offset
   uint32_t k_goff[kSweeps], v_goff[kSweeps];
@@ -197,8 +202,8 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     const int kr = k_row + i * k_rps, vr = v_row + i * v_rps;
     k_on[i] = k_row < k_rps && kr < BCB;
     v_on[i] = v_row < v_rps && vr < BCB;
-    k_goff[i] = k_on[i] ? (uint32_t)(kr * rk * ES + k_cc * 16) : 0x80000000u;
-    v_goff[i] = v_on[i] ? (uint32_t)(vr * rv * ES + v_cc * 16) : 0x80000000u;
+    k_goff[i] = k_on[i] ? (uint32_t)(kr * rk * BITS / 8 + k_cc * CB) : 0x80000000u;
+    v_goff[i] = v_on[i] ? (uint32_t)(vr * rv * BITS / 8 + v_cc * CB) : 0x80000000u;
     k_loff[i] = kr * KROW + k_cc * EPC;
     v_loff[i] = vr * VROW + v_cc * EPC;
   }
@@ -236,7 +241,7 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     const int wave_last_pos = t.pos0 + min(wrow0 + kRowsPerWave, t.rows) - 1;
 
     // register staging of the next block
-    u32x4 kst[kSweeps], vst[kSweeps];
+    u32x4 kst[kSweeps], vst[kSweeps];   // E2M1: the chunk is the lower half
     auto fetch = [&](int c0) {  // rows past kv_len and lanes without a row read zeros through the range check
       __amdgpu_buffer_rsrc_t kr = k_rsrc, vr = v_rsrc;
       int rel = c0;
@@ -246,19 +251,48 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
         const int pi = c0 / t.page_tokens, start = pi * t.page_tokens;
         const int64_t pg = page_table[t.page_first + pi];
         const int rows = min(t.page_tokens, t.kv_len - start);
-        kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(kbase + pg * page_stride_k), 0, rows * rk * ES, 0x00020000);
-        vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<TC*>(vbase + pg * page_stride_v), 0, rows * rv * ES, 0x00020000);
+        kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(kbase + pg * page_stride_k * BITS / 8), 0, rows * rk * BITS / 8, 0x00020000);
+        vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(vbase + pg * page_stride_v * BITS / 8), 0, rows * rv * BITS / 8, 0x00020000);
         rel = c0 - start;
       }
 #pragma unroll
       for (int i = 0; i < kSweeps; ++i) {
-        if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, (int)(k_goff[i] + (uint32_t)(rel * rk * ES)), 0, 0);
-        if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, (int)(v_goff[i] + (uint32_t)(rel * rv * ES)), 0, 0);
+        const int ko = (int)(k_goff[i] + (uint32_t)(rel * rk * BITS / 8)), vo = (int)(v_goff[i] + (uint32_t)(rel * rv * BITS / 8));
+        if constexpr (kFp4) {
+          if (i < k_sweeps) {
+            const u32x2 c = __builtin_amdgcn_raw_buffer_load_b64(kr, ko, 0, 0);
+            kst[i][0] = c[0], kst[i][1] = c[1];
+          }
+          if (i < v_sweeps) {
+            const u32x2 c = __builtin_amdgcn_raw_buffer_load_b64(vr, vo, 0, 0);
+            vst[i][0] = c[0], vst[i][1] = c[1];
+          }
+        } else {
+          if (i < k_sweeps) kst[i] = __builtin_amdgcn_raw_buffer_load_b128(kr, ko, 0, 0);
+          if (i < v_sweeps) vst[i] = __builtin_amdgcn_raw_buffer_load_b128(vr, vo, 0, 0);
+        }
       }
     };
     auto put = [&](uint16_t* dst, const u32x4& chunk) {   // one 16-byte chunk of the cache -> bf16 in LDS
-      if constexpr (ES == 2) {
+      if constexpr (BITS == 16) {
         *reinterpret_cast<u32x4*>(dst) = chunk;
+      } else if constexpr (kFp4) {   // sixteen codes in two words -> sixteen bf16 (which holds every E2M1 value exactly)
+        u32x4 lo, hi;
+#pragma unroll
+        for (int w = 0; w < 2; ++w)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            f32x2 p;
+            switch (b) {   // the byte select is an immediate
+              case 0: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 0); break;
+              case 1: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 1); break;
+              case 2: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 2); break;
+              default: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 3); break;
+            }
+            (w == 0 ? lo : hi)[b] = pack_bf16(p[0], p[1]);
+          }
+        *reinterpret_cast<u32x4*>(dst) = lo;
+        *reinterpret_cast<u32x4*>(dst + 8) = hi;
       } else {
         u32x4 lo, hi;
 #pragma unroll
@@ -466,6 +500,8 @@ fdc_status fdc_latent_attn_prefill(const fdc_layout* lay, const fdc_plan* plan, 
   };
   if (lay->dtype == FDC_FP8)
     go(prefill_kernel<uint8_t>, static_cast<const uint8_t*>(k_cache), static_cast<const uint8_t*>(v_cache));
+  else if (lay->dtype == FDC_FP4)
+    go(prefill_kernel<fp4_t>, static_cast<const fp4_t*>(k_cache), static_cast<const fp4_t*>(v_cache));
   else
     go(prefill_kernel<uint16_t>, static_cast<const uint16_t*>(k_cache), static_cast<const uint16_t*>(v_cache));
   FDC_HIP_CHECK(hipGetLastError());

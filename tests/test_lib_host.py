@@ -230,8 +230,12 @@ def test_e4m3_layout_has_the_bf16_layouts_offsets_at_one_byte_per_element():
     for key in ("koff", "voff", "koff_r", "voff_r"):
         assert np.array_equal(t8[key], t16[key]), key
     assert np.array_equal(2 * t8["k_bytes"], t16["k_bytes"]) and np.array_equal(2 * t8["v_bytes"], t16["v_bytes"])
+    t4 = fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, fdc.FDC_FP4).tables()      # E2M1: half a byte per element
+    for key in ("koff", "voff", "koff_r", "voff_r"):
+        assert np.array_equal(t4[key], t16[key]), key
+    assert np.array_equal(4 * t4["k_bytes"], t16["k_bytes"]) and np.array_equal(4 * t4["v_bytes"], t16["v_bytes"])
     with pytest.raises(fdc.FdcError):
-        fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, 3)     # no such dtype
+        fdc.Layout(1, 4, 256, 128, rk, rv, 3, 100, 4)     # no such dtype
 
 
 def test_select_ranks_bit_exact_with_oracle():
