@@ -772,6 +772,8 @@ def main():
     ap.add_argument("--no-device-planner", action="store_true")
     ap.add_argument("--no-serving-loop", action="store_true")
     ap.add_argument("--no-single-layer", action="store_true", help="skip the uniform-rank and long-context side objects")
+    ap.add_argument("--only-single-layer", default=None, choices=["c2_uniform_decode", "c4_long_decode"],
+                    help="run just this single-layer side measurement and print its object (for counter runs)")
     ap.add_argument("--oracle-legs", default=None, help=argparse.SUPPRESS)   # child process of cpu_baseline
     args = ap.parse_args()
     if args.oracle_legs:
@@ -801,6 +803,10 @@ def main():
         dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
+    if args.only_single_layer:
+        print(json.dumps({"side": args.only_single_layer,
+                          **run_single_layer_decode(fdc, gen, args.only_single_layer, iters=max(args.steps, 4))}))
+        return
     res, state = run_decode_workload(fdc, gen, wl, args.steps, args.warmup, args)
     line = {
         "metric": "latent-KV decode step: achieved HBM GB/s (algorithmic bytes of the whole step / step time)",
