@@ -28,7 +28,7 @@ namespace fdc {
 // measured within 2 % of each other).
 constexpr int kDecodeLoads = 8;
 constexpr int kTokLanes = 64 * kDecodeLoads;
-constexpr int kWavesPerBlock = 4;
+constexpr int kWavesPerBlock = kWorkersPerGroup;
 constexpr int kLdsFloatsPerWave = kTokLanes > 256 ? kTokLanes : 256;  // a block of one-lane rows (E4M3, rank 16) has kTokLanes tokens
 
 // Tokens per block: kDecodeLoads loads of the wider operand, at least one load of the narrower.

@@ -39,7 +39,7 @@ typedef uint32_t gq_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t gq_u32x2 __attribute__((ext_vector_type(2)));
 typedef short gq_s16x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGqaWaves = 4;             // workers (wavefronts) per workgroup
+constexpr int kGqaWaves = kWorkersPerGroup;  // workers (wavefronts) per workgroup
 constexpr int kGqaLdsElems = 4096;       // bf16 elements of V' staging per wave (8 KiB)
 constexpr float kGqaLog2e = 1.4426950408889634f;
 constexpr float kGqaRaise = 6.0f;        // lazy softmax reference: p <= 2^6 between raises

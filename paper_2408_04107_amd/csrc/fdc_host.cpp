@@ -1,6 +1,7 @@
 // Host side of libfdc: error text, the ragged cache layout and the work partitioner.
 // Integer arithmetic only; no GPU is needed for anything in this file.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <new>
@@ -401,10 +402,29 @@ static fdc_status plan_decode_impl(const char* fn, const fdc_layout* lay, int la
   for (size_t i = 0; i < n; ++i) wtiles[i] = tiles[p->worker_items[i]];
   if (!units.empty()) std::memcpy(p->image.data() + p->off_units, units.data(), units.size() * sizeof(DecUnit));
   DecWorker* heads = reinterpret_cast<DecWorker*>(p->image.data() + p->off_worker_ptr);
+  // Launch slot of each worker. The tile kernels run four workers per workgroup and the hardware deals
+  // workgroups to the eight XCDs in turn (workgroup i -> XCD i % 8). Measured on MI355X, the even XCDs stream
+  // 5 to 10 % faster than the odd ones whatever the workload, and what list scheduling leaves between
+  // workers (whole granules: a few percent of the mean) is of that size. So the heavier half of the workers
+  // takes the slots of the even XCDs. In load order inside each half, a compute unit's four workgroups
+  // (32 workgroups of an XCD apart) come from the four quarters of it. The schedule itself is untouched.
+  // (Grouped queries keep the plain order: the same ordering made that kernel 2.5 % slower, its time per tile
+  // follows the planner's cost less closely.)
+  std::vector<int> slot_of(W);
+  for (int w = 0; w < W; ++w) slot_of[w] = w;
+  if (p->G == 1 && W % (2 * kXcds * kWorkersPerGroup) == 0) {
+    std::vector<int> by_load(W);
+    for (int w = 0; w < W; ++w) by_load[w] = w;
+    std::stable_sort(by_load.begin(), by_load.end(),
+                     [&](int a, int b) { return p->worker_load[a] > p->worker_load[b]; });
+    int next[2] = {0, W / 2};   // index into by_load of the next worker of the heavy / light half
+    for (int s = 0; s < W; ++s) slot_of[by_load[next[((s / kWorkersPerGroup) % kXcds) % 2]++]] = s;
+  }
   for (int w = 0; w < W; ++w) {
-    heads[w].begin = p->worker_ptr[w];
-    heads[w].count = p->worker_ptr[w + 1] - p->worker_ptr[w];
-    if (heads[w].count > 0) heads[w].first = wtiles[heads[w].begin];
+    DecWorker& hd = heads[slot_of[w]];
+    hd.begin = p->worker_ptr[w];
+    hd.count = p->worker_ptr[w + 1] - p->worker_ptr[w];
+    if (hd.count > 0) hd.first = wtiles[hd.begin];
   }
   p->off_partials = (p->image.size() + 255) / 256 * 256;
   p->partial_bytes = std::max<size_t>(n * p->G, 1) * kPartialStride * sizeof(float);

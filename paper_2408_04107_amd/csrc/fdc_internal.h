@@ -81,6 +81,10 @@ __device__ inline int32_t dec_tile_len(const DecTile& t, const int32_t* planned_
 #endif
 static_assert(sizeof(DecTile) == 48, "DecTile layout");
 
+// Launch geometry the host planner relies on when it orders the worker headers by launch slot.
+constexpr int kXcds = 8;              // accelerator dies (XCDs) of the GPU; workgroups are dealt to them in turn
+constexpr int kWorkersPerGroup = 4;   // wavefronts (workers) per workgroup of both decode tile kernels
+
 // What a decode worker (one wavefront) reads first: how many tiles it has, where the rest of them
 // are in the worker-ordered tile array, and its first tile inline, so that the cache stream starts
 // after a single dependent load. 64 bytes.
