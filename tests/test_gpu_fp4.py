@@ -308,3 +308,136 @@ def test_post_rope_keys_and_one_launch_prologue_store_e2m1_codes():
     fdc.fdc_project_and_absorb_query(lay4, 0, x, tb2, tp2, A, k2, v2, q, Bk, q2, fdc.FDC_F32)
     torch.cuda.synchronize()
     assert torch.equal(k1, k2) and torch.equal(v1, v2) and torch.equal(q1, q2) and bool(k1.any())
+
+
+def build_paged_cache(rk, rv, seq, P, bt, n_pages, rng, k_gain=2.0, v_gain=2.5):
+    """Packed code buffers of a paged layout (pages scattered by the block table) and the decoded rows per unit."""
+    from oracle import layout as ol
+    H, RK, RV = len(rk), sum(rk), sum(rv)
+    kcodes = np.zeros(n_pages * P * RK, dtype=np.uint8)
+    vcodes = np.zeros(n_pages * P * RV, dtype=np.uint8)
+    Ks, Vs = {}, {}
+    for b, n in enumerate(seq):
+        for h in range(H):
+            kq = fp4.quantise_latent(gen.direct_latent(n, rk[h], 32.0, rng) * k_gain)
+            vq = fp4.quantise_latent(gen.direct_latent(n, rv[h], 32.0, rng) * v_gain)
+            Ks[b, h], Vs[b, h] = fp4.e2m1_decode(kq), fp4.e2m1_decode(vq)
+            for t in range(n):
+                k0 = ol.paged_element_index(rk, P, bt[b], h, t, 0)
+                v0 = ol.paged_element_index(rv, P, bt[b], h, t, 0)
+                kcodes[k0:k0 + rk[h]], vcodes[v0:v0 + rv[h]] = kq[t], vq[t]
+    pack = lambda c: torch.from_numpy(fp4.pack_rows(c.reshape(-1, 2)).ravel()).cuda()
+    return pack(kcodes), pack(vcodes), Ks, Vs
+
+
+@pytest.mark.parametrize("P,W,granule", [(128, 19, 64), (64, 300, 32)])
+def test_paged_decode_on_e2m1_codes(P, W, granule):
+    """Decode over a paged E2M1 cache: tiles are cut at page boundaries and every address is in half bytes."""
+    from tests.test_gpu_paged import build_block_table
+    rk, rv = [16, 64, 128, 48], [32, 128, 16, 80]
+    H, d_h = len(rk), 128
+    seq = [5, 300, 0, 129, 64]
+    say(f"paged decode P={P} W={W} granule={granule}")
+    rng = gen.make_rng(123 + P)
+    bt, n_pages = build_block_table(seq, P, rng)
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], n_pages, P, fdc.FDC_FP4)
+    RK, RV = sum(rk), sum(rv)
+    kc, vc, Ks, Vs = build_paged_cache(rk, rv, seq, P, bt, n_pages, rng)
+    B = len(seq)
+    q_lat = torch.from_numpy((rng.standard_normal((B, RK)) * 0.5).astype(np.float32)).cuda()
+    o_lat = torch.full((B, RV), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.granule = W, granule
+    plan = fdc.fdc_plan_decode_paged(lay, 0, seq, bt, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    out, q64 = o_lat.cpu().numpy().astype(np.float64), q_lat.cpu().numpy().astype(np.float64)
+    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    for b, n in enumerate(seq):
+        for h in range(H):
+            got = out[b, vo[h]:vo[h + 1]]
+            if n == 0:
+                assert not got.any()
+                continue
+            ref = oa.latent_attn_decode(q64[b, ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale)
+            assert_close(got, ref, f"paged b={b} h={h} n={n}", rel_l2_tol=2e-4)
+    say(f"  tiles={plan.export()['n_items']}")
+
+
+def test_paged_prefill_on_e2m1_codes():
+    """Causal prefill over a paged E2M1 cache, chunked prompts, lengths that end inside a page."""
+    from tests.test_gpu_paged import build_block_table
+    rk, rv = [16, 48, 128, 64], [64, 16, 128, 32]
+    H, d_h, P = len(rk), 128, 256
+    kv = [1, 129, 700, 1300, 333]
+    ql = [1, 129, 300, 1300, 0]
+    rng = gen.make_rng(77)
+    bt, n_pages = build_block_table(kv, P, rng)
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], n_pages, P, fdc.FDC_FP4)
+    RK, RV = sum(rk), sum(rv)
+    kc, vc, Ks, Vs = build_paged_cache(rk, rv, kv, P, bt, n_pages, rng)
+    T = int(np.sum(ql))
+    q_lat = torch.from_numpy(gen.round_to_bf16(rng.standard_normal((T, RK)) * 0.5)).to(BF).cuda()
+    o_lat = torch.full((T, RV), float("nan"), dtype=BF, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.br_base, pp.br_cap, pp.cost_mode = 40, 256, 256, 1
+    plan = fdc.fdc_plan_prefill_paged(lay, 0, ql, kv, bt, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_prefill(lay, plan, q_lat, kc, vc, scale, True, o_lat, ws)
+    torch.cuda.synchronize()
+    out, q64 = o_lat.to(torch.float64).cpu().numpy(), q_lat.to(torch.float64).cpu().numpy()
+    assert np.all(np.isfinite(out))
+    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    row0 = np.concatenate([[0], np.cumsum(ql)])
+    got_all, ref_all = [], []
+    for b in range(len(kv)):
+        if ql[b] == 0:
+            continue
+        for h in range(H):
+            ref = oa.latent_attn_prefill(q64[row0[b]:row0[b + 1], ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale, True)
+            got = out[row0[b]:row0[b + 1], vo[h]:vo[h + 1]]
+            assert_close(got, ref, f"b={b} h={h}", max_abs_tol=3e-2)     # values reach +-6
+            got_all.append(got.ravel()), ref_all.append(ref.ravel())
+    ma, rl = assert_close(np.concatenate(got_all), np.concatenate(ref_all), "all", max_abs_tol=3e-2)
+    say(f"  paged prefill tasks={plan.export()['n_items']} max_abs={ma:.2e} rel_l2={rl:.2e}")
+
+
+def test_decode_on_e2m1_codes_at_config3_size_sampled_units():
+    """Layer 0 of the adaptive-rank decode config (batch 16, context 8192, 32 heads) with an E2M1 cache, in the
+    launch configuration bench.py times (fdc_suggest_workers(4)): random bytes on the device (every byte is two
+    valid codes), the oracle on ~60 sampled (sequence, head) units including the narrowest and the widest head."""
+    wl = gen.CONFIGS["c3_adaptive_decode"]
+    r = wl.ranks()[0].tolist()
+    H, B, S, d_h = wl.n_heads, wl.batch, wl.context, wl.d_head
+    W = fdc.fdc_suggest_workers(4)
+    say(f"config 3 layer 0, E2M1: B={B} S={S} W={W}")
+    lay = fdc.Layout(1, H, wl.d_model, d_h, [r], [r], B, S, fdc.FDC_FP4)
+    R = sum(r)
+    tg = torch.Generator(device="cuda:0").manual_seed(4)
+    mk = lambda: torch.randint(0, 256, (B * S * R // 2,), generator=tg, device="cuda:0", dtype=torch.uint8)
+    kc, vc = mk(), mk()
+    rng = gen.make_rng(9)
+    q_lat = torch.from_numpy((rng.standard_normal((B, R)) * 0.3).astype(np.float32)).cuda()     # codes reach +-6
+    o_lat = torch.full((B, R), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = W
+    plan = fdc.fdc_plan_decode(lay, 0, [S] * B, pp)
+    ws = workspace_for(plan)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
+    torch.cuda.synchronize()
+    assert not torch.isnan(o_lat).any()
+    units = {(int(b), int(h)) for b, h in zip(rng.integers(0, B, 60), rng.integers(0, H, 60))}
+    units |= {(0, int(np.argmax(r))), (B - 1, int(np.argmin(r)))}
+    off = np.concatenate([[0], np.cumsum(r)])
+    out, q64 = o_lat.cpu().numpy().astype(np.float64), q_lat.cpu().numpy().astype(np.float64)
+    for b, h in sorted(units):
+        e0 = b * S * R + S * off[h]                       # element offset of the unit, even
+        K = fp4.e2m1_decode(fp4.unpack_rows(kc[e0 // 2:(e0 + S * r[h]) // 2].cpu().numpy())).reshape(S, r[h])
+        V = fp4.e2m1_decode(fp4.unpack_rows(vc[e0 // 2:(e0 + S * r[h]) // 2].cpu().numpy())).reshape(S, r[h])
+        ref = oa.latent_attn_decode(q64[b, off[h]:off[h + 1]], K, V, scale)
+        assert_close(out[b, off[h]:off[h + 1]], ref, f"b={b} h={h} r={r[h]}")
+    say(f"  tiles={plan.export()['n_items']} units checked={len(units)}")
