@@ -38,9 +38,12 @@
  *    a buffer holds elems / 2 bytes and element offsets are halved to address it.
  *    As for FDC_FP8 no scales are stored; here a scale per (head, latent column)
  *    folds into the factors. Supported by fdc_project_latent_kv,
- *    fdc_project_and_absorb_query, fdc_rope_compress_keys, multi-head
- *    fdc_latent_attn_decode(_at, _static) and fdc_latent_attn_prefill; grouped
- *    decode attention over an FDC_FP4 cache is FDC_UNSUPPORTED_DTYPE.
+ *    fdc_project_and_absorb_query, fdc_rope_compress_keys,
+ *    fdc_latent_attn_decode(_at, _static) and fdc_latent_attn_prefill. Grouped
+ *    decode attention streams a tile once for the whole group over FDC_BF16 and
+ *    FDC_FP8 caches; over FDC_FP4 and FDC_F32 caches it runs the multi-head
+ *    kernel once per query head of the group (same results, g times the cache
+ *    traffic).
  *  - fdc_layout and fdc_plan are host objects, immutable after creation
  *    (except that fdc_plan_download fills in the host tables of a plan whose
  *    schedule was computed on the device), destroyed by the matching call.

@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
     const DecWorker* __restrict__ workers, const DecTile* __restrict__ wtiles, const float* __restrict__ q_lat,
     const T* __restrict__ kc, const T* __restrict__ vc, float scale_log2, float* __restrict__ o_lat,
     float* __restrict__ partials, int n_workers, const int32_t* __restrict__ planned_len,
-    const int32_t* __restrict__ seq_len) {
+    const int32_t* __restrict__ seq_len, const int group_j) {
   __shared__ float lds_all[kWavesPerBlock][kLdsFloatsPerWave];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
   const int lane = threadIdx.x % 64;
@@ -319,6 +319,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
   constexpr int BASE = Elem<T>::EL == 16 ? 0 : (Elem<T>::EL == 8 ? 1 : 2);  // smallest lane class (log2 lanes per row) of this element type
   for (int i = 0;;) {
     td.len = dec_tile_len(td, planned_len, seq_len);
+    // query head group_j of the tile's group (0 for multi-head plans): its q', its o', its partial slot
+    td.q_elem += group_j * (td.rk_rv & 0xffff), td.o_elem += group_j * (td.rk_rv >> 16);
+    if (td.slot >= 0) td.slot += group_j * td.slot_stride;
     const int ck = lane_class<T>(td.rk_rv & 0xffff) - BASE, cvv = lane_class<T>(td.rk_rv >> 16) - BASE;
 #define FDC_CASE(a, b)                                                                                      \
   case (a)*4 + (b):                                                                                         \
@@ -567,16 +570,23 @@ static fdc_status decode_impl(const fdc_layout* lay, const fdc_plan* plan, const
   const int W = plan->n_workers;
   const dim3 grid((W + kWavesPerBlock - 1) / kWavesPerBlock), block(kWavesPerBlock * 64);
   const float scale_log2 = scale * kLog2e;
-  if (plan->G > 1 && (lay->dtype == FDC_F32 || lay->dtype == FDC_FP4))
-    FDC_FAIL(FDC_UNSUPPORTED_DTYPE, "fdc_latent_attn_decode: grouped queries need a bf16 or E4M3 layout");
+  // Grouped queries over a bf16 or E4M3 cache stream a tile once for the whole group (matrix-core kernel).
+  // The other element types have no such kernel: the multi-head kernel runs once per query head of the
+  // group, each pass over the same tiles with that head's q', o' and partial slots (g times the traffic).
+  const bool per_head_passes = plan->G > 1 && (lay->dtype == FDC_F32 || lay->dtype == FDC_FP4);
+  const int n_pass = per_head_passes ? plan->G : 1;
   if (plan->on_device || !plan->item_b.empty()) {   // a device plan's tile count is not known here: empty workers return at once
     // a profiling request attaches its two events to the tile kernel's own dispatch (its begin and its end)
-#define FDC_LAUNCH_TILES(kern, ...)                                                          \
-  do {                                                                                       \
-    if (ev0) hipExtLaunchKernelGGL(kern, grid, block, 0, st, ev0, ev1, 0, __VA_ARGS__);      \
-    else hipLaunchKernelGGL(kern, grid, block, 0, st, __VA_ARGS__);                          \
+    // (with several passes: the start event on the first pass, the stop event on the last)
+#define FDC_LAUNCH_TILES(kern, ...)                                                                              \
+  do {                                                                                                           \
+    for (int j = 0; j < n_pass; ++j) {                                                                           \
+      hipEvent_t e0 = j == 0 ? ev0 : nullptr, e1 = j == n_pass - 1 ? ev1 : nullptr;                              \
+      if (e0 || e1) hipExtLaunchKernelGGL(kern, grid, block, 0, st, e0, e1, 0, __VA_ARGS__, j);                  \
+      else hipLaunchKernelGGL(kern, grid, block, 0, st, __VA_ARGS__, j);                                         \
+    }                                                                                                            \
   } while (0)
-    if (plan->G > 1) {
+    if (plan->G > 1 && !per_head_passes) {
       fdc_status gs = launch_decode_gqa(heads, wtiles, static_cast<const float*>(q_lat), k_cache, v_cache,
                                         lay->dtype == FDC_FP8, scale, static_cast<float*>(o_lat), partials, W, planned, lens,
                                         ev0, ev1, st);

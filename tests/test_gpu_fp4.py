@@ -192,21 +192,45 @@ def test_decode_attention_on_e2m1_codes(W, granule, min_split):
     assert torch.equal(o2, o_lat) and torch.equal(o3, o_lat)
 
 
-def test_grouped_decode_over_e2m1_codes_is_refused():
-    lay = fdc.Layout(1, 2, 256, 128, [[16, 64]], [[32, 16]], 2, 128, fdc.FDC_FP4, q_per_kv=4)
+@pytest.mark.parametrize("g,W", [(2, 5), (4, 300)])
+def test_grouped_decode_over_e2m1_codes(g, W):
+    """Grouped queries over an E2M1 cache: the multi-head kernel runs once per query head of the group, each pass
+    with that head's q', o' and partial slots; split units, unsplit units, an empty sequence."""
+    from oracle import gqa as og
+    rk, rv = [16, 64, 128, 48], [32, 16, 80, 128]
+    H, d_h = len(rk), 128
+    seq = [100, 0, 1300, 64]
+    B, S = len(seq), max(seq)
+    say(f"grouped decode g={g} W={W}")
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], B, S, fdc.FDC_FP4, q_per_kv=g)
+    RK, RV = sum(rk), sum(rv)
+    rng = gen.make_rng(31 * g + W)
+    kc, vc, Ks, Vs = build_cache(rk, rv, seq, rng)
+    q_lat = torch.from_numpy((rng.standard_normal((B, g * RK)) * 0.7).astype(np.float32)).cuda()
+    o_lat = torch.full((B, g * RV), float("nan"), dtype=torch.float32, device="cuda:0")
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers = 8
-    plan = fdc.fdc_plan_decode(lay, 0, [100, 128], pp)
+    pp.n_workers = W
+    plan = fdc.fdc_plan_decode(lay, 0, seq, pp)
     ws = workspace_for(plan)
-    kc = torch.zeros(2 * 128 * 80 // 2, dtype=torch.uint8, device="cuda:0")
-    vc = torch.zeros(2 * 128 * 48 // 2, dtype=torch.uint8, device="cuda:0")
-    q = torch.zeros(2, 4 * 80, device="cuda:0")
-    o = torch.full((2, 4 * 48), 5.0, device="cuda:0")
-    with pytest.raises(fdc.FdcError) as e:
-        fdc.fdc_latent_attn_decode(lay, plan, q, kc, vc, 0.1, o, ws)
-    assert e.value.status == -7
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, scale, o_lat, ws)
     torch.cuda.synchronize()
-    assert bool((o == 5.0).all())
+    out, q64 = o_lat.cpu().numpy().astype(np.float64), q_lat.cpu().numpy().astype(np.float64)
+    qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
+    for b, n in enumerate(seq):
+        for hq in range(H * g):
+            h = hq // g
+            got = out[b, oo[hq]:oo[hq + 1]]
+            if n == 0:
+                assert not got.any()
+                continue
+            ref = oa.latent_attn_decode(q64[b, qo[hq]:qo[hq + 1]], Ks[b, h], Vs[b, h], scale)
+            assert_close(got, ref, f"b={b} hq={hq} n={n}", rel_l2_tol=2e-4)
+    o2 = torch.full_like(o_lat, float("nan"))
+    fdc.fdc_latent_attn_decode_static(lay, plan, q_lat, kc, vc, scale, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o2, o_lat)
+    say(f"  tiles={plan.export()['n_items']}")
 
 
 @pytest.mark.parametrize("W,br,chunked", [(5, 64, False), (40, 256, True), (256, 512, False)])

@@ -137,17 +137,45 @@ def test_gqa_decode_bench_shape_sampled_units():
     say(f"  W={W} ranks={r} tiles={n} max_abs={ma:.2e} rel_l2={rl:.2e}")
 
 
-def test_gqa_fp32_layout_is_rejected_for_decode():
-    lay = fdc.Layout(1, 2, 64, 64, [[16, 32]], [[16, 32]], 1, 8, fdc.FDC_F32, q_per_kv=2)
+def test_gqa_decode_on_an_fp32_layout_runs_one_pass_per_query_head():
+    """fp32 caches have no grouped tile kernel: the multi-head kernel runs once per query head of the group.
+    Plain fp32 arithmetic, so the result sits at fp32 rounding distance from the oracle."""
+    rk, rv, g = [16, 32, 64], [32, 16, 48], 3
+    seq = [700, 0, 65]
+    H, d_h, B, S = len(rk), 64, len(seq), max(seq)
+    lay = fdc.Layout(1, H, 64, d_h, [rk], [rv], B, S, fdc.FDC_F32, q_per_kv=g)
     cache = Cache(lay)
+    rng = gen.make_rng(77)
+    koff, voff = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    kb, vb = np.zeros(cache.k.numel(), np.float32), np.zeros(cache.v.numel(), np.float32)
+    Ks, Vs = {}, {}
+    for b, n in enumerate(seq):
+        for h in range(H):
+            Ks[b, h] = gen.direct_latent(n, rk[h], 32.0, rng).astype(np.float32)
+            Vs[b, h] = gen.direct_latent(n, rv[h], 32.0, rng).astype(np.float32)
+            k0, v0 = b * S * cache.RK + S * koff[h], b * S * cache.RV + S * voff[h]
+            kb[k0:k0 + n * rk[h]], vb[v0:v0 + n * rv[h]] = Ks[b, h].ravel(), Vs[b, h].ravel()
+    cache.k.copy_(torch.from_numpy(kb)), cache.v.copy_(torch.from_numpy(vb))
+    q = torch.from_numpy(rng.standard_normal((B, g * cache.RK)).astype(np.float32)).cuda()
+    o = torch.full((B, g * cache.RV), float("nan"), device="cuda:0")
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers = 4
-    plan = fdc.fdc_plan_decode(lay, 0, [8], pp)
+    pp.n_workers = 11
+    plan = fdc.fdc_plan_decode(lay, 0, seq, pp)
     ws = workspace_for(plan)
-    q = torch.zeros(1, 2 * cache.RK, device="cuda:0")
-    o = torch.zeros(1, 2 * cache.RV, device="cuda:0")
-    with pytest.raises(fdc.FdcError):
-        fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, 0.1, o, ws)
+    scale = 1 / math.sqrt(d_h)
+    fdc.fdc_latent_attn_decode(lay, plan, q, cache.k, cache.v, scale, o, ws)
+    torch.cuda.synchronize()
+    out, q64 = o.cpu().numpy().astype(np.float64), q.cpu().numpy().astype(np.float64)
+    qo, oo = og.query_offsets(rk, g), og.query_offsets(rv, g)
+    for b, n in enumerate(seq):
+        for hq in range(H * g):
+            got = out[b, oo[hq]:oo[hq + 1]]
+            if n == 0:
+                assert not got.any()
+                continue
+            ref = oa.latent_attn_decode(q64[b, qo[hq]:qo[hq + 1]], Ks[b, hq // g].astype(np.float64),
+                                        Vs[b, hq // g].astype(np.float64), scale)
+            assert_close(got, ref, f"b={b} hq={hq}", rel_l2_tol=1e-5)
 
 
 @pytest.mark.parametrize("g,T", [(2, 5), (4, 300), (8, 70)])
