@@ -233,22 +233,23 @@ def test_grouped_decode_over_e2m1_codes(g, W):
     say(f"  tiles={plan.export()['n_items']}")
 
 
+@pytest.mark.parametrize("g", [1, 2])
 @pytest.mark.parametrize("W,br,chunked", [(5, 64, False), (40, 256, True), (256, 512, False)])
-def test_prefill_attention_on_e2m1_codes(W, br, chunked):
+def test_prefill_attention_on_e2m1_codes(W, br, chunked, g):
     """Causal prefill over E2M1 codes (whole and chunked prompts): the kernel widens the codes to bf16 while
     staging, which is exact, so the bf16 tolerance applies."""
     rk, rv = [16, 48, 128, 64, 32], [64, 16, 128, 32, 48]
     H, d_h = len(rk), 128
     kv = [1, 129, 700, 1300, 333]
     ql = [1, 129, 300, 1300, 0] if chunked else [1, 129, 700, 1300, 333]
-    say(f"prefill W={W} br={br} chunked={chunked}")
+    say(f"prefill W={W} br={br} chunked={chunked} g={g}")
     rng = gen.make_rng(7 * W + br)
     RK, RV = sum(rk), sum(rv)
-    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], len(kv), max(kv), fdc.FDC_FP4)
+    lay = fdc.Layout(1, H, 256, d_h, [rk], [rv], len(kv), max(kv), fdc.FDC_FP4, q_per_kv=g)
     kc, vc, Ks, Vs = build_cache(rk, rv, kv, rng)
     T = int(np.sum(ql))
-    q_lat = torch.from_numpy(gen.round_to_bf16(rng.standard_normal((T, RK)) * 0.5)).to(BF).cuda()
-    o_lat = torch.full((T, RV), float("nan"), dtype=BF, device="cuda:0")
+    q_lat = torch.from_numpy(gen.round_to_bf16(rng.standard_normal((T, g * RK)) * 0.5)).to(BF).cuda()
+    o_lat = torch.full((T, g * RV), float("nan"), dtype=BF, device="cuda:0")
     pp = fdc.fdc_plan_params_default()
     pp.n_workers, pp.br_base, pp.br_cap, pp.cost_mode = W, br, br, 1
     plan = fdc.fdc_plan_prefill(lay, 0, ql, kv, pp)
@@ -258,16 +259,18 @@ def test_prefill_attention_on_e2m1_codes(W, br, chunked):
     torch.cuda.synchronize()
     out, q64 = o_lat.to(torch.float64).cpu().numpy(), q_lat.to(torch.float64).cpu().numpy()
     assert np.all(np.isfinite(out))
-    ko, vo = np.concatenate([[0], np.cumsum(rk)]), np.concatenate([[0], np.cumsum(rv)])
+    from oracle import gqa as og
+    ko, vo = og.query_offsets(rk, g), og.query_offsets(rv, g)
     row0 = np.concatenate([[0], np.cumsum(ql)])
     got_all, ref_all = [], []
     for b in range(len(kv)):
         if ql[b] == 0:
             continue
-        for h in range(H):
-            ref = oa.latent_attn_prefill(q64[row0[b]:row0[b + 1], ko[h]:ko[h + 1]], Ks[b, h], Vs[b, h], scale, True)
-            got = out[row0[b]:row0[b + 1], vo[h]:vo[h + 1]]
-            assert_close(got, ref, f"b={b} h={h}", max_abs_tol=3e-2)     # values reach +-6
+        for hq in range(H * g):
+            h = hq // g
+            ref = oa.latent_attn_prefill(q64[row0[b]:row0[b + 1], ko[hq]:ko[hq + 1]], Ks[b, h], Vs[b, h], scale, True)
+            got = out[row0[b]:row0[b + 1], vo[hq]:vo[hq + 1]]
+            assert_close(got, ref, f"b={b} hq={hq}", max_abs_tol=3e-2)     # values reach +-6
             got_all.append(got.ravel()), ref_all.append(ref.ravel())
     ma, rl = assert_close(np.concatenate(got_all), np.concatenate(ref_all), "all", max_abs_tol=3e-2)
     say(f"  tasks={plan.export()['n_items']} max_abs={ma:.2e} rel_l2={rl:.2e}")
