@@ -318,6 +318,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
   DecTile td = hd->first;
   constexpr int BASE = Elem<T>::EL == 16 ? 0 : (Elem<T>::EL == 8 ? 1 : 2);  // smallest lane class (log2 lanes per row) of this element type
   for (int i = 0;;) {
+    // the record of the next tile is requested before this one is streamed, so that a tile boundary does not
+    // wait for it (the last iteration re-reads the current record: always a valid address)
+    const DecTile next = wtiles[begin + min(i + 1, count - 1)];
     td.len = dec_tile_len(td, planned_len, seq_len);
     // query head group_j of the tile's group (0 for multi-head plans): its q', its o', its partial slot
     td.q_elem += group_j * (td.rk_rv & 0xffff), td.o_elem += group_j * (td.rk_rv >> 16);
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void decode_tiles_kernel(
     }
 #undef FDC_CASE
     if (++i >= count) break;
-    td = wtiles[begin + i];
+    td = next;
   }
 }
 

@@ -344,6 +344,7 @@ __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
   if (count == 0) return;
   DecTile td = hd->first;
   for (int i = 0;;) {
+    const DecTile next = wtiles[begin + min(i + 1, count - 1)];   // requested ahead of the tile boundary
     td.len = dec_tile_len(td, planned_len, seq_len);
     const int rmax = max(td.rk_rv & 0xffff, td.rk_rv >> 16);
     switch ((rmax + 31) / 32) {
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kGqaWaves * 64) void decode_gqa_tiles_kernel(
       default: break;
     }
     if (++i >= count) break;
-    td = wtiles[begin + i];
+    td = next;
   }
 }
 
