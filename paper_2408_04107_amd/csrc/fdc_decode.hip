@@ -27,13 +27,17 @@ namespace fdc {
 // Wave-wide 16-byte loads of the wider operand per block: 8 KiB per wave in flight and side (4 to 16
 // measured within 2 % of each other).
 constexpr int kDecodeLoads = 8;
+// The code caches take half as many: sixteen elements per load keep twice the widened values live, and with
+// eight loads the E4M3 instance needs 152 registers (three wavefronts per SIMD, 76 us for layer 0 of the
+// adaptive-rank config); with four it fits four wavefronts (112 registers, 69 us). 2 and 6 are slower again.
+constexpr int kDecodeLoadsCodes = 4;
 constexpr int kTokLanes = 64 * kDecodeLoads;
 constexpr int kWavesPerBlock = kWorkersPerGroup;
 constexpr int kLdsFloatsPerWave = kTokLanes > 256 ? kTokLanes : 256;  // a block of one-lane rows (E4M3, rank 16) has kTokLanes tokens
 
 // Tokens per block: kDecodeLoads loads of the wider operand, at least one load of the narrower.
-constexpr int block_tokens(int lk, int lv) {
-  int t = kTokLanes / (lk > lv ? lk : lv);
+constexpr int block_tokens(int lk, int lv, int loads = kDecodeLoads) {
+  int t = 64 * loads / (lk > lv ? lk : lv);
   const int need = 64 / (lk < lv ? lk : lv);
   return t > need ? t : need;
 }
@@ -87,7 +91,7 @@ struct Elem;
 // that the narrowest row, sixteen codes, is still one lane's load).
 template <>
 struct Elem<uint16_t> {  // bf16 bits
-  static constexpr int EL = 8, BITS = 16;
+  static constexpr int EL = 8, BITS = 16, LOADS = kDecodeLoads;
   typedef u32x4 Reg;
   __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
@@ -101,7 +105,7 @@ struct Elem<uint16_t> {  // bf16 bits
 };
 template <>
 struct Elem<uint8_t> {  // OCP E4M3 codes: sixteen elements per 16-byte load, decoded in pairs (v_cvt_pk_f32_fp8)
-  static constexpr int EL = 16, BITS = 8;
+  static constexpr int EL = 16, BITS = 8, LOADS = kDecodeLoadsCodes;
   typedef u32x4 Reg;
   __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
@@ -117,7 +121,7 @@ struct Elem<uint8_t> {  // OCP E4M3 codes: sixteen elements per 16-byte load, de
 };
 template <>
 struct Elem<fp4_t> {  // OCP E2M1 codes: sixteen elements per 8-byte load, decoded a byte (two codes) at a time
-  static constexpr int EL = 16, BITS = 4;
+  static constexpr int EL = 16, BITS = 4, LOADS = kDecodeLoadsCodes;
   typedef u32x2 Reg;
   __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
     return __builtin_amdgcn_raw_buffer_load_b64(rsrc, off, 0, kStreamPolicy);
@@ -136,7 +140,7 @@ struct Elem<fp4_t> {  // OCP E2M1 codes: sixteen elements per 8-byte load, decod
 };
 template <>
 struct Elem<float> {
-  static constexpr int EL = 4, BITS = 32;
+  static constexpr int EL = 4, BITS = 32, LOADS = kDecodeLoads;
   typedef u32x4 Reg;
   __device__ static __forceinline__ Reg load(__amdgpu_buffer_rsrc_t rsrc, int off) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, off, 0, kStreamPolicy);
@@ -155,7 +159,7 @@ __device__ __forceinline__ void decode_tile(const DecTile& td, const float* __re
                                             float* __restrict__ o_lat, float* __restrict__ partials, float* lds,
                                             const int lane) {
   constexpr int EL = Elem<T>::EL;
-  constexpr int TB = block_tokens(LK, LV);                              // tokens per block
+  constexpr int TB = block_tokens(LK, LV, Elem<T>::LOADS);              // tokens per block
   constexpr int RK_ROWS = 64 / LK, RV_ROWS = 64 / LV;                    // rows per wave-wide load
   constexpr int NK = TB / RK_ROWS, NV = TB / RV_ROWS;                    // loads per lane per block
   constexpr int NS = (TB + 63) / 64;                                     // scores per lane per block
