@@ -98,8 +98,7 @@ def run_decode_workload(fdc, gen, wl, steps, warmup, args):
     kc, vc, A_cat_t, Bk, Mt, plans, wss = [], [], [], [], [], [], []
     pp = fdc.fdc_plan_params_default()
     pp.n_workers, pp.min_split = W, wl.min_split
-    if args.granule:
-        pp.granule = args.granule
+    pp.granule = args.granule or wl.granule
     t_plan = 0.0
     for l in range(L):
         k = torch.empty(int(t["k_bytes"][l]) // 2, dtype=bf, device=dev)
@@ -819,7 +818,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "layers": wl.n_layers, "heads": wl.n_heads, "d_head": wl.d_head,
                    "batch": wl.batch, "context": wl.context, "ranks": "adaptive 16..128, P(r)~1/r"
-                   if wl.rank_seed is not None else "uniform 64", "kv_dtype": "bf16", "accumulate": "fp32"},
+                   if wl.rank_seed is not None else "uniform 64", "kv_dtype": "bf16", "accumulate": "fp32",
+                   "planner_granule": args.granule or wl.granule},
         "pct_of_hbm_peak": 100.0 * res["value"] / HBM_PEAK_GBPS,
         "roofline": res["roofline"], "decode_attn": res["decode_attn"],
         "decode_other_calls_layer0": res["decode_other_calls_layer0"],

@@ -158,7 +158,7 @@ def test_decode_config3_layer_sampled_units():
     g = gen.make_rng(42)
     units = {(int(b), int(h)) for b, h in zip(g.integers(0, wl.batch, 96), g.integers(0, wl.n_heads, 96))}
     units |= {(0, int(np.argmax(r))), (wl.batch - 1, int(np.argmin(r)))}
-    ma, rl, n, _ = run_decode(r, r, [wl.context] * wl.batch, W, device_fill=True, seed=1,
+    ma, rl, n, _ = run_decode(r, r, [wl.context] * wl.batch, W, device_fill=True, seed=1, granule=wl.granule,
                               check_units=sorted(units))
     say(f"  tiles={n} checked_units={len(units)} max_abs={ma:.2e} rel_l2={rl:.2e}")
 

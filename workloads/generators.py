@@ -138,6 +138,7 @@ class Workload:
     rank_seed: Optional[int] = None       # adaptive draw; None = explicit ranks
     explicit_ranks: Optional[List[int]] = None
     min_split: int = 1
+    granule: int = 64     # tokens per cut of the decode planner (a launch parameter, not part of the method's arithmetic)
     note: str = ""
     _ranks: Optional[np.ndarray] = field(default=None, repr=False)
 
@@ -168,7 +169,7 @@ CONFIGS = {
     "c3_adaptive_decode": Workload(
         name="c3_adaptive_decode", n_layers=32, n_heads=32, d_model=4096, d_head=128,
         batch=16, context=8192, kv_dtype="bf16", decay=32.0, seed=0, phase="decode",
-        rank_seed=0),
+        rank_seed=0, granule=128),
     # Long-context decode, one sequence, split-K over >= 256 chunks per head.
     "c4_long_decode": Workload(
         name="c4_long_decode", n_layers=1, n_heads=32, d_model=4096, d_head=128,
