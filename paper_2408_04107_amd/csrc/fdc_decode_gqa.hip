@@ -55,17 +55,19 @@ __device__ __forceinline__ uint32_t gq_pack(float lo, float hi) {  // v_cvt_pk_b
   r.v = __builtin_convertvector(gq_f32x2{lo, hi}, gq_bf16x2);
   return r.u;
 }
-// Sixteen E4M3 codes (16 bytes) -> sixteen bf16 in the same order (v_cvt_pk_f32_fp8, then v_cvt_pk_bf16_f32;
-// bf16 holds every code value exactly).
+// Sixteen E4M3 codes (16 bytes) -> sixteen bf16 in the same order: v_cvt_scalef32_pk_bf16_fp8 with scale 1
+// turns two codes into two packed bf16 in one instruction (bf16 holds every code value exactly).
+__device__ __forceinline__ uint32_t gq_codes_to_bf16(uint32_t word, bool upper) {
+  union { gq_bf16x2 v; uint32_t u; } r;
+  r.v = upper ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, true)
+              : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(word, 1.0f, false);
+  return r.u;
+}
 __device__ __forceinline__ void gq_widen16(const gq_u32x4& c, gq_u32x4& lo, gq_u32x4& hi) {
-#pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(c[w], false);  // bytes 0, 1 of the word
-    const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(c[w], true);   // bytes 2, 3
-    const uint32_t p0 = gq_pack(a[0], a[1]), p1 = gq_pack(b[0], b[1]);
-    if (w < 2) lo[2 * w] = p0, lo[2 * w + 1] = p1;
-    else hi[2 * (w - 2)] = p0, hi[2 * (w - 2) + 1] = p1;
-  }
+  lo = gq_u32x4{gq_codes_to_bf16(c[0], false), gq_codes_to_bf16(c[0], true), gq_codes_to_bf16(c[1], false),
+                gq_codes_to_bf16(c[1], true)};
+  hi = gq_u32x4{gq_codes_to_bf16(c[2], false), gq_codes_to_bf16(c[2], true), gq_codes_to_bf16(c[3], false),
+                gq_codes_to_bf16(c[3], true)};
 }
 // reductions over the four lanes l, l ^ 16, l ^ 32, l ^ 48 that share a query
 __device__ __forceinline__ float gq_row_max(float v) {

@@ -276,32 +276,28 @@ __device__ __forceinline__ void prefill_task(const PreTask& t, const uint16_t* _
     auto put = [&](uint16_t* dst, const u32x4& chunk) {   // one 16-byte chunk of the cache -> bf16 in LDS
       if constexpr (BITS == 16) {
         *reinterpret_cast<u32x4*>(dst) = chunk;
-      } else if constexpr (kFp4) {   // sixteen codes in two words -> sixteen bf16 (which holds every E2M1 value exactly)
-        u32x4 lo, hi;
+      } else if constexpr (kFp4) {   // sixteen codes in two words -> sixteen bf16 (which holds every E2M1 value exactly),
+        u32x4 lo, hi;                // two codes per instruction (v_cvt_scalef32_pk_bf16_fp4, scale 1; the byte select is an immediate)
 #pragma unroll
-        for (int w = 0; w < 2; ++w)
-#pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            f32x2 p;
-            switch (b) {   // the byte select is an immediate
-              case 0: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 0); break;
-              case 1: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 1); break;
-              case 2: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 2); break;
-              default: p = __builtin_amdgcn_cvt_scalef32_pk_f32_fp4(chunk[w], 1.0f, 3); break;
-            }
-            (w == 0 ? lo : hi)[b] = pack_bf16(p[0], p[1]);
-          }
+        for (int w = 0; w < 2; ++w) {
+          union { bf16x2 v; uint32_t u; } b0, b1, b2, b3;
+          b0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(chunk[w], 1.0f, 0);
+          b1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(chunk[w], 1.0f, 1);
+          b2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(chunk[w], 1.0f, 2);
+          b3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(chunk[w], 1.0f, 3);
+          (w == 0 ? lo : hi) = u32x4{b0.u, b1.u, b2.u, b3.u};
+        }
         *reinterpret_cast<u32x4*>(dst) = lo;
         *reinterpret_cast<u32x4*>(dst + 8) = hi;
-      } else {
+      } else {   // sixteen E4M3 codes -> sixteen bf16, two per instruction (v_cvt_scalef32_pk_bf16_fp8, scale 1)
         u32x4 lo, hi;
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          const auto a = __builtin_amdgcn_cvt_pk_f32_fp8(chunk[w], false);  // bytes 0, 1 of the word
-          const auto b = __builtin_amdgcn_cvt_pk_f32_fp8(chunk[w], true);   // bytes 2, 3
-          const uint32_t p0 = pack_bf16(a[0], a[1]), p1 = pack_bf16(b[0], b[1]);
-          if (w < 2) lo[2 * w] = p0, lo[2 * w + 1] = p1;
-          else hi[2 * (w - 2)] = p0, hi[2 * (w - 2) + 1] = p1;
+          union { bf16x2 v; uint32_t u; } a, b;
+          a.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(chunk[w], 1.0f, false);  // bytes 0, 1 of the word
+          b.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(chunk[w], 1.0f, true);   // bytes 2, 3
+          if (w < 2) lo[2 * w] = a.u, lo[2 * w + 1] = b.u;
+          else hi[2 * (w - 2)] = a.u, hi[2 * (w - 2) + 1] = b.u;
         }
         *reinterpret_cast<u32x4*>(dst) = lo;
         *reinterpret_cast<u32x4*>(dst + 8) = hi;

@@ -468,3 +468,25 @@ def test_decode_on_e2m1_codes_at_config3_size_sampled_units():
         ref = oa.latent_attn_decode(q64[b, off[h]:off[h + 1]], K, V, scale)
         assert_close(out[b, off[h]:off[h + 1]], ref, f"b={b} h={h} r={r[h]}")
     say(f"  tiles={plan.export()['n_items']} units checked={len(units)}")
+
+
+def test_prefill_reads_every_e2m1_code_exactly():
+    """The prefill staging widens E2M1 codes to bf16 with the hardware's packed conversion. Row i is peaked on
+    token i (weights exactly one-hot in bf16), so output row i is V' row i decoded: all sixteen codes, in every
+    nibble position of a word, must come back as the format's values, bit for bit."""
+    n, r = 16, 16
+    rows = (np.arange(n)[:, None] + np.arange(r)[None, :]) % 16          # every code in every column
+    lay = fdc.Layout(1, 1, 256, 128, [[r]], [[r]], 1, n, fdc.FDC_FP4)
+    key_vals = np.zeros((n, r))
+    key_vals[np.arange(n), np.arange(n)] = 6.0                            # K'[t] = 6 e_t (the largest code)
+    kc = torch.from_numpy(fp4.pack_rows(fp4.quantise_latent(key_vals)).ravel()).cuda()
+    vc = torch.from_numpy(fp4.pack_rows(rows.astype(np.uint8)).ravel()).cuda()
+    q_lat = (torch.eye(n, r) * 512.0).to(BF).cuda()                       # score 3072 * scale on the diagonal
+    o_lat = torch.full((n, r), float("nan"), dtype=BF, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.br_base, pp.br_cap = 2, 64, 64
+    plan = fdc.fdc_plan_prefill(lay, 0, [n], [n], pp)
+    ws = workspace_for(plan)
+    fdc.fdc_latent_attn_prefill(lay, plan, q_lat, kc, vc, 1 / math.sqrt(128), True, o_lat, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(o_lat.to(torch.float64).cpu().numpy(), fp4.e2m1_decode(rows))

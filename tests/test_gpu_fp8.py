@@ -361,3 +361,62 @@ def test_decode_on_e4m3_codes_at_config3_size_sampled_units():
         ref = oa.latent_attn_decode(q64[b, off[h]:off[h + 1]], K, V, scale)
         assert_close(out[b, off[h]:off[h + 1]] / 100.0, ref / 100.0, f"b={b} h={h} r={r[h]}")
     say(f"  tiles={plan.export()['n_items']} units checked={len(units)}")
+
+
+def _all_codes_rows():
+    """[16, 16] uint8: every E4M3 code once (the two NaN codes replaced by zero), row t = codes 16 t .. 16 t + 15."""
+    c = np.arange(256, dtype=np.uint8).reshape(16, 16).copy()
+    c[c == 0x7F] = 0
+    c[c == 0xFF] = 0
+    return c
+
+
+@pytest.mark.parametrize("g", [4, 16])
+def test_grouped_decode_reads_every_e4m3_code_exactly(g):
+    """The grouped kernel widens codes to bf16 operands with the hardware's packed conversion. Each query is peaked
+    on one token (weights exactly one-hot in bf16), so an output row is that token's V' row decoded: all 254
+    finite codes must come back as the format's values, bit for bit."""
+    rows = _all_codes_rows()
+    n, r = 16, 16
+    B = n // g if g <= n else 1
+    lay = fdc.Layout(1, 1, 256, 128, [[r]], [[r]], B, n, fdc.FDC_FP8, q_per_kv=g)
+    key_codes = np.zeros((n, r), np.uint8)
+    key_codes[np.arange(n), np.arange(n)] = fp8.quantise_latent(np.array([[64.0]]))[0, 0]      # K'[t] = 64 e_t
+    kc = torch.from_numpy(np.tile(key_codes.ravel(), B)).cuda()
+    vc = torch.from_numpy(np.tile(rows.ravel(), B)).cuda()
+    q = np.zeros((B, g, r), np.float32)
+    for b in range(B):
+        for j in range(g):
+            q[b, j, (b * g + j) % n] = 64.0                  # query (b, j) selects token b g + j: score 4096 * scale
+    q_lat = torch.from_numpy(q.reshape(B, g * r)).cuda()
+    o_lat = torch.full((B, g * r), float("nan"), dtype=torch.float32, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers = 3
+    plan = fdc.fdc_plan_decode(lay, 0, [n] * B, pp)
+    ws = workspace_for(plan)
+    fdc.fdc_latent_attn_decode(lay, plan, q_lat, kc, vc, 1 / math.sqrt(128), o_lat, ws)
+    torch.cuda.synchronize()
+    out = o_lat.cpu().numpy().reshape(B, g, r)
+    want = fp8.e4m3_decode(rows)
+    for b in range(B):
+        for j in range(g):
+            assert np.array_equal(out[b, j].astype(np.float64), want[(b * g + j) % n]), (b, j)
+
+
+def test_prefill_reads_every_e4m3_code_exactly():
+    """Same for the prefill kernel's staging (codes widened to bf16 on the way into LDS): row i is peaked on token i."""
+    rows = _all_codes_rows()
+    n, r = 16, 16
+    lay = fdc.Layout(1, 1, 256, 128, [[r]], [[r]], 1, n, fdc.FDC_FP8)
+    key_codes = np.zeros((n, r), np.uint8)
+    key_codes[np.arange(n), np.arange(n)] = fp8.quantise_latent(np.array([[64.0]]))[0, 0]
+    kc, vc = torch.from_numpy(key_codes.ravel()).cuda(), torch.from_numpy(rows.ravel().copy()).cuda()
+    q_lat = (torch.eye(n, r) * 64.0).to(BF).cuda()
+    o_lat = torch.full((n, r), float("nan"), dtype=BF, device="cuda:0")
+    pp = fdc.fdc_plan_params_default()
+    pp.n_workers, pp.br_base, pp.br_cap = 2, 64, 64
+    plan = fdc.fdc_plan_prefill(lay, 0, [n], [n], pp)
+    ws = workspace_for(plan)
+    fdc.fdc_latent_attn_prefill(lay, plan, q_lat, kc, vc, 1 / math.sqrt(128), True, o_lat, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(o_lat.to(torch.float64).cpu().numpy(), fp8.e4m3_decode(rows))
