@@ -648,7 +648,7 @@ def run_device_planner(fdc, gen, wl, iters=5):
     L, H, B, S = wl.n_layers, wl.n_heads, wl.batch, wl.context
     lay = fdc.Layout(L, H, wl.d_model, wl.d_head, ranks, ranks, B, S, fdc.FDC_BF16)
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(0), wl.min_split
+    pp.n_workers, pp.min_split, pp.granule = fdc.fdc_suggest_workers(0), wl.min_split, wl.granule
     plans, wss = [], []
     for l in range(L):
         plan = fdc.fdc_plan_decode_device(lay, l, B, 0, pp)
@@ -687,8 +687,8 @@ def run_serving_loop(fdc, gen, wl, steps=64):
     device memory and grow by one token per step, every layer appends its K'/V' rows at the sequence's end
     (fdc_project_and_absorb_query), attends at the actual lengths on a plan made for the lengths rounded up
     to the granule (fdc_latent_attn_decode_at), and all layers are re-planned on the GPU
-    (fdc_plan_decode_run) whenever a sequence enters a new granule: once in the 64 steps timed here, which
-    start at context - 64 and end at the workload's context."""
+    (fdc_plan_decode_run) whenever a sequence enters a new granule: once in the steps timed here (one granule's
+    worth), which end at the workload's context."""
     import torch
     dev = "cuda:0"
     ranks = wl.ranks()
@@ -698,7 +698,7 @@ def run_serving_loop(fdc, gen, wl, steps=64):
     gt = torch.Generator(device=dev).manual_seed(wl.seed + 1)
     bf = torch.bfloat16
     pp = fdc.fdc_plan_params_default()
-    pp.n_workers, pp.min_split = fdc.fdc_suggest_workers(0), wl.min_split
+    pp.n_workers, pp.min_split, pp.granule = fdc.fdc_suggest_workers(0), wl.min_split, wl.granule
     G = pp.granule
     kc, vc, A_cat_t, Bk, Mt, plans, wss = [], [], [], [], [], [], []
     for l in range(L):
@@ -852,7 +852,7 @@ def main():
     if not args.no_device_planner:
         side("device_planner", lambda: run_device_planner(fdc, gen, wl))
     if not args.no_serving_loop:
-        side("serving_loop", lambda: run_serving_loop(fdc, gen, wl))
+        side("serving_loop", lambda: run_serving_loop(fdc, gen, wl, steps=wl.granule))
     print(json.dumps(line))
 
 
