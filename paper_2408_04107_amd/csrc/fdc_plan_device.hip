@@ -387,6 +387,65 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(DevPlanLaunch
   __syncthreads();
   block_exclusive_scan(chunk_base, n_chunks, red32);   // tiles are numbered by (unit, first token) = chunk order
 
+  // ---- launch slots -----------------------------------------------------------------------------------
+  // As in the host planner: the tile kernel runs kWorkersPerGroup workers per workgroup, workgroup i runs on XCD
+  // i % kXcds, and the even XCDs stream faster, so the heavier half of the workers takes their slots. Here the
+  // half is found without a sort: the median load by bisection on its value (32 counts over the workgroup), then
+  // every worker's rank among the heavier ones, among those at the median and among the rest (one scan over
+  // per-thread counts). Inside a half workers keep id order (the host orders them by load: headers are not part
+  // of the exported tables). loads[w] becomes the slot of worker w.
+  const int per_w = (W + kPlanThreads - 1) / kPlanThreads;
+  const bool slotted = c.g == 1 && !overflow && W % (2 * kXcds * kWorkersPerGroup) == 0 && per_w <= 4;
+  if (slotted) {
+    __shared__ uint32_t sh_cnt;
+    const int w_lo = min(W, tid * per_w), w_hi = min(W, w_lo + per_w);
+    uint32_t my[4] = {0, 0, 0, 0};
+    for (int i = w_lo; i < w_hi; ++i) my[i - w_lo] = loads[i];
+    auto count_above = [&](uint32_t thr, bool or_equal) -> uint32_t {   // workers with load > thr (>= thr)
+      if (tid == 0) sh_cnt = 0;
+      __syncthreads();
+      uint32_t cnt = 0;
+      for (int i = w_lo; i < w_hi; ++i) cnt += (my[i - w_lo] > thr || (or_equal && my[i - w_lo] == thr)) ? 1u : 0u;
+      if (cnt) atomicAdd(&sh_cnt, cnt);
+      __syncthreads();
+      const uint32_t total = sh_cnt;
+      __syncthreads();
+      return total;
+    };
+    uint32_t lo = 0, hi = 0xffffffffu;   // the smallest T with at most W / 2 loads above it
+    for (int it = 0; it < 32; ++it) {
+      const uint32_t mid = lo + (hi - lo) / 2;
+      if (count_above(mid, false) > (uint32_t)(W / 2)) lo = mid + 1;
+      else hi = mid;
+    }
+    const uint32_t T = lo;
+    const uint32_t n_above = count_above(T, false), n_extra = (uint32_t)(W / 2) - n_above;   // at T: the first n_extra join them
+    uint32_t mine = 0;   // this thread's workers above T (low half), at T (high half)
+    for (int i = w_lo; i < w_hi; ++i) mine += my[i - w_lo] > T ? 1u : (my[i - w_lo] == T ? 0x10000u : 0u);
+    red32[tid] = mine;
+    __syncthreads();
+    for (int o = 1; o < kPlanThreads; o <<= 1) {   // inclusive scan of the packed counts (both stay below 2^16)
+      const uint32_t add = tid >= o ? red32[tid - o] : 0;
+      __syncthreads();
+      red32[tid] += add;
+      __syncthreads();
+    }
+    uint32_t run = tid > 0 ? red32[tid - 1] : 0;
+    __syncthreads();   // red32 is free again
+    for (int i = w_lo; i < w_hi; ++i) {
+      const uint32_t above = run & 0xffffu, at = run >> 16, v = my[i - w_lo];
+      int half, idx;   // position inside the heavier (0) or the lighter (1) half
+      if (v > T) half = 0, idx = (int)above;
+      else if (v == T && at < n_extra) half = 0, idx = (int)(n_above + at);
+      else half = 1, idx = i - (int)(above + min(at, n_extra));
+      const int grp = idx / kWorkersPerGroup;   // the half's workgroups in launch order
+      const int wg = kXcds * (grp / (kXcds / 2)) + 2 * (grp % (kXcds / 2)) + half;
+      loads[i] = (uint32_t)(wg * kWorkersPerGroup + idx % kWorkersPerGroup);
+      run += v > T ? 1u : (v == T ? 0x10000u : 0u);
+    }
+    __syncthreads();
+  }
+
   for (int k = tid; k < n; k += kPlanThreads) {
     const int4 pa = pieces[2 * (size_t)k], pb = pieces[2 * (size_t)k + 1];
     const int ci = pa.x, b = pa.y & 0xffff, h = pa.y >> 16, lo = pa.z, hi = pa.w;
@@ -419,17 +478,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_decode_kernel(DevPlanLaunch
     t.slot_stride = n_u;
     t.b_end = b | (hi == len[b] ? (int32_t)0x80000000 : 0);
     wtiles[pos] = t;
-    if (rank == 0) heads[w].first = t;
+    if (rank == 0) heads[slotted ? (int)loads[w] : w].first = t;
     ex_b[item] = b, ex_h[item] = h, ex_lo[item] = lo, ex_hi[item] = hi;
     ex_witems[pos] = item;
   }
   for (int w = tid; w < W; w += kPlanThreads) {
     const int begin = (int)wcount[w], count = (int)wcount[w + 1] - begin;
-    heads[w].begin = begin, heads[w].count = count, heads[w].pad[0] = 0, heads[w].pad[1] = 0;
+    DecWorker& hd = heads[slotted ? (int)loads[w] : w];
+    hd.begin = begin, hd.count = count, hd.pad[0] = 0, hd.pad[1] = 0;
     if (count == 0) {
       DecTile z;
       memset(&z, 0, sizeof(z));
-      heads[w].first = z;
+      hd.first = z;
     }
     ex_wptr[w] = begin;
   }
