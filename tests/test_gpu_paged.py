@@ -102,6 +102,11 @@ def test_paged_decode(g, P, granule, W, min_split):
             ref = x64[row0 + t] @ A64[koff[h]:koff[h + 1]].T
             got = np.array([kbuf[ol.paged_element_index(rk, P, bt[5], h, t, i)] for i in range(rk[h])])
             assert_close(got, ref, f"projected K' row t={t} h={h}")
+    # the entry point on the library's own workspace takes paged plans as well: same tables, same bits
+    o_static = torch.full_like(o_lat, float("nan"))
+    fdc.fdc_latent_attn_decode_static(lay, plan, q_lat, cache.k, cache.v, scale, o_static)
+    torch.cuda.synchronize()
+    assert torch.equal(o_static, o_lat)
     say(f"  tiles={plan.export()['n_items']} max_abs={ma:.2e} rel_l2={rl:.2e}")
 
 
